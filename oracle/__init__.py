@@ -1,0 +1,196 @@
+"""CPU oracle for the correction-based fault-tolerant reduce / allreduce.
+
+TEST INFRASTRUCTURE ONLY.  This package wraps ``ftred_oracle.c`` (a literal,
+slow simulation with per-process message queues) and ``definition.py`` (the
+plain definition of a valid result).  Only the tests, the smoke check and the
+benchmark's CPU-baseline leg may import it; the GPU library never does, and the
+two share no code.
+
+numpy in, numpy out; every array is indexed by PHYSICAL rank.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+from .definition import survivor_reduce, valid_results, is_valid_result  # noqa: F401
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "ftred_oracle.c")
+_LIB = os.path.join(_HERE, "libftred_oracle.so")
+
+NO_RANK = 0xFFFFFFFF
+I64, U32, F64 = 0, 1, 2
+SUM, BOR = 0, 1
+ST_OK, ST_ROOT_FAILED, ST_NO_CLEAN_SUBTREE, ST_BAD_FAILURE_SET, ST_INCONSISTENT, ST_NO_LIVE_ROOT = range(6)
+
+_NP_DTYPE = {I64: np.int64, U32: np.uint32, F64: np.float64}
+
+
+def build(force: bool = False) -> str:
+    """Compile the C oracle with gcc (a second or two).  Returns the library path."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp", "-Wall", "-Wextra",
+               "-ffp-contract=off", _SRC, "-o", _LIB]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        _lib = ctypes.CDLL(_LIB)
+    return _lib
+
+
+def _p(a):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _fail_arrays(fail_rank, fail_round):
+    fr = np.ascontiguousarray(np.asarray(fail_rank, dtype=np.uint32).reshape(-1))
+    fo = np.ascontiguousarray(np.asarray(fail_round, dtype=np.uint32).reshape(-1))
+    assert fr.shape == fo.shape
+    if fr.size == 0:            # keep the pointers valid
+        fr = np.full(1, NO_RANK, dtype=np.uint32)
+        fo = np.zeros(1, dtype=np.uint32)
+        return fr, fo, 0
+    return fr, fo, fr.size
+
+
+def structure(P: int, f: int, root: int = 0) -> dict:
+    """Tree and group structure (see ``oracle_structure`` in the C file)."""
+    lib = _load()
+    out = dict(
+        parent=np.zeros(P, np.int64), subtree=np.zeros(P, np.uint32), group=np.zeros(P, np.int64),
+        gpos=np.zeros(P, np.uint32), gsize=np.zeros(P, np.uint32), height=np.zeros(P, np.uint32),
+        depth=np.zeros(P, np.uint32), send_round=np.zeros(P, np.uint32))
+    D = ctypes.c_uint32(0)
+    rc = lib.oracle_structure(ctypes.c_uint32(P), ctypes.c_uint32(f), ctypes.c_uint32(root),
+                              _p(out["parent"]), _p(out["subtree"]), _p(out["group"]), _p(out["gpos"]),
+                              _p(out["gsize"]), _p(out["height"]), _p(out["depth"]),
+                              _p(out["send_round"]), ctypes.byref(D))
+    if rc != 0:
+        raise ValueError("oracle_structure: invalid arguments")
+    out["D"] = int(D.value)
+    return out
+
+
+def reduce(P, f, payload, dtype, op, root=0, fail_rank=(), fail_round=(), disable_uc=False, trace=False):
+    """One reduce; payload[P][elems].  Returns a dict (result, status, msgs, rounds, traces)."""
+    lib = _load()
+    npdt = _NP_DTYPE[dtype]
+    x = np.ascontiguousarray(np.asarray(payload, dtype=npdt).reshape(P, -1))
+    elems = x.shape[1]
+    fr, fo, nfail = _fail_arrays(fail_rank, fail_round)
+    result = np.zeros(elems, npdt)
+    status = ctypes.c_uint32(0)
+    rounds = ctypes.c_uint32(0)
+    msgs = np.zeros(2, np.uint64)
+    v = np.zeros((P, elems), npdt) if trace else None
+    sent = np.zeros(P, np.uint8) if trace else None
+    flag = np.zeros(P, np.uint8) if trace else None
+    tmsg = np.zeros((P, elems), npdt) if trace else None
+    rc = lib.oracle_reduce(ctypes.c_uint32(P), ctypes.c_uint32(f), ctypes.c_uint32(elems),
+                           ctypes.c_int(dtype), ctypes.c_int(op), ctypes.c_int(int(disable_uc)),
+                           ctypes.c_uint32(root), _p(x), ctypes.c_uint32(nfail), _p(fr), _p(fo),
+                           _p(result), ctypes.byref(status), _p(msgs), ctypes.byref(rounds),
+                           _p(v), _p(sent), _p(flag), _p(tmsg))
+    if rc != 0:
+        raise ValueError("oracle_reduce: invalid arguments")
+    return dict(result=result, status=int(status.value), msgs=msgs, rounds=int(rounds.value),
+                v_after_uc=v, tree_sent=sent, tree_flag=flag, tree_msg=tmsg)
+
+
+def allreduce(P, f, payload, dtype, op, fail_rank=(), fail_round=(), want_out=True):
+    """One allreduce; payload[P][elems].  Returns a dict."""
+    lib = _load()
+    npdt = _NP_DTYPE[dtype]
+    x = np.ascontiguousarray(np.asarray(payload, dtype=npdt).reshape(P, -1))
+    elems = x.shape[1]
+    fr, fo, nfail = _fail_arrays(fail_rank, fail_round)
+    result = np.zeros(elems, npdt)
+    status = ctypes.c_uint32(0)
+    attempts = ctypes.c_uint32(0)
+    rounds = ctypes.c_uint32(0)
+    msgs = np.zeros(4, np.uint64)
+    has = np.zeros(P, np.uint8)
+    out = np.zeros((P, elems), npdt) if want_out else None
+    rc = lib.oracle_allreduce(ctypes.c_uint32(P), ctypes.c_uint32(f), ctypes.c_uint32(elems),
+                              ctypes.c_int(dtype), ctypes.c_int(op), _p(x),
+                              ctypes.c_uint32(nfail), _p(fr), _p(fo),
+                              _p(result), ctypes.byref(status), ctypes.byref(attempts), _p(msgs),
+                              ctypes.byref(rounds), _p(has), _p(out))
+    if rc != 0:
+        raise ValueError("oracle_allreduce: invalid arguments")
+    return dict(result=result, status=int(status.value), attempts=int(attempts.value), msgs=msgs,
+                rounds=int(rounds.value), has=has, out=out)
+
+
+def _batch_common(P, payload, dtype, S, fail_rank, fail_round):
+    npdt = _NP_DTYPE[dtype]
+    x = np.ascontiguousarray(np.asarray(payload, dtype=npdt))
+    if x.ndim == 2:                     # one payload shared by all scenarios
+        assert x.shape[0] == P
+        stride = 0
+        elems = x.shape[1]
+    else:
+        assert x.shape[0] == S and x.shape[1] == P
+        elems = x.shape[2]
+        stride = P * elems * x.itemsize
+    fr = np.ascontiguousarray(np.asarray(fail_rank, dtype=np.uint32).reshape(S, -1))
+    fo = np.ascontiguousarray(np.asarray(fail_round, dtype=np.uint32).reshape(S, -1))
+    assert fr.shape == fo.shape
+    nfail = fr.shape[1]
+    if nfail == 0:
+        fr = np.full((S, 1), NO_RANK, np.uint32)
+        fo = np.zeros((S, 1), np.uint32)
+        nfail = 1
+    return npdt, x, elems, stride, fr, fo, nfail
+
+
+def reduce_batch(P, f, payload, dtype, op, S, root=None, fail_rank=(), fail_round=(), threads=0):
+    """S independent reduces; payload[S][P][elems] or [P][elems] (shared)."""
+    lib = _load()
+    npdt, x, elems, stride, fr, fo, nfail = _batch_common(P, payload, dtype, S, fail_rank, fail_round)
+    rt = None if root is None else np.ascontiguousarray(np.asarray(root, dtype=np.uint32).reshape(S))
+    result = np.zeros((S, elems), npdt)
+    status = np.zeros(S, np.uint32)
+    msgs = np.zeros((S, 2), np.uint64)
+    used = lib.oracle_reduce_batch(ctypes.c_uint32(P), ctypes.c_uint32(f), ctypes.c_uint32(elems),
+                                   ctypes.c_int(dtype), ctypes.c_int(op), ctypes.c_uint32(S), _p(rt),
+                                   _p(x), ctypes.c_uint64(stride), ctypes.c_uint32(nfail), _p(fr), _p(fo),
+                                   _p(result), _p(status), _p(msgs), ctypes.c_int(threads))
+    if used < 0:
+        raise ValueError("oracle_reduce_batch: invalid arguments")
+    return dict(result=result, status=status, msgs=msgs, threads=used)
+
+
+def allreduce_batch(P, f, payload, dtype, op, S, fail_rank=(), fail_round=(), threads=0,
+                    want_has=True, want_out=False):
+    """S independent allreduces; payload[S][P][elems] or [P][elems] (shared)."""
+    lib = _load()
+    npdt, x, elems, stride, fr, fo, nfail = _batch_common(P, payload, dtype, S, fail_rank, fail_round)
+    result = np.zeros((S, elems), npdt)
+    status = np.zeros(S, np.uint32)
+    attempts = np.zeros(S, np.uint32)
+    rounds = np.zeros(S, np.uint32)
+    msgs = np.zeros((S, 4), np.uint64)
+    has = np.zeros((S, P), np.uint8) if want_has else None
+    out = np.zeros((S, P, elems), npdt) if want_out else None
+    used = lib.oracle_allreduce_batch(ctypes.c_uint32(P), ctypes.c_uint32(f), ctypes.c_uint32(elems),
+                                      ctypes.c_int(dtype), ctypes.c_int(op), ctypes.c_uint32(S),
+                                      _p(x), ctypes.c_uint64(stride), ctypes.c_uint32(nfail), _p(fr), _p(fo),
+                                      _p(result), _p(status), _p(attempts), _p(msgs), _p(rounds),
+                                      _p(has), _p(out), ctypes.c_int(threads))
+    if used < 0:
+        raise ValueError("oracle_allreduce_batch: invalid arguments")
+    return dict(result=result, status=status, attempts=attempts, msgs=msgs, rounds=rounds,
+                has=has, out=out, threads=used)

@@ -1,0 +1,793 @@
+/*
+ * CPU oracle for the correction-based fault-tolerant reduce and allreduce
+ * (Kuettler & Haertig, "Fault-tolerant Reduce and Allreduce operations based on
+ * correction").
+ *
+ * THIS IS TEST INFRASTRUCTURE, NOT THE PRODUCT.  It is a plain, slow, literal
+ * simulation: one object per process, one message queue per process, explicit
+ * adjacency lists, a global round loop.  It exists so that the GPU library can
+ * be checked against something that can be compared with the paper by eye.
+ * It shares no code, header, table or constant with the GPU library.
+ *
+ * What follows the paper directly:
+ *   - root relabelling by swapping the root's number with 0      (section "Reduce")
+ *   - up-correction groups by group number floor((p-1)/(f+1)); the root joins
+ *     the last group iff that group is short          (section "Up-Correction")
+ *   - Algorithm "Up-correction": every member sends its ORIGINAL input to every
+ *     other member and folds what it receives; no failure information is sent
+ *   - Algorithm "reduce, non-roots": up-correction, then receive from all
+ *     children, fold, update failure information, send to parent
+ *   - Algorithm "reduce, root": optional up-correction, then take a child
+ *     message that reports no failure; add the root's value iff the sender's
+ *     subtree does not already contain it
+ *   - failure information: the single "failed" bit, set in the tree phase when
+ *     a child's value is missing, untouched in up-correction
+ *                                             (section "Failure information")
+ *   - I(f)-tree: the root has f+1 children whose subtrees differ in size by at
+ *     most one; process a is in subtree k iff (a-1) mod (f+1) == k-1
+ *                                  (Definition and proof of the first theorem)
+ *   - Algorithm "Allreduce": r <- 0; repeat { reduce to r; broadcast from r;
+ *     ok <- broadcast succeeded; r <- successor(r) }
+ *
+ * Readings taken where the paper is silent (each is also listed in the design
+ * notes of the repository):
+ *   R1 round model: global rounds 1,2,...; a message sent in round r reaches an
+ *      alive receiver at the end of round r.  Every message has the round it has
+ *      in the failure-free run; a message that is absent at the end of that
+ *      round means "sender failed" (stands for time-out + failure monitor).
+ *      fail_round 0 = failed before the operation; fail_round r >= 1 = the
+ *      process does everything of rounds < r and nothing from round r on.
+ *   R2 up-correction order: in round t (1..f) the member with index i of a group
+ *      of size g sends to index (i+t) mod g iff t <= g-1.
+ *   R3 tree inside a root subtree: filled breadth-first, two children per node.
+ *   R4 a tree process sends in round f + 1 + height(process).
+ *   R5 root choice among child messages: lowest child number whose message is
+ *      present and reports no failure.
+ *   R6 allreduce roots: physical ranks 0,1,...,f in this order; they may fail
+ *      only before the operation.
+ *   R7 broadcast (defined in a companion paper, not available): tree-down over
+ *      the same tree (D rounds), then f correction rounds in which every holder
+ *      sends the value to group mate (i+t) mod g.
+ *
+ * parity pins: every function of this file is pinned by tests (worked example
+ * of the paper, brute force over all failure subsets against the survivor
+ * reduction, one-hot multiplicities, message-count closed forms).  Not pinned by
+ * the paper (they are this repository's definitions): the number of rounds, the
+ * choice among valid results under in-operation failures, and the broadcast's
+ * message counts.
+ */
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+#define ORACLE_NO_RANK 0xFFFFFFFFu
+
+enum { OR_I64 = 0, OR_U32 = 1, OR_F64 = 2 };
+enum { OR_SUM = 0, OR_BOR = 1 };
+enum {
+    OR_ST_OK = 0,
+    OR_ST_ROOT_FAILED = 1,
+    OR_ST_NO_CLEAN_SUBTREE = 2,
+    OR_ST_BAD_FAILURE_SET = 3,
+    OR_ST_INCONSISTENT = 4,
+    OR_ST_NO_LIVE_ROOT = 5
+};
+enum { MSG_UC = 0, MSG_TREE = 1, MSG_BCAST = 2, MSG_BCORR = 3 };
+
+/* ------------------------------------------------------------------ */
+/* reduction function                                                   */
+
+static size_t elem_size(int dtype)
+{
+    return dtype == OR_U32 ? 4 : 8;
+}
+
+/* dst <- reduce_function(dst, src), element by element */
+static void combine(int dtype, int op, uint32_t elems, void *dst, const void *src)
+{
+    uint32_t e;
+    if (dtype == OR_F64) {
+        double *d = (double *)dst;
+        const double *s = (const double *)src;
+        for (e = 0; e < elems; ++e) d[e] = d[e] + s[e];
+    } else if (dtype == OR_I64) {
+        /* wrapping sum: done on the unsigned representation */
+        uint64_t *d = (uint64_t *)dst;
+        const uint64_t *s = (const uint64_t *)src;
+        for (e = 0; e < elems; ++e) d[e] = (op == OR_SUM) ? d[e] + s[e] : (d[e] | s[e]);
+    } else {
+        uint32_t *d = (uint32_t *)dst;
+        const uint32_t *s = (const uint32_t *)src;
+        for (e = 0; e < elems; ++e) d[e] = (op == OR_SUM) ? d[e] + s[e] : (d[e] | s[e]);
+    }
+}
+
+/* ------------------------------------------------------------------ */
+/* structure: built constructively, with explicit lists                 */
+
+typedef struct {
+    uint32_t P, f, root;
+    uint32_t *phys_of_virt;   /* [P] */
+    uint32_t *virt_of_phys;   /* [P] */
+    int64_t *parent;          /* [P] virtual parent, -1 for the root */
+    uint32_t *nkids;          /* [P] */
+    uint32_t *kids;           /* [P][2] for non-roots */
+    uint32_t *root_kids;      /* [f+1] */
+    uint32_t *subtree;        /* [P] 0 for the root, else 1..f+1 */
+    int64_t *group;           /* [P] group id or -1 */
+    uint32_t *gpos;           /* [P] index in the group's member list */
+    uint32_t ngroups;
+    uint32_t *gsize;          /* [ngroups] */
+    uint32_t *gmembers;       /* [ngroups][f+2] */
+    uint32_t *height;         /* [P] */
+    uint32_t *depth;          /* [P] */
+    uint32_t D;               /* height of the root */
+} topo_t;
+
+static void topo_free(topo_t *t)
+{
+    free(t->phys_of_virt); free(t->virt_of_phys); free(t->parent); free(t->nkids);
+    free(t->kids); free(t->root_kids); free(t->subtree); free(t->group); free(t->gpos);
+    free(t->gsize); free(t->gmembers); free(t->height); free(t->depth);
+    memset(t, 0, sizeof(*t));
+}
+
+static int topo_build(topo_t *t, uint32_t P, uint32_t f, uint32_t root)
+{
+    uint32_t v, k, nsub = f + 1, gcap = f + 2;
+    uint32_t *open_head, *open_tail, *open_next, *sub_count;
+    memset(t, 0, sizeof(*t));
+    if (P < f + 2 || root >= P) return -1;
+    t->P = P; t->f = f; t->root = root;
+    t->phys_of_virt = malloc(sizeof(uint32_t) * P);
+    t->virt_of_phys = malloc(sizeof(uint32_t) * P);
+    t->parent = malloc(sizeof(int64_t) * P);
+    t->nkids = calloc(P, sizeof(uint32_t));
+    t->kids = calloc((size_t)P * 2, sizeof(uint32_t));
+    t->root_kids = calloc(nsub, sizeof(uint32_t));
+    t->subtree = calloc(P, sizeof(uint32_t));
+    t->group = malloc(sizeof(int64_t) * P);
+    t->gpos = calloc(P, sizeof(uint32_t));
+    t->ngroups = (P - 1) / (f + 1) + 1;
+    t->gsize = calloc(t->ngroups, sizeof(uint32_t));
+    t->gmembers = calloc((size_t)t->ngroups * gcap, sizeof(uint32_t));
+    t->height = calloc(P, sizeof(uint32_t));
+    t->depth = calloc(P, sizeof(uint32_t));
+
+    /* the root's number is swapped with 0 */
+    for (v = 0; v < P; ++v) t->phys_of_virt[v] = v;
+    t->phys_of_virt[0] = root;
+    t->phys_of_virt[root] = 0;
+    if (root == 0) t->phys_of_virt[0] = 0;
+    for (v = 0; v < P; ++v) t->virt_of_phys[t->phys_of_virt[v]] = v;
+
+    /* I(f)-tree: deal 1..P-1 round-robin to f+1 subtrees; inside a subtree the
+       next process becomes a child of the oldest process with a free slot */
+    open_head = malloc(sizeof(uint32_t) * nsub);   /* oldest process with < 2 children */
+    open_tail = malloc(sizeof(uint32_t) * nsub);
+    open_next = calloc(P, sizeof(uint32_t));       /* queue links */
+    sub_count = calloc(nsub, sizeof(uint32_t));
+    t->parent[0] = -1;
+    t->nkids[0] = 0;
+    k = 0;
+    for (v = 1; v < P; ++v) {
+        t->subtree[v] = k + 1;
+        if (sub_count[k] == 0) {
+            t->parent[v] = 0;
+            t->root_kids[t->nkids[0]++] = v;
+            open_head[k] = v;
+        } else {
+            uint32_t p = open_head[k];
+            t->parent[v] = p;
+            t->kids[2 * (size_t)p + t->nkids[p]++] = v;
+            if (t->nkids[p] == 2) open_head[k] = open_next[p];
+            open_next[open_tail[k]] = v;
+        }
+        open_tail[k] = v;
+        sub_count[k]++;
+        k = (k + 1) % nsub;
+    }
+    free(open_head); free(open_tail); free(open_next); free(sub_count);
+
+    /* up-correction groups: consecutive runs of f+1 processes; a short last
+       run takes the root as its last member */
+    for (v = 0; v < P; ++v) t->group[v] = -1;
+    {
+        uint32_t g = 0;
+        for (v = 1; v < P; ++v) {
+            t->group[v] = g;
+            t->gpos[v] = t->gsize[g];
+            t->gmembers[(size_t)g * gcap + t->gsize[g]++] = v;
+            if (t->gsize[g] == f + 1) ++g;
+        }
+        if (g < t->ngroups && t->gsize[g] > 0 && t->gsize[g] < f + 1) {
+            t->group[0] = g;
+            t->gpos[0] = t->gsize[g];
+            t->gmembers[(size_t)g * gcap + t->gsize[g]++] = 0;
+            ++g;
+        }
+        t->ngroups = g;
+    }
+
+    /* depth and height from the explicit parent links (children have larger
+       numbers than their parents) */
+    for (v = 1; v < P; ++v) t->depth[v] = t->depth[t->parent[v]] + 1;
+    for (v = P - 1; v >= 1; --v) {
+        uint32_t p = (uint32_t)t->parent[v];
+        if (t->height[p] < t->height[v] + 1) t->height[p] = t->height[v] + 1;
+    }
+    t->D = t->height[0];
+    return 0;
+}
+
+/* ------------------------------------------------------------------ */
+/* processes, messages, network                                         */
+
+typedef struct msg {
+    struct msg *next;
+    int kind;
+    uint32_t src, dst;       /* virtual ranks */
+    int flag;                /* failure information: the single failed bit */
+    unsigned char *data;
+} msg_t;
+
+typedef struct {
+    msg_t *head, *tail;      /* inbox: FIFO queue */
+} inbox_t;
+
+typedef struct {
+    const topo_t *t;
+    uint32_t elems; int dtype, op;
+    size_t bytes;            /* bytes of one value */
+    uint32_t nfail;
+    const uint32_t *fail_virt;   /* [nfail] virtual ranks (ORACLE_NO_RANK = unused) */
+    const uint32_t *fail_round;  /* [nfail] */
+    unsigned char *input;    /* [P][bytes] by virtual rank */
+    unsigned char *data;     /* [P][bytes] working value of each process */
+    inbox_t *inbox;          /* [P] */
+    msg_t *inflight_head, *inflight_tail;
+    /* arena for messages */
+    unsigned char *arena; size_t arena_used, arena_cap;
+    uint64_t sent[4];
+    /* broadcast state */
+    unsigned char *has;      /* [P] */
+    unsigned char *held;     /* [P][bytes] */
+    /* traces (by virtual rank) */
+    unsigned char *trace_v;  /* [P][bytes] or NULL */
+    unsigned char *trace_sent, *trace_flag; /* [P] or NULL */
+    unsigned char *trace_msg; /* [P][bytes] or NULL */
+    int disable_uc;
+} sim_t;
+
+static int alive(const sim_t *s, uint32_t v, uint32_t round)
+{
+    uint32_t i;
+    for (i = 0; i < s->nfail; ++i)
+        if (s->fail_virt[i] == v)
+            return s->fail_round[i] != 0 && round < s->fail_round[i];
+    return 1;
+}
+
+static void *arena_alloc(sim_t *s, size_t n)
+{
+    void *p;
+    n = (n + 15) & ~(size_t)15;
+    if (s->arena_used + n > s->arena_cap) {
+        /* chain a new block; old blocks are leaked into a list */
+        size_t cap = s->arena_cap ? s->arena_cap : ((size_t)1 << 20);
+        unsigned char *blk;
+        while (cap < n + 16) cap *= 2;
+        blk = malloc(cap + 16);
+        *(unsigned char **)blk = s->arena;   /* link to previous block base */
+        s->arena = blk;
+        s->arena_used = 16;
+        s->arena_cap = cap + 16;
+    }
+    p = s->arena + s->arena_used;
+    s->arena_used += n;
+    return p;
+}
+
+static void arena_release(sim_t *s)
+{
+    while (s->arena) {
+        unsigned char *prev = *(unsigned char **)s->arena;
+        free(s->arena);
+        s->arena = prev;
+    }
+    s->arena_used = s->arena_cap = 0;
+}
+
+/* send: completes whether or not the destination is alive */
+static void net_send(sim_t *s, int kind, uint32_t src, uint32_t dst, const void *data, int flag)
+{
+    msg_t *m = arena_alloc(s, sizeof(msg_t));
+    m->next = NULL; m->kind = kind; m->src = src; m->dst = dst; m->flag = flag;
+    m->data = arena_alloc(s, s->bytes);
+    memcpy(m->data, data, s->bytes);
+    if (s->inflight_tail) s->inflight_tail->next = m; else s->inflight_head = m;
+    s->inflight_tail = m;
+    s->sent[kind]++;
+}
+
+/* end of a round: messages reach the inboxes of processes alive in this round;
+   a failed process gives no reaction to a message */
+static void net_deliver(sim_t *s, uint32_t round)
+{
+    msg_t *m = s->inflight_head;
+    while (m) {
+        msg_t *nx = m->next;
+        m->next = NULL;
+        if (alive(s, m->dst, round)) {
+            inbox_t *q = &s->inbox[m->dst];
+            if (q->tail) q->tail->next = m; else q->head = m;
+            q->tail = m;
+        }
+        m = nx;
+    }
+    s->inflight_head = s->inflight_tail = NULL;
+}
+
+/* remove and return the first message of this kind from src (or NULL) */
+static msg_t *inbox_take(sim_t *s, uint32_t v, int kind, uint32_t src)
+{
+    inbox_t *q = &s->inbox[v];
+    msg_t *prev = NULL, *m = q->head;
+    while (m) {
+        if (m->kind == kind && m->src == src) {
+            if (prev) prev->next = m->next; else q->head = m->next;
+            if (q->tail == m) q->tail = prev;
+            m->next = NULL;
+            return m;
+        }
+        prev = m; m = m->next;
+    }
+    return NULL;
+}
+
+/* remove and return the first message of this kind (any sender) */
+static msg_t *inbox_take_any(sim_t *s, uint32_t v, int kind)
+{
+    inbox_t *q = &s->inbox[v];
+    msg_t *prev = NULL, *m = q->head;
+    while (m) {
+        if (m->kind == kind) {
+            if (prev) prev->next = m->next; else q->head = m->next;
+            if (q->tail == m) q->tail = prev;
+            m->next = NULL;
+            return m;
+        }
+        prev = m; m = m->next;
+    }
+    return NULL;
+}
+
+static void clear_inboxes(sim_t *s)
+{
+    uint32_t v;
+    for (v = 0; v < s->t->P; ++v) s->inbox[v].head = s->inbox[v].tail = NULL;
+    s->inflight_head = s->inflight_tail = NULL;
+}
+
+/* ------------------------------------------------------------------ */
+/* one reduce to virtual rank 0, global rounds base+1 .. base+f+D        */
+/* returns the per-operation status; result (bytes) valid when OK        */
+
+static int run_reduce(sim_t *s, uint32_t base, void *result)
+{
+    const topo_t *t = s->t;
+    const uint32_t P = t->P, f = t->f, gcap = t->f + 2;
+    const uint32_t R = f + t->D;
+    uint32_t r, v, c;
+    unsigned char *fold = malloc(s->bytes);
+
+    /* every process starts from its input; "senddata" is the input itself */
+    memcpy(s->data, s->input, (size_t)P * s->bytes);
+    clear_inboxes(s);
+
+    for (r = 1; r <= R; ++r) {
+        const uint32_t now = base + r;
+        /* --- sends of this round, from the state at the start of the round --- */
+        for (v = 0; v < P; ++v) {
+            if (!alive(s, v, now)) continue;
+            if (r <= f) {
+                /* up-correction round t = r */
+                if (!s->disable_uc && t->group[v] >= 0) {
+                    uint32_t g = (uint32_t)t->group[v], gs = t->gsize[g];
+                    if (r <= gs - 1) {
+                        uint32_t mate = t->gmembers[(size_t)g * gcap + (t->gpos[v] + r) % gs];
+                        net_send(s, MSG_UC, v, mate, s->input + (size_t)v * s->bytes, 0);
+                    }
+                }
+            } else if (v != 0 && r == f + 1 + t->height[v]) {
+                /* tree phase: all children had their turn; fold and send up */
+                int flag = 0;
+                memcpy(fold, s->data + (size_t)v * s->bytes, s->bytes);
+                for (c = 0; c < t->nkids[v]; ++c) {
+                    msg_t *m = inbox_take(s, v, MSG_TREE, t->kids[2 * (size_t)v + c]);
+                    if (m) {
+                        combine(s->dtype, s->op, s->elems, fold, m->data);
+                        if (m->flag) flag = 1;
+                    } else {
+                        flag = 1;    /* no value from this child */
+                    }
+                }
+                net_send(s, MSG_TREE, v, (uint32_t)t->parent[v], fold, flag);
+                if (s->trace_sent) s->trace_sent[v] = 1;
+                if (s->trace_flag) s->trace_flag[v] = (unsigned char)flag;
+                if (s->trace_msg) memcpy(s->trace_msg + (size_t)v * s->bytes, fold, s->bytes);
+            }
+        }
+        /* --- end of round: deliveries, then receivers act --- */
+        net_deliver(s, now);
+        if (r <= f) {
+            for (v = 0; v < P; ++v) {
+                msg_t *m;
+                if (!alive(s, v, now)) continue;
+                while ((m = inbox_take_any(s, v, MSG_UC)) != NULL)
+                    combine(s->dtype, s->op, s->elems, s->data + (size_t)v * s->bytes, m->data);
+            }
+        }
+        if (r == f && s->trace_v) memcpy(s->trace_v, s->data, (size_t)P * s->bytes);
+    }
+    if (f == 0 && s->trace_v) memcpy(s->trace_v, s->data, (size_t)P * s->bytes);
+    free(fold);
+
+    /* --- the root, at the end of the last round --- */
+    if (!alive(s, 0, base + R)) return OR_ST_ROOT_FAILED;
+    for (c = 0; c < t->nkids[0]; ++c) {
+        uint32_t child = t->root_kids[c];
+        msg_t *m = inbox_take(s, 0, MSG_TREE, child);
+        int included = 0;
+        uint32_t i;
+        if (!m || m->flag) continue;      /* absent, or failure in that subtree */
+        /* is the root's value already in this message?  Yes iff the sender's
+           subtree holds a member of the root's up-correction group. */
+        if (!s->disable_uc && t->group[0] >= 0) {
+            uint32_t g = (uint32_t)t->group[0];
+            for (i = 0; i < t->gsize[g]; ++i) {
+                uint32_t mem = t->gmembers[(size_t)g * gcap + i];
+                if (mem != 0 && t->subtree[mem] == t->subtree[child]) included = 1;
+            }
+        }
+        if (included) {
+            memcpy(result, m->data, s->bytes);
+        } else {
+            memcpy(result, s->data, s->bytes);                   /* the root's value */
+            combine(s->dtype, s->op, s->elems, result, m->data);
+        }
+        return OR_ST_OK;
+    }
+    return OR_ST_NO_CLEAN_SUBTREE;
+}
+
+/* broadcast of `value` from virtual rank 0, rounds base+1 .. base+D+f */
+static void run_broadcast(sim_t *s, uint32_t base, const void *value)
+{
+    const topo_t *t = s->t;
+    const uint32_t P = t->P, f = t->f, gcap = t->f + 2;
+    uint32_t r, v, c;
+    clear_inboxes(s);
+    memset(s->has, 0, P);
+    s->has[0] = 1;
+    memcpy(s->held, value, s->bytes);
+    for (r = 1; r <= t->D + f; ++r) {
+        const uint32_t now = base + r;
+        for (v = 0; v < P; ++v) {
+            if (!alive(s, v, now) || !s->has[v]) continue;
+            if (r <= t->D) {
+                /* tree-down: depth r-1 sends to all its children */
+                if (t->depth[v] != r - 1) continue;
+                if (v == 0) {
+                    for (c = 0; c < t->nkids[0]; ++c)
+                        net_send(s, MSG_BCAST, 0, t->root_kids[c], s->held, 0);
+                } else {
+                    for (c = 0; c < t->nkids[v]; ++c)
+                        net_send(s, MSG_BCAST, v, t->kids[2 * (size_t)v + c],
+                                 s->held + (size_t)v * s->bytes, 0);
+                }
+            } else if (t->group[v] >= 0) {
+                /* correction round tt: every holder sends to one group mate */
+                uint32_t tt = r - t->D;
+                uint32_t g = (uint32_t)t->group[v], gs = t->gsize[g];
+                if (tt <= gs - 1) {
+                    uint32_t mate = t->gmembers[(size_t)g * gcap + (t->gpos[v] + tt) % gs];
+                    net_send(s, MSG_BCORR, v, mate, s->held + (size_t)v * s->bytes, 0);
+                }
+            }
+        }
+        net_deliver(s, now);
+        for (v = 0; v < P; ++v) {
+            msg_t *m;
+            if (!alive(s, v, now)) continue;
+            while ((m = inbox_take_any(s, v, r <= t->D ? MSG_BCAST : MSG_BCORR)) != NULL) {
+                if (!s->has[v]) {       /* keep the first value */
+                    s->has[v] = 1;
+                    memcpy(s->held + (size_t)v * s->bytes, m->data, s->bytes);
+                }
+            }
+        }
+    }
+}
+
+/* ------------------------------------------------------------------ */
+/* set-up shared by the entry points                                    */
+
+static int check_failures(uint32_t P, uint32_t nfail, const uint32_t *fail_rank)
+{
+    uint32_t i, j;
+    for (i = 0; i < nfail; ++i) {
+        if (fail_rank[i] == ORACLE_NO_RANK) continue;
+        if (fail_rank[i] >= P) return -1;
+        for (j = 0; j < i; ++j)
+            if (fail_rank[j] == fail_rank[i]) return -1;
+    }
+    return 0;
+}
+
+static void sim_init(sim_t *s, const topo_t *t, uint32_t elems, int dtype, int op,
+                     const void *payload /* by physical rank */,
+                     uint32_t nfail, const uint32_t *fail_rank, const uint32_t *fail_round,
+                     uint32_t *fail_virt_buf)
+{
+    uint32_t v, i;
+    memset(s, 0, sizeof(*s));
+    s->t = t; s->elems = elems; s->dtype = dtype; s->op = op;
+    s->bytes = elems * elem_size(dtype);
+    s->nfail = nfail;
+    for (i = 0; i < nfail; ++i)
+        fail_virt_buf[i] = fail_rank[i] == ORACLE_NO_RANK ? ORACLE_NO_RANK
+                                                          : t->virt_of_phys[fail_rank[i]];
+    s->fail_virt = fail_virt_buf;
+    s->fail_round = fail_round;
+    s->input = malloc((size_t)t->P * s->bytes);
+    s->data = malloc((size_t)t->P * s->bytes);
+    s->inbox = calloc(t->P, sizeof(inbox_t));
+    s->has = calloc(t->P, 1);
+    s->held = calloc((size_t)t->P, s->bytes);
+    for (v = 0; v < t->P; ++v)
+        memcpy(s->input + (size_t)v * s->bytes,
+               (const unsigned char *)payload + (size_t)t->phys_of_virt[v] * s->bytes, s->bytes);
+}
+
+static void sim_free(sim_t *s)
+{
+    free(s->input); free(s->data); free(s->inbox); free(s->has); free(s->held);
+    free(s->trace_v); free(s->trace_sent); free(s->trace_flag); free(s->trace_msg);
+    arena_release(s);
+}
+
+/* ------------------------------------------------------------------ */
+/* entry points                                                         */
+
+/* Structure of the tree and the groups for (P, f, root), all arrays indexed by
+   PHYSICAL rank and holding physical ranks.  parent = -1 for the root;
+   group = -1 for a process in no group; send_round = round of the tree-phase
+   message (0 for the root).  Returns 0, or -1 for invalid arguments. */
+int oracle_structure(uint32_t P, uint32_t f, uint32_t root,
+                     int64_t *parent, uint32_t *subtree, int64_t *group, uint32_t *gpos,
+                     uint32_t *gsize, uint32_t *height, uint32_t *depth,
+                     uint32_t *send_round, uint32_t *D_out)
+{
+    topo_t t;
+    uint32_t v;
+    if (topo_build(&t, P, f, root) != 0) { topo_free(&t); return -1; }
+    for (v = 0; v < P; ++v) {
+        uint32_t p = t.phys_of_virt[v];
+        parent[p] = t.parent[v] < 0 ? -1 : (int64_t)t.phys_of_virt[t.parent[v]];
+        subtree[p] = t.subtree[v];
+        group[p] = t.group[v];
+        gpos[p] = t.gpos[v];
+        gsize[p] = t.group[v] >= 0 ? t.gsize[t.group[v]] : 0;
+        height[p] = t.height[v];
+        depth[p] = t.depth[v];
+        send_round[p] = v == 0 ? 0 : f + 1 + t.height[v];
+    }
+    *D_out = t.D;
+    topo_free(&t);
+    return 0;
+}
+
+/* One reduce.  payload[P][elems] by physical rank.  Failure entries with rank
+   ORACLE_NO_RANK are unused.  Outputs: result[elems] (valid when *status == OK),
+   msgs[2] = {up-correction, tree} messages sent, *rounds = f + D.
+   Optional traces (NULL to skip), indexed by physical rank: v_after_uc[P][elems]
+   = value of each process after the up-correction phase; tree_sent/tree_flag[P]
+   and tree_msg[P][elems] = whether, with which failed bit and with which value
+   each process sent its tree message.  disable_uc != 0 skips the up-correction
+   sends (control experiment: the plain tree).  Returns 0, -1 on bad arguments. */
+int oracle_reduce(uint32_t P, uint32_t f, uint32_t elems, int dtype, int op, int disable_uc,
+                  uint32_t root, const void *payload,
+                  uint32_t nfail, const uint32_t *fail_rank, const uint32_t *fail_round,
+                  void *result, uint32_t *status, uint64_t *msgs, uint32_t *rounds,
+                  void *v_after_uc, uint8_t *tree_sent, uint8_t *tree_flag, void *tree_msg)
+{
+    topo_t t;
+    sim_t s;
+    uint32_t *fv, v;
+    int st;
+    if (elems == 0 || (dtype == OR_F64 && op != OR_SUM) || dtype < 0 || dtype > 2) return -1;
+    if (topo_build(&t, P, f, root) != 0) { topo_free(&t); return -1; }
+    *rounds = f + t.D;
+    msgs[0] = msgs[1] = 0;
+    if (check_failures(P, nfail, fail_rank) != 0) {
+        *status = OR_ST_BAD_FAILURE_SET;
+        topo_free(&t);
+        return 0;
+    }
+    fv = malloc(sizeof(uint32_t) * (nfail + 1));
+    sim_init(&s, &t, elems, dtype, op, payload, nfail, fail_rank, fail_round, fv);
+    s.disable_uc = disable_uc;
+    if (v_after_uc) s.trace_v = calloc(P, s.bytes);
+    if (tree_sent) s.trace_sent = calloc(P, 1);
+    if (tree_flag) s.trace_flag = calloc(P, 1);
+    if (tree_msg) s.trace_msg = calloc(P, s.bytes);
+    memset(result, 0, s.bytes);
+    st = run_reduce(&s, 0, result);
+    if (st != OR_ST_OK) memset(result, 0, s.bytes);
+    *status = (uint32_t)st;
+    msgs[0] = s.sent[MSG_UC];
+    msgs[1] = s.sent[MSG_TREE];
+    for (v = 0; v < P; ++v) {
+        uint32_t p = t.phys_of_virt[v];
+        if (v_after_uc) memcpy((unsigned char *)v_after_uc + (size_t)p * s.bytes, s.trace_v + (size_t)v * s.bytes, s.bytes);
+        if (tree_sent) tree_sent[p] = s.trace_sent[v];
+        if (tree_flag) tree_flag[p] = s.trace_flag[v];
+        if (tree_msg) memcpy((unsigned char *)tree_msg + (size_t)p * s.bytes, s.trace_msg + (size_t)v * s.bytes, s.bytes);
+    }
+    sim_free(&s);
+    free(fv);
+    topo_free(&t);
+    return 0;
+}
+
+/* One allreduce.  Roots tried: physical ranks 0,1,..,f.  A failure listed for
+   one of these ranks with fail_round != 0 is outside the semantics (the roots
+   may fail only before the operation) => BAD_FAILURE_SET.  Global rounds keep
+   counting over the attempts: attempt a occupies rounds a*2(f+D)+1 .. (a+1)*2(f+D).
+   Outputs: result[elems]; has[P] (1 = the process holds the value at the end);
+   out[P][elems] (the value held, zeros where has == 0; may be NULL);
+   *attempts; msgs[4] = {up-correction, tree, broadcast tree, broadcast correction}
+   summed over all attempts; *rounds = attempts * 2(f+D). */
+int oracle_allreduce(uint32_t P, uint32_t f, uint32_t elems, int dtype, int op,
+                     const void *payload,
+                     uint32_t nfail, const uint32_t *fail_rank, const uint32_t *fail_round,
+                     void *result, uint32_t *status, uint32_t *attempts, uint64_t *msgs,
+                     uint32_t *rounds, uint8_t *has, void *out)
+{
+    uint32_t a, i, v, base = 0;
+    size_t bytes;
+    uint32_t *fv;
+    int st = OR_ST_NO_LIVE_ROOT;
+    if (elems == 0 || (dtype == OR_F64 && op != OR_SUM) || dtype < 0 || dtype > 2) return -1;
+    if (P < f + 2) return -1;
+    bytes = elems * elem_size(dtype);
+    memset(result, 0, bytes);
+    memset(has, 0, P);
+    if (out) memset(out, 0, (size_t)P * bytes);
+    msgs[0] = msgs[1] = msgs[2] = msgs[3] = 0;
+    *attempts = 0; *rounds = 0;
+    if (check_failures(P, nfail, fail_rank) != 0) { *status = OR_ST_BAD_FAILURE_SET; return 0; }
+    for (i = 0; i < nfail; ++i)
+        if (fail_rank[i] != ORACLE_NO_RANK && fail_rank[i] <= f && fail_round[i] != 0) {
+            *status = OR_ST_BAD_FAILURE_SET;
+            return 0;
+        }
+    fv = malloc(sizeof(uint32_t) * (nfail + 1));
+    for (a = 0; a <= f; ++a) {
+        topo_t t;
+        sim_t s;
+        uint32_t Ra, n_alive = 0, n_ok = 0;
+        int rst;
+        topo_build(&t, P, f, a);
+        Ra = 2 * (f + t.D);
+        sim_init(&s, &t, elems, dtype, op, payload, nfail, fail_rank, fail_round, fv);
+        *attempts = a + 1;
+        rst = run_reduce(&s, base, result);
+        msgs[0] += s.sent[MSG_UC];
+        msgs[1] += s.sent[MSG_TREE];
+        if (rst == OR_ST_OK) {
+            run_broadcast(&s, base + f + t.D, result);
+            msgs[2] += s.sent[MSG_BCAST];
+            msgs[3] += s.sent[MSG_BCORR];
+        } else {
+            memset(s.has, 0, P);
+        }
+        *rounds = base + Ra;
+        /* "ok <- broadcast finished successfully", judged by every process that
+           is still alive in the last round of the attempt */
+        for (v = 0; v < P; ++v)
+            if (alive(&s, v, base + Ra)) { ++n_alive; if (s.has[v]) ++n_ok; }
+        if (rst == OR_ST_NO_CLEAN_SUBTREE) {
+            st = OR_ST_NO_CLEAN_SUBTREE;
+        } else if (n_ok == n_alive && n_alive > 0 && rst == OR_ST_OK) {
+            st = OR_ST_OK;
+            for (v = 0; v < P; ++v) {
+                uint32_t p = t.phys_of_virt[v];
+                has[p] = s.has[v];
+                if (out && s.has[v])
+                    memcpy((unsigned char *)out + (size_t)p * bytes, s.held + (size_t)v * bytes, bytes);
+            }
+        } else if (n_ok == 0) {
+            st = OR_ST_NO_LIVE_ROOT;      /* nobody got a value: try the successor */
+        } else {
+            st = OR_ST_INCONSISTENT;      /* some have it, some do not */
+        }
+        sim_free(&s);
+        topo_free(&t);
+        base += Ra;
+        if (st != OR_ST_NO_LIVE_ROOT) break;
+    }
+    if (st != OR_ST_OK) memset(result, 0, bytes);
+    *status = (uint32_t)st;
+    free(fv);
+    return 0;
+}
+
+/* Batches: scenario i uses payload + i*payload_stride_bytes (stride 0 = one
+   payload shared by all), root[i] (NULL = 0), failure rows i of [S][nfail].
+   Scenarios are independent and are spread over `threads` OpenMP threads
+   (<= 0: the runtime's default).  Returns the number of threads used, or -1. */
+int oracle_reduce_batch(uint32_t P, uint32_t f, uint32_t elems, int dtype, int op,
+                        uint32_t S, const uint32_t *root,
+                        const void *payload, uint64_t payload_stride_bytes,
+                        uint32_t nfail, const uint32_t *fail_rank, const uint32_t *fail_round,
+                        void *result, uint32_t *status, uint64_t *msgs, int threads)
+{
+    int64_t i;
+    int bad = 0, used = 1;
+    size_t bytes = elems * elem_size(dtype);
+#ifdef _OPENMP
+    if (threads > 0) omp_set_num_threads(threads);
+    used = omp_get_max_threads();
+#endif
+#pragma omp parallel for schedule(dynamic, 1)
+    for (i = 0; i < (int64_t)S; ++i) {
+        uint32_t rounds;
+        int rc = oracle_reduce(P, f, elems, dtype, op, 0, root ? root[i] : 0,
+                               (const unsigned char *)payload + (size_t)i * payload_stride_bytes,
+                               nfail, fail_rank + (size_t)i * nfail, fail_round + (size_t)i * nfail,
+                               (unsigned char *)result + (size_t)i * bytes, status + i,
+                               msgs + 2 * (size_t)i, &rounds, NULL, NULL, NULL, NULL);
+        if (rc != 0) {
+#pragma omp atomic write
+            bad = 1;
+        }
+    }
+    return bad ? -1 : used;
+}
+
+int oracle_allreduce_batch(uint32_t P, uint32_t f, uint32_t elems, int dtype, int op,
+                           uint32_t S, const void *payload, uint64_t payload_stride_bytes,
+                           uint32_t nfail, const uint32_t *fail_rank, const uint32_t *fail_round,
+                           void *result, uint32_t *status, uint32_t *attempts, uint64_t *msgs,
+                           uint32_t *rounds, uint8_t *has /* [S][P] or NULL */,
+                           void *out /* [S][P][elems] or NULL */, int threads)
+{
+    int64_t i;
+    int bad = 0, used = 1;
+    size_t bytes = elems * elem_size(dtype);
+#ifdef _OPENMP
+    if (threads > 0) omp_set_num_threads(threads);
+    used = omp_get_max_threads();
+#endif
+#pragma omp parallel for schedule(dynamic, 1)
+    for (i = 0; i < (int64_t)S; ++i) {
+        uint8_t *h = has ? has + (size_t)i * P : malloc(P);
+        int rc = oracle_allreduce(P, f, elems, dtype, op,
+                                  (const unsigned char *)payload + (size_t)i * payload_stride_bytes,
+                                  nfail, fail_rank + (size_t)i * nfail, fail_round + (size_t)i * nfail,
+                                  (unsigned char *)result + (size_t)i * bytes, status + i,
+                                  attempts + i, msgs + 4 * (size_t)i, rounds + i, h,
+                                  out ? (unsigned char *)out + (size_t)i * P * bytes : NULL);
+        if (!has) free(h);
+        if (rc != 0) {
+#pragma omp atomic write
+            bad = 1;
+        }
+    }
+    return bad ? -1 : used;
+}
