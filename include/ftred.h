@@ -1,0 +1,210 @@
+/*
+ * ftred - round-synchronous execution of the correction-based fault-tolerant
+ * reduce and allreduce over P virtual processes and a batch of S failure
+ * scenarios on one MI355X (gfx950).
+ *
+ * Method: Kuettler & Haertig, "Fault-tolerant Reduce and Allreduce operations
+ * based on correction".  Citations below name that paper's sections,
+ * algorithms and theorems.
+ *
+ * Conventions of every entry point
+ *   - returns an int code (FTRED_OK = 0); never throws, never aborts.  On an
+ *     error the message is available from ftred_last_error() (thread-local).
+ *   - "dev" pointers are device (HBM) pointers owned by the caller; "host"
+ *     pointers are host memory.  The library owns only the plan.
+ *   - `hip_stream` is a hipStream_t passed as void* (NULL = the null stream).
+ *     Calls enqueue work on that stream and return without waiting, except
+ *     where stated.
+ *   - ranks in arguments and results are PHYSICAL ranks 0..P-1; the relabelling
+ *     that makes the root number 0 (section "Reduce", first paragraph) is
+ *     internal.
+ *   - a scenario = one independent execution of the operation with its own
+ *     failure set (and payload, root).  Argument errors give FTRED_EINVAL;
+ *     errors in the DATA of one scenario give a per-scenario status and the run
+ *     goes on for the others.
+ *
+ * Failure model (sections "Failures", "Reduce / Semantics"; rounds are this
+ * library's execution model): per scenario f slots (fail_rank, fail_round).
+ * fail_rank = FTRED_NO_RANK marks an unused slot.  fail_round = 0: the process
+ * failed before the operation.  fail_round = r >= 1: the process performs all
+ * sends of global rounds < r and nothing from round r on (fail-stop).  Global
+ * rounds count from 1; in an allreduce they keep counting over the attempts.
+ * A message that is missing in the round it has in the failure-free run tells
+ * the receiver that the sender failed.
+ */
+#ifndef FTRED_H
+#define FTRED_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct ftred_plan_s ftred_plan_t;   /* opaque; created by ftred_plan, freed by ftred_plan_destroy */
+
+enum { FTRED_OK = 0, FTRED_EINVAL = 1, FTRED_ENOMEM = 2, FTRED_EDEVICE = 3, FTRED_EUNSUPPORTED = 4 };
+
+/* element type of the payload */
+enum { FTRED_I64 = 0, FTRED_U32 = 1, FTRED_F64 = 2 };
+
+/* reduction function (section "Reduce": associative and commutative).
+   SUM wraps for the integer types; BOR (bitwise or) is for integer types only. */
+enum { FTRED_SUM = 0, FTRED_BOR = 1 };
+
+/* per-scenario status */
+enum {
+    FTRED_ST_OK = 0,
+    FTRED_ST_ROOT_FAILED = 1,        /* reduce only: the root failed, the operation is a no-op
+                                        (section "Reduce / Algorithm") */
+    FTRED_ST_NO_CLEAN_SUBTREE = 2,   /* the root found no child reporting "no failure" (Algorithm
+                                        "reduce, root"); impossible with <= f failures (third theorem) */
+    FTRED_ST_BAD_FAILURE_SET = 3     /* a rank >= P, a rank listed twice, a root >= P, or (allreduce) a
+                                        root candidate 0..f listed with fail_round != 0; nothing is
+                                        simulated, outputs of the scenario are zero */
+};
+
+#define FTRED_NO_RANK 0xFFFFFFFFu
+#define FTRED_MAX_F 15u
+
+/* ftred_validate verdict bits (0 = valid) */
+enum {
+    FTRED_BAD_VALUE = 1,      /* result is not the reduction over the never-failed processes plus one
+                                 subset of the processes that failed during the operation */
+    FTRED_BAD_HOLDER = 2,     /* allreduce: a never-failed process does not hold the result, or holds
+                                 another value; or a process failed beforehand is marked as holder */
+    FTRED_BAD_STATUS = 4,     /* status does not match the failure set (e.g. OK with a failed root) */
+    FTRED_BAD_COUNT = 8       /* message counters outside what the message-count theorems allow */
+};
+
+typedef struct ftred_info {
+    uint32_t P, f, elems, dtype, op;
+    uint32_t groups_full;        /* floor((P-1)/(f+1)) up-correction groups of f+1 processes */
+    uint32_t a;                  /* ((P-1) mod (f+1)) + 1; the root is in a group iff a > 1 */
+    uint32_t D;                  /* height of the tree (rounds of the tree phase) */
+    uint32_t rounds_reduce;      /* f + D */
+    uint32_t rounds_attempt;     /* 2 (f + D): reduce, broadcast down the tree, f correction rounds */
+    uint32_t tiers;              /* kernel launches of one tree phase */
+    uint32_t reserved;
+    uint64_t msgs_uc_ff;         /* failure-free up-correction messages (message-count theorem) */
+    uint64_t msgs_tree_ff;       /* failure-free tree messages = P - 1 */
+    uint64_t msgs_bcast_tree_ff; /* failure-free broadcast tree messages = P - 1 */
+    uint64_t msgs_bcast_corr_ff; /* failure-free broadcast correction messages (= msgs_uc_ff) */
+} ftred_info_t;
+
+/* Create a plan for P processes, failure bound f, `elems` values of `dtype` per
+   process and reduction `op`.  Requires P >= f + 2 (the root needs f+1 children:
+   definition of the I(f)-tree), f <= FTRED_MAX_F, elems >= 1, P * elems * size
+   < 2^31 bytes, no BOR on FTRED_F64.  flags: 0, or an LDS budget in KiB (8..60)
+   for the tree kernels' tiles.  Host call; no device work. */
+int ftred_plan(ftred_plan_t **out, uint32_t P, uint32_t f, uint32_t elems, int dtype, int op, uint32_t flags);
+int ftred_plan_info(const ftred_plan_t *plan, ftred_info_t *info /* host, written */);
+void ftred_plan_destroy(ftred_plan_t *plan);
+const char *ftred_last_error(void);      /* never NULL; valid until the thread's next failing call */
+
+/* Bytes of device workspace a run or validation of S scenarios needs. */
+uint64_t ftred_workspace_bytes(const ftred_plan_t *plan, uint32_t S);
+
+/* Index arithmetic of one process (host call, no device work): the tree of
+   section "Reduce / Properties" (definition of the I(f)-tree; subtree rule of
+   the replication theorem's proof) and the up-correction group of section
+   "Up-Correction", for operation root `root`.  All ranks physical.
+   parent = FTRED_NO_RANK for the root; children: up to f+1 entries for the root,
+   two otherwise; group[0..group_size) in group order (empty if the process is in
+   no group), group_pos = own index in it; subtree = 0 for the root else 1..f+1;
+   send_round = round of the tree message inside one reduce (0 for the root). */
+typedef struct ftred_partners {
+    uint32_t parent;
+    uint32_t n_children;
+    uint32_t children[FTRED_MAX_F + 1];
+    uint32_t group_size, group_pos;
+    uint32_t group[FTRED_MAX_F + 1];
+    uint32_t subtree, depth, height, send_round;
+} ftred_partners_t;
+int ftred_partners(const ftred_plan_t *plan, uint32_t root, uint32_t rank, ftred_partners_t *out /* host */);
+
+/* The same arithmetic evaluated on the GPU for every rank (device index functions
+   as used by the kernels): each output is dev [P] uint32 or NULL. */
+int ftred_structure(const ftred_plan_t *plan, uint32_t root,
+                    uint32_t *parent, uint32_t *subtree, uint32_t *group_id, uint32_t *group_pos,
+                    uint32_t *group_size, uint32_t *depth, uint32_t *send_round, void *hip_stream);
+
+/* S fault-tolerant reduces (Algorithms "Up-correction", "reduce at non-roots",
+   "reduce at the root"; failure information = the single failed bit of section
+   "Failure information").
+     root        dev [S] root of each scenario, or NULL = 0
+     payload     dev [S][P][elems] input of every process; scen_stride_elems =
+                 distance between scenarios in elements (P*elems when packed,
+                 0 = one payload shared by all scenarios)
+     fail_rank, fail_round  dev [S][max(f,1)]
+     result      dev [S][elems] value returned at the root (zeros unless status OK)
+     status      dev [S]
+     msgs        dev [S][2] uint64 {up-correction, tree} messages sent, or NULL
+     workspace   dev, ftred_workspace_bytes(plan, S) bytes, 256-byte aligned
+   The root delivers iff it is alive in the last round f + D.  Among several
+   children reporting "no failure" the root takes the lowest-numbered one. */
+int ftred_run_reduce(const ftred_plan_t *plan, uint32_t S, const uint32_t *root,
+                     const void *payload, uint64_t scen_stride_elems,
+                     const uint32_t *fail_rank, const uint32_t *fail_round,
+                     void *result, uint32_t *status, uint64_t *msgs,
+                     void *workspace, uint64_t workspace_bytes, void *hip_stream);
+
+/* S fault-tolerant allreduces (Algorithm "Allreduce"): reduce to root r, broadcast
+   from r, retry with r+1 while r had failed; roots tried are ranks 0,1,..,f and
+   may fail only before the operation (section "Allreduce / Description").  The
+   broadcast sends the value down the same tree (D rounds) and then runs f
+   correction rounds in the up-correction groups (every holder sends to one group
+   mate per round).
+     result          dev [S][elems] the value every surviving process holds
+     has_bitmap      dev [S][ceil(P/32)] bit p%32 of word p/32 = process p holds it; or NULL
+     per_process_out dev [S][P][elems] receive buffer of every process (zeros for
+                     processes that hold nothing); or NULL
+     attempts        dev [S] roots tried; msgs dev [S][4] uint64 {up-correction, tree,
+                     broadcast tree, broadcast correction} over all attempts, or NULL */
+int ftred_run_allreduce(const ftred_plan_t *plan, uint32_t S,
+                        const void *payload, uint64_t scen_stride_elems,
+                        const uint32_t *fail_rank, const uint32_t *fail_round,
+                        void *result, uint32_t *has_bitmap, void *per_process_out,
+                        uint32_t *status, uint32_t *attempts, uint64_t *msgs,
+                        void *workspace, uint64_t workspace_bytes, void *hip_stream);
+
+/* Check results against the semantics (sections "Reduce / Semantics", items 3
+   and 4, and "Allreduce / Semantics", items 4 and 5; message-count theorems),
+   independently of the protocol: per scenario the reduction over the never-failed
+   processes is recomputed from the payload, and the result must equal it combined
+   with one subset of the processes that failed during the operation (integers:
+   exactly; FTRED_F64: within 1e-12 * sum of |x| per element).  kind 0 = reduce,
+   1 = allreduce.  has_bitmap / per_process_out / msgs may be NULL (not checked).
+   verdict dev [S] gets FTRED_BAD_* bits; *n_invalid (host, may be NULL) gets the
+   number of scenarios with verdict != 0: when it is not NULL the call waits for
+   the stream. */
+int ftred_validate(const ftred_plan_t *plan, int kind, uint32_t S, const uint32_t *root,
+                   const void *payload, uint64_t scen_stride_elems,
+                   const uint32_t *fail_rank, const uint32_t *fail_round,
+                   const void *result, const uint32_t *has_bitmap, const void *per_process_out,
+                   const uint32_t *status, const uint32_t *attempts, const uint64_t *msgs,
+                   uint32_t *verdict, uint64_t *n_invalid,
+                   void *workspace, uint64_t workspace_bytes, void *hip_stream);
+
+/* Counter-based failure scenarios on the device (Philox4x32-10, counter =
+   (scenario, slot, draw, stream), key = seed): k uniform in 0..f failed ranks per
+   scenario, uniform without replacement; each failure happens during the operation
+   with probability inop_permille/1000 at a round uniform in 1..A*rounds_per_attempt
+   (A = 1 + number of leading ranks 0,1,.. below `protected_ranks` in the set), else
+   before the operation; ranks below protected_ranks always fail before it.
+   root_out (dev [S] or NULL) gets a uniform root per scenario.
+   fail_rank, fail_round: dev [S][max(f,1)], written.  Scenario ids scen0..scen0+S-1. */
+int ftred_gen_failures(const ftred_plan_t *plan, uint64_t seed, uint32_t S, uint32_t scen0,
+                       uint32_t inop_permille, uint32_t rounds_per_attempt, uint32_t protected_ranks,
+                       uint32_t *root_out, uint32_t *fail_rank, uint32_t *fail_round, void *hip_stream);
+
+/* Counter-based integer payloads on the device, same generator: payload dev
+   [S][P][elems] of the plan's integer dtype, each value `bits` random bits
+   (FTRED_I64: minus 2^(bits-1), i.e. uniform in [-2^(bits-1), 2^(bits-1))). */
+int ftred_gen_payload_int(const ftred_plan_t *plan, uint64_t seed, uint32_t S, uint32_t scen0,
+                          uint32_t bits, void *payload, void *hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FTRED_H */

@@ -1,0 +1,368 @@
+// C-ABI of libftred (declared in include/ftred.h): plan, launch logic, and the
+// kernels that do not depend on the value type's arithmetic (scenario check,
+// index arithmetic for every rank).
+#include <hip/hip_runtime.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <new>
+
+#include "../../include/ftred.h"
+#include "ftred_kernels.h"
+#include "ftred_phases.h"
+#include "ftred_plan.h"
+
+using namespace ftred;
+
+// ---------------------------------------------------------------------------
+// errors
+
+static thread_local char g_err[512] = "";
+
+int ftred::set_error(int code, const char* fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+#define fail ftred::set_error
+
+extern "C" const char* ftred_last_error(void) { return g_err; }
+
+// ---------------------------------------------------------------------------
+// plan
+
+extern "C" int ftred_plan(ftred_plan_t** out, uint32_t P, uint32_t f, uint32_t elems, int dtype, int op,
+                          uint32_t flags)
+{
+    if (!out) return fail(FTRED_EINVAL, "ftred_plan: out is NULL");
+    *out = nullptr;
+    if (f > FTRED_MAX_F) return fail(FTRED_EUNSUPPORTED, "ftred_plan: f = %u exceeds %u", f, FTRED_MAX_F);
+    if (P < f + 2) return fail(FTRED_EINVAL, "ftred_plan: P = %u < f + 2 = %u (the root needs f+1 children)", P, f + 2);
+    if (elems < 1) return fail(FTRED_EINVAL, "ftred_plan: elems must be >= 1");
+    if (dtype != FTRED_I64 && dtype != FTRED_U32 && dtype != FTRED_F64)
+        return fail(FTRED_EINVAL, "ftred_plan: unknown dtype %d", dtype);
+    if (op != FTRED_SUM && op != FTRED_BOR) return fail(FTRED_EINVAL, "ftred_plan: unknown op %d", op);
+    if (dtype == FTRED_F64 && op == FTRED_BOR) return fail(FTRED_EINVAL, "ftred_plan: bitwise or needs an integer type");
+    const uint32_t esz = dtype == FTRED_U32 ? 4u : 8u;
+    if (uint64_t(P) * elems * esz >= (uint64_t(1) << 31))
+        return fail(FTRED_EUNSUPPORTED, "ftred_plan: P * elems * size must stay below 2^31 bytes");
+    uint32_t budget = 40u * 1024u;
+    if (flags != 0) {
+        if (flags < 8 || flags > 60) return fail(FTRED_EINVAL, "ftred_plan: flags = LDS budget in KiB, 8..60");
+        budget = flags * 1024u;
+    }
+    ftred_plan_t* p = new (std::nothrow) ftred_plan_t;
+    if (!p) return fail(FTRED_ENOMEM, "ftred_plan: out of host memory");
+    memset(p, 0, sizeof(*p));
+    p->g = make_geom(P, f, elems, esz);
+    p->dtype = dtype;
+    p->op = op;
+    const Geom& g = p->g;
+
+    // tiers of the tree phase, deepest first
+    const uint32_t cap_rows = budget / (g.RB + 4u);
+    if (cap_rows < 3) {
+        delete p;
+        return fail(FTRED_EUNSUPPORTED, "ftred_plan: one up-correction group (%u bytes) does not fit the LDS tile", g.RB);
+    }
+    const uint32_t hcap0 = ilog2(cap_rows + 1u) - 1u;            // 2^(h+1) - 1 <= cap_rows
+    const uint32_t hcap1 = ilog2(cap_rows + 1u) - 2u;            // 2^(h+2) - 1 <= cap_rows
+    uint32_t nt = 0;
+    {
+        uint32_t h0 = hcap0 < g.L ? hcap0 : g.L;
+        TierDesc& t = p->tiers[nt++];
+        t.dlo = g.L - h0; t.dhi = g.L; t.child_in = 0;
+        int d = int(t.dlo) - 1;
+        while (d >= 0) {
+            if (nt == kMaxTiers) {
+                delete p;
+                return fail(FTRED_EUNSUPPORTED, "ftred_plan: the tree needs more than %d tiers at this LDS budget", kMaxTiers);
+            }
+            uint32_t h = hcap1 < uint32_t(d) ? hcap1 : uint32_t(d);
+            TierDesc& u = p->tiers[nt++];
+            u.dlo = uint32_t(d) - h; u.dhi = uint32_t(d); u.child_in = 1;
+            d = int(u.dlo) - 1;
+        }
+    }
+    p->ntiers = nt;
+    uint32_t off = align_up(g.EB, 16);      // [0, EB): the root's value after up-correction
+    p->vroot_off = 0;
+    for (uint32_t t = 0; t < nt; ++t) {
+        TierDesc& td = p->tiers[t];
+        const uint32_t h = td.dhi - td.dlo;
+        td.is_top = td.dlo == 0 ? 1u : 0u;
+        td.lds_rows = ((2u << h) - 1u) + (td.child_in ? (2u << h) : 0u);
+        td.lds_bytes = uint32_t(sizeof(FailTab)) + align_up(td.lds_rows * 4u, 16) + td.lds_rows * g.RB;
+        if (td.lds_bytes > p->max_lds) p->max_lds = td.lds_bytes;
+        if (t > 0) { td.in_off = p->tiers[t - 1].out_off; td.in_meta_off = p->tiers[t - 1].out_meta_off; }
+        if (!td.is_top) {
+            td.out_off = off;
+            off += align_up((1u << td.dlo) * g.RB, 16);
+            td.out_meta_off = off;
+            off += align_up((1u << td.dlo) * 4u, 16);
+        }
+    }
+    p->ws_scen = align_up(off, 256);
+    p->retry_blocks = 64;
+    // broadcast / validation chunks: about 32 KiB of payload, a multiple of 32 ranks
+    {
+        uint32_t c = (32u * 1024u) / g.EB;
+        c = c / 32u * 32u;
+        if (c < 32u) c = 32u;
+        if (c > 8192u) c = 8192u;
+        p->bc_chunk = c;
+        p->val_chunk = c;
+    }
+    *out = p;
+    return FTRED_OK;
+}
+
+extern "C" void ftred_plan_destroy(ftred_plan_t* plan) { delete plan; }
+
+extern "C" int ftred_plan_info(const ftred_plan_t* plan, ftred_info_t* info)
+{
+    if (!plan || !info) return fail(FTRED_EINVAL, "ftred_plan_info: NULL argument");
+    const Geom& g = plan->g;
+    memset(info, 0, sizeof(*info));
+    info->P = g.P; info->f = g.f; info->elems = g.E;
+    info->dtype = uint32_t(plan->dtype); info->op = uint32_t(plan->op);
+    info->groups_full = (g.P - 1) / g.W;
+    info->a = g.a;
+    info->D = g.D;
+    info->rounds_reduce = g.Rred;
+    info->rounds_attempt = g.Ratt;
+    info->tiers = plan->ntiers;
+    info->msgs_uc_ff = msgs_uc_ff(g);
+    info->msgs_tree_ff = g.P - 1;
+    info->msgs_bcast_tree_ff = g.P - 1;
+    info->msgs_bcast_corr_ff = msgs_uc_ff(g);
+    return FTRED_OK;
+}
+
+extern "C" uint64_t ftred_workspace_bytes(const ftred_plan_t* plan, uint32_t S)
+{
+    if (!plan) return 0;
+    return ws_total(plan, S);
+}
+
+// ---------------------------------------------------------------------------
+// index arithmetic of one process, on the host
+
+extern "C" int ftred_partners(const ftred_plan_t* plan, uint32_t root, uint32_t rank, ftred_partners_t* out)
+{
+    if (!plan || !out) return fail(FTRED_EINVAL, "ftred_partners: NULL argument");
+    const Geom& g = plan->g;
+    if (root >= g.P || rank >= g.P) return fail(FTRED_EINVAL, "ftred_partners: rank or root >= P");
+    memset(out, 0, sizeof(*out));
+    PartnerInfo pi;
+    partners_of(g, root, rank, pi);
+    out->parent = pi.parent;
+    out->n_children = pi.n_children;
+    for (uint32_t i = 0; i < pi.n_children; ++i) out->children[i] = pi.children[i];
+    out->group_size = pi.group_size;
+    out->group_pos = pi.group_pos;
+    for (uint32_t i = 0; i < pi.group_size; ++i) out->group[i] = pi.group[i];
+    out->subtree = pi.subtree;
+    out->depth = pi.depth;
+    out->height = pi.height;
+    out->send_round = pi.send_round;
+    return FTRED_OK;
+}
+
+__global__ void structure_kernel(Geom g, uint32_t root, uint32_t* parent, uint32_t* subtree, uint32_t* group_id,
+                                 uint32_t* group_pos, uint32_t* group_size_out, uint32_t* depth,
+                                 uint32_t* send_round)
+{
+    uint32_t p = blockIdx.x * blockDim.x + threadIdx.x;
+    if (p >= g.P) return;
+    PartnerInfo pi;
+    partners_of(g, root, p, pi);
+    if (parent) parent[p] = pi.parent;
+    if (subtree) subtree[p] = pi.subtree;
+    if (group_id) group_id[p] = pi.group_id;
+    if (group_pos) group_pos[p] = pi.group_pos;
+    if (group_size_out) group_size_out[p] = pi.group_size;
+    if (depth) depth[p] = pi.depth;
+    if (send_round) send_round[p] = pi.send_round;
+}
+
+extern "C" int ftred_structure(const ftred_plan_t* plan, uint32_t root, uint32_t* parent, uint32_t* subtree,
+                               uint32_t* group_id, uint32_t* group_pos, uint32_t* group_size_out,
+                               uint32_t* depth, uint32_t* send_round, void* hip_stream)
+{
+    if (!plan) return fail(FTRED_EINVAL, "ftred_structure: plan is NULL");
+    if (root >= plan->g.P) return fail(FTRED_EINVAL, "ftred_structure: root >= P");
+    hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
+    const uint32_t grid = (plan->g.P + 255u) / 256u;
+    hipLaunchKernelGGL(structure_kernel, dim3(grid), dim3(256), 0, st, plan->g, root, parent, subtree, group_id,
+                       group_pos, group_size_out, depth, send_round);
+    HIP_TRY(hipGetLastError());
+    return FTRED_OK;
+}
+
+// ---------------------------------------------------------------------------
+// launch helpers
+
+static hipError_t dispatch_tier(const ftred_plan_t* p, const RunArgs& A, uint32_t grid, uint32_t lds, hipStream_t st)
+{
+    if (p->dtype == FTRED_I64) return p->op == FTRED_SUM ? launch_tier_i64_sum(A, grid, lds, st) : launch_tier_i64_bor(A, grid, lds, st);
+    if (p->dtype == FTRED_U32) return p->op == FTRED_SUM ? launch_tier_u32_sum(A, grid, lds, st) : launch_tier_u32_bor(A, grid, lds, st);
+    return launch_tier_f64_sum(A, grid, lds, st);
+}
+
+static hipError_t dispatch_retry(const ftred_plan_t* p, const RunArgs& A, uint32_t grid, uint32_t lds, hipStream_t st)
+{
+    if (p->dtype == FTRED_I64) return p->op == FTRED_SUM ? launch_retry_i64_sum(A, grid, lds, st) : launch_retry_i64_bor(A, grid, lds, st);
+    if (p->dtype == FTRED_U32) return p->op == FTRED_SUM ? launch_retry_u32_sum(A, grid, lds, st) : launch_retry_u32_bor(A, grid, lds, st);
+    return launch_retry_f64_sum(A, grid, lds, st);
+}
+
+static int check_common(const char* who, const ftred_plan_t* plan, uint32_t S, const void* payload,
+                        uint64_t scen_stride_elems, const uint32_t* fail_rank, const uint32_t* fail_round,
+                        const void* workspace, uint64_t workspace_bytes)
+{
+    if (!plan) return fail(FTRED_EINVAL, "%s: plan is NULL", who);
+    if (S == 0) return fail(FTRED_EINVAL, "%s: S must be >= 1", who);
+    if (!payload || !fail_rank || !fail_round) return fail(FTRED_EINVAL, "%s: payload, fail_rank and fail_round are required", who);
+    const Geom& g = plan->g;
+    if (scen_stride_elems != 0 && scen_stride_elems < uint64_t(g.P) * g.E)
+        return fail(FTRED_EINVAL, "%s: scen_stride_elems %llu < P * elems", who, (unsigned long long)scen_stride_elems);
+    if (reinterpret_cast<uintptr_t>(payload) % g.esz != 0) return fail(FTRED_EINVAL, "%s: payload is not aligned to its element size", who);
+    if (!workspace) return fail(FTRED_EINVAL, "%s: workspace is NULL", who);
+    if (reinterpret_cast<uintptr_t>(workspace) % 256 != 0) return fail(FTRED_EINVAL, "%s: workspace must be 256-byte aligned", who);
+    if (workspace_bytes < ftred_workspace_bytes(plan, S))
+        return fail(FTRED_EINVAL, "%s: workspace of %llu bytes, %llu needed", who, (unsigned long long)workspace_bytes,
+                    (unsigned long long)ftred_workspace_bytes(plan, S));
+    for (uint32_t t = 0; t < plan->ntiers; ++t)
+        if ((uint64_t(S) << plan->tiers[t].dlo) >= (uint64_t(1) << 31))
+            return fail(FTRED_EUNSUPPORTED, "%s: S = %u scenarios need too many workgroups; split the batch", who, S);
+    return FTRED_OK;
+}
+
+static void fill_run_args(RunArgs& A, const ftred_plan_t* p, uint32_t S, const void* payload, uint64_t scen_stride_elems,
+                          const uint32_t* fail_rank, const uint32_t* fail_round, void* workspace)
+{
+    memset(&A, 0, sizeof(A));
+    const Geom& g = p->g;
+    A.g = g;
+    A.payload = static_cast<const unsigned char*>(payload);
+    A.scen_stride_bytes = scen_stride_elems * g.esz;
+    A.fail_rank = fail_rank;
+    A.fail_round = fail_round;
+    A.S = S;
+    A.ws = static_cast<unsigned char*>(workspace);
+    A.ws_stride = p->ws_scen;
+    A.vroot_off = p->vroot_off;
+    A.vec16 = (g.EB % 16 == 0 && reinterpret_cast<uintptr_t>(payload) % 16 == 0 && A.scen_stride_bytes % 16 == 0) ? 1u : 0u;
+    A.ntiers = p->ntiers;
+    for (uint32_t t = 0; t < p->ntiers; ++t) A.tiers[t] = p->tiers[t];
+}
+
+// ---------------------------------------------------------------------------
+// reduce
+
+extern "C" int ftred_run_reduce(const ftred_plan_t* plan, uint32_t S, const uint32_t* root, const void* payload,
+                                uint64_t scen_stride_elems, const uint32_t* fail_rank, const uint32_t* fail_round,
+                                void* result, uint32_t* status, uint64_t* msgs, void* workspace,
+                                uint64_t workspace_bytes, void* hip_stream)
+{
+    int rc = check_common("ftred_run_reduce", plan, S, payload, scen_stride_elems, fail_rank, fail_round, workspace,
+                          workspace_bytes);
+    if (rc != FTRED_OK) return rc;
+    if (!result || !status) return fail(FTRED_EINVAL, "ftred_run_reduce: result and status are required");
+    if (reinterpret_cast<uintptr_t>(result) % plan->g.esz != 0)
+        return fail(FTRED_EINVAL, "ftred_run_reduce: result must be aligned to the element size");
+    hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
+    const Geom& g = plan->g;
+
+    hipLaunchKernelGGL(prepass_kernel, dim3((S + 255u) / 256u), dim3(256), 0, st, g, 0u, S, root, fail_rank, fail_round,
+                       status, static_cast<uint32_t*>(nullptr), reinterpret_cast<unsigned long long*>(msgs), 2u,
+                       static_cast<unsigned char*>(result));
+    HIP_TRY(hipGetLastError());
+
+    RunArgs A;
+    fill_run_args(A, plan, S, payload, scen_stride_elems, fail_rank, fail_round, workspace);
+    A.root = root;
+    A.status = status;
+    A.result = static_cast<unsigned char*>(result);
+    A.msgs = reinterpret_cast<unsigned long long*>(msgs);
+    A.nmsg = 2;
+    for (uint32_t t = 0; t < plan->ntiers; ++t) {
+        A.tier = t;
+        HIP_TRY(dispatch_tier(plan, A, S << plan->tiers[t].dlo, plan->tiers[t].lds_bytes, st));
+    }
+    return FTRED_OK;
+}
+
+// ---------------------------------------------------------------------------
+// allreduce
+
+extern "C" int ftred_run_allreduce(const ftred_plan_t* plan, uint32_t S, const void* payload, uint64_t scen_stride_elems,
+                                   const uint32_t* fail_rank, const uint32_t* fail_round, void* result,
+                                   uint32_t* has_bitmap, void* per_process_out, uint32_t* status, uint32_t* attempts,
+                                   uint64_t* msgs, void* workspace, uint64_t workspace_bytes, void* hip_stream)
+{
+    int rc = check_common("ftred_run_allreduce", plan, S, payload, scen_stride_elems, fail_rank, fail_round, workspace,
+                          workspace_bytes);
+    if (rc != FTRED_OK) return rc;
+    if (!result || !status || !attempts) return fail(FTRED_EINVAL, "ftred_run_allreduce: result, status and attempts are required");
+    if (reinterpret_cast<uintptr_t>(result) % plan->g.esz != 0 || reinterpret_cast<uintptr_t>(per_process_out) % plan->g.esz != 0)
+        return fail(FTRED_EINVAL, "ftred_run_allreduce: result and per_process_out must be aligned to the element size");
+    hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
+    const Geom& g = plan->g;
+
+    hipLaunchKernelGGL(prepass_kernel, dim3((S + 255u) / 256u), dim3(256), 0, st, g, 1u, S,
+                       static_cast<const uint32_t*>(nullptr), fail_rank, fail_round, status, attempts,
+                       reinterpret_cast<unsigned long long*>(msgs), 4u, static_cast<unsigned char*>(result));
+    HIP_TRY(hipGetLastError());
+
+    RunArgs A;
+    fill_run_args(A, plan, S, payload, scen_stride_elems, fail_rank, fail_round, workspace);
+    A.attempts = attempts;
+    A.status = status;
+    A.result = static_cast<unsigned char*>(result);
+    A.msgs = reinterpret_cast<unsigned long long*>(msgs);
+    A.nmsg = 4;
+
+    // attempts whose root had failed beforehand (none in most batches): own scratch
+    if (g.f > 0) {
+        RunArgs R = A;
+        R.ws = A.ws + uint64_t(S) * plan->ws_scen;
+        uint32_t blocks = plan->retry_blocks < S ? plan->retry_blocks : S;
+        HIP_TRY(dispatch_retry(plan, R, blocks, plan->max_lds, st));
+    }
+    // the attempt that succeeds
+    for (uint32_t t = 0; t < plan->ntiers; ++t) {
+        A.tier = t;
+        HIP_TRY(dispatch_tier(plan, A, S << plan->tiers[t].dlo, plan->tiers[t].lds_bytes, st));
+    }
+    // broadcast down the tree and correction rounds
+    BcastArgs B;
+    memset(&B, 0, sizeof(B));
+    B.g = g;
+    B.S = S;
+    B.attempts = attempts;
+    B.status = status;
+    B.fail_rank = fail_rank;
+    B.fail_round = fail_round;
+    B.result = static_cast<const unsigned char*>(result);
+    B.has_bitmap = has_bitmap;
+    B.out = static_cast<unsigned char*>(per_process_out);
+    B.msgs = reinterpret_cast<unsigned long long*>(msgs);
+    B.chunk = plan->bc_chunk;
+    B.nchunks = (g.P + plan->bc_chunk - 1) / plan->bc_chunk;
+    B.div_nchunks = make_fastdiv(B.nchunks);
+    B.vec16 = (g.EB % 16 == 0 && reinterpret_cast<uintptr_t>(result) % 16 == 0 &&
+               (!per_process_out || reinterpret_cast<uintptr_t>(per_process_out) % 16 == 0)) ? 1u : 0u;
+    if (uint64_t(S) * B.nchunks >= (uint64_t(1) << 31))
+        return fail(FTRED_EUNSUPPORTED, "ftred_run_allreduce: S = %u scenarios need too many workgroups; split the batch", S);
+    const uint32_t lds = bcast_lds_bytes(B);
+    hipLaunchKernelGGL(bcast_kernel, dim3(S * B.nchunks), dim3(kThreads), lds, st, B);
+    HIP_TRY(hipGetLastError());
+    return FTRED_OK;
+}

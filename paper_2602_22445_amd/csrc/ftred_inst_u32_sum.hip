@@ -1,0 +1,8 @@
+// Instantiation of the tree-phase kernels for one value type and operator
+// (all compile-time group widths); kept in a file of its own so that the
+// instantiations compile in parallel.
+#include "ftred_kernels.h"
+
+namespace ftred {
+FTRED_DEFINE_LAUNCHERS(u32_sum, uint32_t, 0)
+}  // namespace ftred

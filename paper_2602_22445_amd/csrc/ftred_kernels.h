@@ -1,0 +1,584 @@
+// Device code of the up-correction phase, the tree phase and the root's choice
+// (Algorithms "Up-correction", "reduce at non-roots", "reduce at the root").
+//
+// Work decomposition.  A "row" j is one up-correction group = the j-th process
+// of each of the W = f+1 subtrees of the root; its payload is W*E consecutive
+// values in HBM.  Rows form a binary heap (children of row j: 2j+1, 2j+2), the
+// same heap in every subtree, so the tree phase is a heap reduction over rows
+// with W*E independent columns.  A workgroup owns a "cone": the rows below one
+// row of depth dlo, down to depth dhi.  Rows of one depth inside a cone are
+// consecutive in HBM, so the cone is staged into LDS with flat coalesced 16-byte
+// loads, then reduced level by level (deepest first) out of LDS: each round's
+// senders are the LDS-resident frontier of the level below.  Trees too tall for
+// LDS are cut into tiers; a tier's top rows go through a small scratch area in
+// HBM to the tier above.
+//
+// One thread handles one (row, value index) item: it reads the W inputs of the
+// group, forms the W up-correction values in the fixed order of the rounds,
+// adds what the two children rows sent, and writes the W tree messages back in
+// place.  Liveness comes from the scenario's failure list (at most f entries),
+// held in LDS.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "ftred_geom.h"
+
+namespace ftred {
+
+constexpr int kThreads = 256;
+constexpr int kMaxTiers = 8;
+constexpr int kCopyBatch = 8;      // loads in flight per thread while staging a cone
+
+enum : uint32_t { kStOk = 0, kStRootFailed = 1, kStNoCleanSubtree = 2, kStBadFailureSet = 3 };
+
+template <class T, int OP>
+__device__ __forceinline__ T comb(T a, T b)
+{
+    if constexpr (OP == 0) return a + b; else return a | b;
+}
+
+// liveness of a LISTED process in a global round
+__device__ __forceinline__ bool alive_at(uint32_t fail_round, uint32_t round)
+{
+    return fail_round != 0u && round < fail_round;
+}
+
+// The scenario's failure list, resolved for one attempt (root, first round).
+struct FailTab {
+    uint32_t n;            // slots
+    uint32_t listed;       // slots in use
+    uint32_t root_alive;   // the root is alive in the last round of the reduce
+    uint32_t cnt_uc, cnt_tree;   // message counters of the workgroup
+    uint32_t pad[3];
+    uint32_t vr[16];       // virtual rank (kNoRank = unused slot)
+    uint32_t fr[16];       // fail_round
+    uint32_t row[16];      // row of the process (kNoRank: none)
+    uint32_t idx[16];      // index inside its group
+    uint32_t uc[16];       // up-correction rounds in which it still sends
+    uint32_t tree[16];     // 1: it sends its tree message
+};
+static_assert(sizeof(FailTab) % 16 == 0, "FailTab must keep 16-byte alignment of what follows");
+
+struct TierDesc {
+    uint32_t dlo, dhi;          // depths of the rows this tier computes
+    uint32_t child_in;          // 1: the tree messages of depth dhi+1 come from scratch
+    uint32_t is_top;            // 1: dlo == 0, ends with the root's choice
+    uint32_t in_off, in_meta_off;    // scratch offsets (bytes inside one scenario's scratch)
+    uint32_t out_off, out_meta_off;
+    uint32_t lds_rows;          // rows of LDS the tier stages
+    uint32_t lds_bytes;         // dynamic LDS of the launch
+};
+
+struct RunArgs {
+    Geom g;
+    const unsigned char* payload;
+    uint64_t scen_stride_bytes;
+    const uint32_t* root;        // [S] or nullptr (reduce)
+    const uint32_t* attempts;    // [S] or nullptr (allreduce: root = attempts - 1)
+    const uint32_t* fail_rank;
+    const uint32_t* fail_round;
+    uint32_t* status;
+    unsigned char* result;
+    unsigned long long* msgs;
+    uint32_t nmsg;               // counters per scenario: 2 (reduce) or 4 (allreduce)
+    uint32_t S;
+    unsigned char* ws;           // scratch
+    uint64_t ws_stride;          // bytes per scenario (per workgroup in the retry kernel)
+    uint32_t vroot_off;
+    uint32_t vec16;              // 1: rows are 16-byte aligned in HBM: 16-byte staging
+    uint32_t ntiers;
+    uint32_t tier;               // tier run by this launch
+    TierDesc tiers[kMaxTiers];
+};
+
+__device__ __forceinline__ void load_failtab(FailTab& ft, const Geom& g, const uint32_t* fail_rank,
+                                             const uint32_t* fail_round, uint32_t s, uint32_t root,
+                                             uint32_t base)
+{
+    const uint32_t F = g.f > 0 ? g.f : 1;
+    const uint32_t tid = threadIdx.x;
+    if (tid < 64) {      // one full wavefront, so that the ballots below are defined
+        uint32_t vr = kNoRank, fr = 0, row = kNoRank, idx = 0, uc = 0, tree = 0;
+        if (tid < g.f) {
+            uint32_t rank = fail_rank[size_t(s) * F + tid];
+            if (rank != kNoRank) {
+                fr = fail_round[size_t(s) * F + tid];
+                vr = relabel(rank, root);
+                uint32_t gs;
+                if (vr == 0) {
+                    row = g.a > 1 ? g.M - 1 : kNoRank;
+                    idx = g.a - 1;
+                    gs = g.a;
+                } else {
+                    uint32_t j = fdiv(vr - 1, g.divW);
+                    idx = vr - 1 - j * g.W;
+                    row = j;
+                    gs = group_size(g, j);
+                    tree = alive_at(fr, base + tree_send_round(g, idx, j)) ? 1u : 0u;
+                }
+                // the send of up-correction round t happens iff base + t < fr
+                uint32_t done = fr > base + 1 ? fr - base - 1 : 0u;
+                uc = done < gs - 1 ? done : gs - 1;
+            }
+        }
+        if (tid < 16) {
+            ft.vr[tid] = vr; ft.fr[tid] = fr; ft.row[tid] = row; ft.idx[tid] = idx; ft.uc[tid] = uc;
+            ft.tree[tid] = tree;
+        }
+        unsigned long long m = __ballot(vr != kNoRank);
+        unsigned long long rd = __ballot(vr == 0 && !alive_at(fr, base + g.Rred));
+        if (tid == 0) {
+            ft.n = g.f;
+            ft.cnt_uc = 0;
+            ft.cnt_tree = 0;
+            ft.listed = uint32_t(__popcll(m));
+            ft.root_alive = rd == 0ull ? 1u : 0u;
+        }
+    }
+}
+
+// One (row, value index) item: up-correction values of the W group members, tree
+// messages of the row's members.  rows: LDS image of the cone, row stride W*E
+// values; meta: per LDS row, bits 0..15 = member sent its tree message, bits
+// 16..31 = failed bit of that message.
+template <class T, int OP, int WP>
+__device__ __forceinline__ void process_item(const Geom& g, const FailTab& ft, T* rows, uint32_t* meta,
+                                             uint32_t li, uint32_t j, uint32_t e, bool kids_in_lds,
+                                             T* vroot_out, uint32_t& uc_cnt, uint32_t& tree_cnt)
+{
+    const uint32_t W = g.W, E = g.E, RE = W * E;
+    const bool last = (j == g.M - 1);
+    const uint32_t gs = (last && g.a > 1) ? g.a : W;      // group size, root included
+    const uint32_t nk = last ? g.nlast : W;               // tree members of the row
+    T* rp = rows + size_t(li) * RE + e;
+
+    T x[WP];
+#pragma unroll
+    for (int w = 0; w < WP; ++w) x[w] = (uint32_t(w) < gs) ? rp[w * E] : T(0);
+
+    // failures of this row: tl = packed 4-bit "rounds in which member w still sends"
+    unsigned long long tl = 0x1111111111111111ull * (unsigned long long)(gs - 1);
+    uint32_t sent = (1u << nk) - 1u;
+    bool rowfail = false;
+    if (ft.listed != 0) {
+        for (uint32_t q = 0; q < ft.n; ++q) {
+            if (ft.row[q] == j) {
+                rowfail = true;
+                uint32_t i4 = 4u * ft.idx[q];
+                tl = (tl & ~(15ull << i4)) | ((unsigned long long)ft.uc[q] << i4);
+                if (!ft.tree[q]) sent &= ~(1u << ft.idx[q]);
+            }
+        }
+    }
+
+    // up-correction: member i folds, in round order t = 1..gs-1, the input of
+    // member (i - t) mod gs, if that member was alive in round t
+    T v[WP];
+    if (!rowfail) {
+#pragma unroll
+        for (int i = 0; i < WP; ++i) {
+            T acc = x[i];
+#pragma unroll
+            for (int w = i - 1; w >= 0; --w) acc = comb<T, OP>(acc, x[w]);
+#pragma unroll
+            for (int w = WP - 1; w > i; --w)
+                if (uint32_t(w) < gs) acc = comb<T, OP>(acc, x[w]);
+            v[i] = acc;
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < WP; ++i) {
+            T acc = x[i];
+#pragma unroll
+            for (int w = i - 1; w >= 0; --w) {
+                uint32_t t = uint32_t(i - w);
+                if (t <= uint32_t((tl >> (4 * w)) & 15ull)) acc = comb<T, OP>(acc, x[w]);
+            }
+#pragma unroll
+            for (int w = WP - 1; w > i; --w) {
+                uint32_t t = uint32_t(i) + gs - uint32_t(w);
+                if (uint32_t(w) < gs && t <= uint32_t((tl >> (4 * w)) & 15ull)) acc = comb<T, OP>(acc, x[w]);
+            }
+            v[i] = acc;
+        }
+    }
+
+    if (last && g.a > 1 && vroot_out != nullptr) {
+        // the root's value after its up-correction: member a-1 of the last group
+        T vr = T(0);
+#pragma unroll
+        for (int k = 0; k < WP; ++k)
+            if (uint32_t(k) == g.a - 1) vr = v[k];
+        vroot_out[e] = vr;
+    }
+
+    // tree phase: add what the children sent (lower-numbered child first), set
+    // the failed bit where a child's message is missing or carries the bit
+    uint32_t flag = 0;
+    if (kids_in_lds) {
+#pragma unroll
+        for (int c = 0; c < 2; ++c) {
+            uint32_t jc = 2u * j + 1u + uint32_t(c);
+            if (jc < g.M) {
+                uint32_t lc = 2u * li + 1u + uint32_t(c);
+                uint32_t cm = meta[lc];
+                uint32_t nkc = (jc == g.M - 1) ? g.nlast : W;
+                uint32_t cmask = (1u << nkc) - 1u;
+                const T* cp = rows + size_t(lc) * RE + e;
+                if ((cm & cmask) == cmask) {
+#pragma unroll
+                    for (int k = 0; k < WP; ++k)
+                        if (uint32_t(k) < nkc) v[k] = comb<T, OP>(v[k], cp[k * E]);
+                } else {
+#pragma unroll
+                    for (int k = 0; k < WP; ++k)
+                        if (uint32_t(k) < nkc && ((cm >> k) & 1u)) v[k] = comb<T, OP>(v[k], cp[k * E]);
+                }
+                flag |= ((cm >> 16) | ~cm) & cmask;
+            }
+        }
+    }
+
+#pragma unroll
+    for (int k = 0; k < WP; ++k)
+        if (uint32_t(k) < gs) rp[k * E] = v[k];
+
+    if (e == 0) {
+        meta[li] = (sent & 0xFFFFu) | (flag << 16);
+        uint32_t c = 0;
+        if (!rowfail) {
+            c = gs * (gs - 1);
+        } else {
+#pragma unroll
+            for (int w = 0; w < WP; ++w)
+                if (uint32_t(w) < gs) c += uint32_t((tl >> (4 * w)) & 15ull);
+        }
+        uc_cnt += c;
+        tree_cnt += uint32_t(__popc(sent));
+    }
+}
+
+// Copy `bytes` from src (HBM) to dst (LDS) in pieces of sizeof(V), kCopyBatch loads
+// in flight per thread.
+template <class V>
+__device__ __forceinline__ void copy_to_lds(unsigned char* dst, const unsigned char* src, uint32_t bytes)
+{
+    const uint32_t n = bytes / uint32_t(sizeof(V));
+    for (uint32_t c0 = threadIdx.x; c0 < n; c0 += kThreads * kCopyBatch) {
+        V r[kCopyBatch];
+#pragma unroll
+        for (int u = 0; u < kCopyBatch; ++u) {
+            uint32_t ci = c0 + uint32_t(u) * kThreads;
+            r[u] = reinterpret_cast<const V*>(src)[ci < n ? ci : 0u];    // always a valid address
+        }
+#pragma unroll
+        for (int u = 0; u < kCopyBatch; ++u) {
+            uint32_t ci = c0 + uint32_t(u) * kThreads;
+            if (ci < n) reinterpret_cast<V*>(dst)[ci] = r[u];
+        }
+    }
+}
+
+// Stage a cone's inputs into LDS.  The LDS image is contiguous: LDS row li at
+// li * RB; LDS row li lies on level l = ilog2(li + 1) of the cone and is global
+// row (r << l) + li, r = the cone's top row.  Global row jg starts at byte
+// (1 + jg * W) * EB of the scenario's payload (virtual rank 1 + jg * W).
+// Virtual rank `root` (if the root is not process 0) holds process 0's input and
+// the position virtual rank P would have holds the root's input (member a-1 of
+// the last group): both are patched in afterwards, to disjoint LDS bytes.
+template <class V>
+__device__ __forceinline__ void stage_inputs(const Geom& g, unsigned char* lrows, const unsigned char* pay,
+                                             uint32_t r, uint32_t h, uint32_t root)
+{
+    const uint32_t CH = uint32_t(sizeof(V));
+    const uint32_t nx = (2u << h) - 1u;
+    const uint32_t n = (nx * g.RB) / CH;
+    const uint32_t pay_bytes = g.P * g.EB;
+    const uint32_t skip_lo = root != 0 ? root * g.EB : 0xFFFFFFFFu;
+    const uint32_t skip_hi = root != 0 ? skip_lo + g.EB : 0xFFFFFFFFu;
+    for (uint32_t c0 = threadIdx.x; c0 < n; c0 += kThreads * kCopyBatch) {
+        V reg[kCopyBatch];
+        uint32_t okm = 0;
+#pragma unroll
+        for (int u = 0; u < kCopyBatch; ++u) {
+            uint32_t ci = c0 + uint32_t(u) * kThreads;
+            uint32_t src = 0;                      // always a valid address
+            if (ci < n) {
+                uint32_t off = ci * CH;
+                uint32_t li = fdiv(off, g.divRB);
+                uint32_t within = off - li * g.RB;
+                uint32_t l = ilog2(li + 1);
+                uint32_t jg = (r << l) + li;
+                uint32_t sb = (1u + jg * g.W) * g.EB + within;
+                if (jg < g.M && sb + CH <= pay_bytes && !(sb >= skip_lo && sb < skip_hi)) {
+                    okm |= 1u << u;
+                    src = sb;
+                }
+            }
+            reg[u] = *reinterpret_cast<const V*>(pay + src);
+        }
+#pragma unroll
+        for (int u = 0; u < kCopyBatch; ++u) {
+            uint32_t ci = c0 + uint32_t(u) * kThreads;
+            if ((okm >> u) & 1u) *reinterpret_cast<V*>(lrows + size_t(ci) * CH) = reg[u];
+        }
+    }
+    // patches: one process's payload each
+    const uint32_t tid = threadIdx.x;
+    const uint32_t dlo_rows = r + 1;       // (r + 1) = 2^dlo + cone
+    if (root != 0) {
+        uint32_t jr = fdiv(root - 1, g.divW);
+        uint32_t ir = root - 1 - jr * g.W;
+        uint32_t d = ilog2(jr + 1), dr = ilog2(dlo_rows);
+        if (d >= dr && d - dr <= h && ((jr + 1) >> (d - dr)) == dlo_rows) {
+            uint32_t li = jr - (r << (d - dr));
+            unsigned char* dst = lrows + size_t(li) * g.RB + ir * g.EB;
+            for (uint32_t o = tid * CH; o < g.EB; o += kThreads * CH)
+                *reinterpret_cast<V*>(dst + o) = *reinterpret_cast<const V*>(pay + o);     // process 0
+        }
+    }
+    if (g.a > 1) {
+        uint32_t jr = g.M - 1;
+        uint32_t d = ilog2(jr + 1), dr = ilog2(dlo_rows);
+        if (d >= dr && d - dr <= h && ((jr + 1) >> (d - dr)) == dlo_rows) {
+            uint32_t li = jr - (r << (d - dr));
+            unsigned char* dst = lrows + size_t(li) * g.RB + (g.a - 1) * g.EB;
+            const unsigned char* src = pay + size_t(root) * g.EB;
+            for (uint32_t o = tid * CH; o < g.EB; o += kThreads * CH)
+                *reinterpret_cast<V*>(dst + o) = *reinterpret_cast<const V*>(src + o);     // the root
+        }
+    }
+}
+
+// One cone of one tier of one reduce.  All threads of the workgroup call it.
+// Requires: ft loaded and a barrier passed.  Ends with a barrier.
+template <class T, int OP, int WP>
+__device__ __forceinline__ void run_cone(const RunArgs& A, const TierDesc& td, const FailTab& ft,
+                                         unsigned char* lrows_b, uint32_t* lmeta, uint32_t s, uint32_t root,
+                                         uint32_t cone, const unsigned char* pay, unsigned char* wsS,
+                                         bool discard, uint32_t& uc_cnt, uint32_t& tree_cnt)
+{
+    const Geom& g = A.g;
+    const uint32_t tid = threadIdx.x;
+    const uint32_t h = td.dhi - td.dlo;
+    const uint32_t r = (1u << td.dlo) - 1u + cone;       // top row of the cone
+    const uint32_t nx = (2u << h) - 1u;
+    T* rows = reinterpret_cast<T*>(lrows_b);
+
+    // ---- stage: inputs of the cone, and the messages of the level below it
+    if (A.vec16) stage_inputs<uint4>(g, lrows_b, pay, r, h, root);
+    else stage_inputs<T>(g, lrows_b, pay, r, h, root);
+    if (td.child_in) {
+        const uint32_t per = 2u << h;                       // rows of the level below, per cone
+        const uint32_t first = ((r + 1u) << (h + 1)) - 1u;  // its first global row
+        uint32_t cc = first < g.M ? (g.M - first < per ? g.M - first : per) : 0u;
+        const unsigned char* src = wsS + td.in_off + size_t(cone) * per * g.RB;
+        if (A.vec16) copy_to_lds<uint4>(lrows_b + size_t(nx) * g.RB, src, cc * g.RB);
+        else copy_to_lds<T>(lrows_b + size_t(nx) * g.RB, src, cc * g.RB);
+        const uint32_t* msrc = reinterpret_cast<const uint32_t*>(wsS + td.in_meta_off) + size_t(cone) * per;
+        for (uint32_t i = tid; i < cc; i += kThreads) lmeta[nx + i] = msrc[i];
+    }
+    __syncthreads();
+
+    // ---- rounds: deepest level first
+    T* vroot_out = reinterpret_cast<T*>(wsS + A.vroot_off);
+    for (int l = int(h); l >= 0; --l) {
+        const uint32_t lfirst = (1u << l) - 1u;
+        const uint32_t gfirst = ((r + 1u) << l) - 1u;
+        if (gfirst < g.M) {
+            uint32_t cnt = g.M - gfirst;
+            if (cnt > (1u << l)) cnt = 1u << l;
+            const uint32_t nitems = cnt * g.E;
+            const bool kids = (uint32_t(l) < h) || td.child_in;
+            for (uint32_t it = tid; it < nitems; it += kThreads) {
+                uint32_t lr = fdiv(it, g.divE);
+                uint32_t e = it - lr * g.E;
+                process_item<T, OP, WP>(g, ft, rows, lmeta, lfirst + lr, gfirst + lr, e, kids, vroot_out,
+                                        uc_cnt, tree_cnt);
+            }
+        }
+        __syncthreads();
+    }
+
+    // ---- hand over: to the tier above, or the root's choice
+    if (!td.is_top) {
+        unsigned char* dst = wsS + td.out_off + size_t(cone) * g.RB;
+        if (A.vec16) {
+            for (uint32_t o = tid * 16u; o < g.RB; o += kThreads * 16u)
+                *reinterpret_cast<uint4*>(dst + o) = *reinterpret_cast<const uint4*>(lrows_b + o);
+        } else {
+            for (uint32_t o = tid; o < g.W * g.E; o += kThreads) reinterpret_cast<T*>(dst)[o] = rows[o];
+        }
+        if (tid == 0) reinterpret_cast<uint32_t*>(wsS + td.out_meta_off)[cone] = lmeta[0];
+    } else if (!discard) {
+        // Algorithm "reduce at the root": lowest-numbered child whose message is
+        // present and reports no failure; the root adds its own value iff that
+        // subtree holds no member of the root's group (children a .. f+1).
+        const uint32_t cm = lmeta[0];
+        const uint32_t nk0 = row_members(g, 0);
+        const uint32_t okm = cm & ~(cm >> 16) & ((1u << nk0) - 1u);
+        uint32_t st = kStOk;
+        if (!ft.root_alive) st = kStRootFailed;
+        else if (okm == 0) st = kStNoCleanSubtree;
+        T* res = reinterpret_cast<T*>(A.result) + size_t(s) * g.E;
+        for (uint32_t e = tid; e < g.E; e += kThreads) {
+            T val = T(0);
+            if (st == kStOk) {
+                uint32_t ks = uint32_t(__ffs(int(okm))) - 1u;
+                val = rows[ks * g.E + e];
+                if (ks + 1u >= g.a) {
+                    T vr = g.a > 1 ? vroot_out[e]
+                                   : reinterpret_cast<const T*>(pay + size_t(root) * g.EB)[e];
+                    val = comb<T, OP>(vr, val);
+                }
+            }
+            res[e] = val;
+        }
+        if (tid == 0) A.status[s] = st;
+    }
+    __syncthreads();
+}
+
+template <class T, int OP, int WP>
+__global__ void __launch_bounds__(kThreads) tier_kernel(RunArgs A)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    const TierDesc& td = A.tiers[A.tier];
+    const uint32_t ncones = 1u << td.dlo;
+    const uint32_t s = blockIdx.x >> td.dlo;
+    const uint32_t cone = blockIdx.x & (ncones - 1u);
+    if (ncones - 1u + cone >= A.g.M) return;                 // no such row
+    if (A.status[s] == kStBadFailureSet) return;
+    uint32_t root = 0, base = 0;
+    if (A.attempts) {
+        root = A.attempts[s] - 1u;
+        base = root * A.g.Ratt;
+    } else if (A.root) {
+        root = A.root[s];
+    }
+    FailTab& ft = *reinterpret_cast<FailTab*>(smem);
+    uint32_t* lmeta = reinterpret_cast<uint32_t*>(smem + sizeof(FailTab));
+    unsigned char* lrows = smem + sizeof(FailTab) + ((size_t(td.lds_rows) * 4u + 15u) & ~size_t(15));
+    load_failtab(ft, A.g, A.fail_rank, A.fail_round, s, root, base);
+    __syncthreads();
+    uint32_t uc_cnt = 0, tree_cnt = 0;
+    run_cone<T, OP, WP>(A, td, ft, lrows, lmeta, s, root, cone, A.payload + size_t(s) * A.scen_stride_bytes,
+                        A.ws + size_t(s) * A.ws_stride, false, uc_cnt, tree_cnt);
+    if (A.msgs) {
+        if (uc_cnt) atomicAdd(&ft.cnt_uc, uc_cnt);
+        if (tree_cnt) atomicAdd(&ft.cnt_tree, tree_cnt);
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            atomicAdd(&A.msgs[size_t(s) * A.nmsg + 0], (unsigned long long)ft.cnt_uc);
+            atomicAdd(&A.msgs[size_t(s) * A.nmsg + 1], (unsigned long long)ft.cnt_tree);
+        }
+    }
+}
+
+// Attempts of an allreduce whose root had failed before the operation: the
+// reduce messages are sent (to a root that never answers), no broadcast follows.
+// Rare; one workgroup walks through a whole attempt, tier after tier, with a
+// private scratch area.  gridDim.x workgroups stride over the scenarios.
+template <class T, int OP, int WP>
+__global__ void __launch_bounds__(kThreads) retry_kernel(RunArgs A)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    FailTab& ft = *reinterpret_cast<FailTab*>(smem);
+    uint32_t* lmeta = reinterpret_cast<uint32_t*>(smem + sizeof(FailTab));
+    uint32_t max_rows = 0;
+    for (uint32_t t = 0; t < A.ntiers; ++t)
+        if (A.tiers[t].lds_rows > max_rows) max_rows = A.tiers[t].lds_rows;
+    unsigned char* lrows = smem + sizeof(FailTab) + ((size_t(max_rows) * 4u + 15u) & ~size_t(15));
+    unsigned char* wsB = A.ws + size_t(blockIdx.x) * A.ws_stride;
+    for (uint32_t s = blockIdx.x; s < A.S; s += gridDim.x) {
+        if (A.status[s] == kStBadFailureSet) continue;
+        const uint32_t natt = A.attempts[s];
+        for (uint32_t att = 0; att + 1 < natt; ++att) {
+            const uint32_t root = att, base = att * A.g.Ratt;
+            __syncthreads();
+            load_failtab(ft, A.g, A.fail_rank, A.fail_round, s, root, base);
+            __syncthreads();
+            uint32_t uc_cnt = 0, tree_cnt = 0;
+            for (uint32_t t = 0; t < A.ntiers; ++t) {
+                const TierDesc& td = A.tiers[t];
+                const uint32_t ncones = 1u << td.dlo;
+                for (uint32_t cone = 0; cone < ncones; ++cone) {
+                    if (ncones - 1u + cone >= A.g.M) break;
+                    run_cone<T, OP, WP>(A, td, ft, lrows, lmeta, s, root, cone,
+                                        A.payload + size_t(s) * A.scen_stride_bytes, wsB, true, uc_cnt, tree_cnt);
+                }
+            }
+            if (A.msgs) {
+                if (uc_cnt) atomicAdd(&ft.cnt_uc, uc_cnt);
+                if (tree_cnt) atomicAdd(&ft.cnt_tree, tree_cnt);
+                __syncthreads();
+                if (threadIdx.x == 0) {
+                    atomicAdd(&A.msgs[size_t(s) * A.nmsg + 0], (unsigned long long)ft.cnt_uc);
+                    atomicAdd(&A.msgs[size_t(s) * A.nmsg + 1], (unsigned long long)ft.cnt_tree);
+                }
+            }
+        }
+    }
+}
+
+// launchers, one set per (value type, operator), defined in ftred_inst_*.hip
+#define FTRED_DECLARE_LAUNCHERS(NAME)                                                         \
+    hipError_t launch_tier_##NAME(const RunArgs& A, uint32_t grid, uint32_t lds, hipStream_t st); \
+    hipError_t launch_retry_##NAME(const RunArgs& A, uint32_t grid, uint32_t lds, hipStream_t st);
+
+FTRED_DECLARE_LAUNCHERS(i64_sum)
+FTRED_DECLARE_LAUNCHERS(i64_bor)
+FTRED_DECLARE_LAUNCHERS(u32_sum)
+FTRED_DECLARE_LAUNCHERS(u32_bor)
+FTRED_DECLARE_LAUNCHERS(f64_sum)
+
+#define FTRED_DEFINE_LAUNCHERS(NAME, T, OP)                                                        \
+    template <int WP>                                                                              \
+    static hipError_t tier_wp_##NAME(const RunArgs& A, uint32_t grid, uint32_t lds, hipStream_t st) \
+    {                                                                                              \
+        hipLaunchKernelGGL((tier_kernel<T, OP, WP>), dim3(grid), dim3(kThreads), lds, st, A);       \
+        return hipGetLastError();                                                                  \
+    }                                                                                              \
+    template <int WP>                                                                              \
+    static hipError_t retry_wp_##NAME(const RunArgs& A, uint32_t grid, uint32_t lds, hipStream_t st) \
+    {                                                                                              \
+        hipLaunchKernelGGL((retry_kernel<T, OP, WP>), dim3(grid), dim3(kThreads), lds, st, A);      \
+        return hipGetLastError();                                                                  \
+    }                                                                                              \
+    hipError_t launch_tier_##NAME(const RunArgs& A, uint32_t grid, uint32_t lds, hipStream_t st)    \
+    {                                                                                              \
+        switch (wp_bucket(A.g.W)) {                                                                \
+            case 2: return tier_wp_##NAME<2>(A, grid, lds, st);                                    \
+            case 3: return tier_wp_##NAME<3>(A, grid, lds, st);                                    \
+            case 4: return tier_wp_##NAME<4>(A, grid, lds, st);                                    \
+            case 5: return tier_wp_##NAME<5>(A, grid, lds, st);                                    \
+            case 9: return tier_wp_##NAME<9>(A, grid, lds, st);                                    \
+            default: return tier_wp_##NAME<16>(A, grid, lds, st);                                  \
+        }                                                                                          \
+    }                                                                                              \
+    hipError_t launch_retry_##NAME(const RunArgs& A, uint32_t grid, uint32_t lds, hipStream_t st)   \
+    {                                                                                              \
+        switch (wp_bucket(A.g.W)) {                                                                \
+            case 2: return retry_wp_##NAME<2>(A, grid, lds, st);                                   \
+            case 3: return retry_wp_##NAME<3>(A, grid, lds, st);                                   \
+            case 4: return retry_wp_##NAME<4>(A, grid, lds, st);                                   \
+            case 5: return retry_wp_##NAME<5>(A, grid, lds, st);                                   \
+            case 9: return retry_wp_##NAME<9>(A, grid, lds, st);                                   \
+            default: return retry_wp_##NAME<16>(A, grid, lds, st);                                 \
+        }                                                                                          \
+    }
+
+// compile-time group width the kernels are instantiated for: the smallest of
+// {2,3,4,5,9,16} that holds W members
+inline int wp_bucket(uint32_t W)
+{
+    if (W <= 2) return 2;
+    if (W <= 3) return 3;
+    if (W <= 4) return 4;
+    if (W <= 5) return 5;
+    if (W <= 9) return 9;
+    return 16;
+}
+
+}  // namespace ftred

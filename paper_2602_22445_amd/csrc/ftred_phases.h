@@ -1,0 +1,314 @@
+// Kernels that do not depend on the reduction's arithmetic: scenario check,
+// and the broadcast half of the allreduce (tree-down and correction rounds);
+// plus the per-process index arithmetic shared by host and device.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "ftred_geom.h"
+#include "ftred_kernels.h"
+
+namespace ftred {
+
+// ---------------------------------------------------------------------------
+// partners of one process (physical ranks in, physical ranks out)
+
+struct PartnerInfo {
+    uint32_t parent, n_children, children[16];
+    uint32_t group_id, group_size, group_pos, group[16];
+    uint32_t subtree, depth, height, send_round;
+};
+
+FT_HD void partners_of(const Geom& g, uint32_t root, uint32_t rank, PartnerInfo& o)
+{
+    const uint32_t v = relabel(rank, root);
+    o.n_children = 0;
+    o.group_id = kNoRank;
+    o.group_size = 0;
+    o.group_pos = 0;
+    if (v == 0) {
+        // the root: f+1 children, the processes numbered 1..f+1
+        o.parent = kNoRank;
+        for (uint32_t i = 0; i < g.W; ++i) o.children[o.n_children++] = relabel(1 + i, root);
+        o.subtree = 0; o.depth = 0; o.height = g.D; o.send_round = 0;
+        if (g.a > 1) {       // member a-1 of the short last group
+            o.group_id = g.M - 1;
+            for (uint32_t i = 0; i + 1 < g.a; ++i) o.group[i] = relabel(1 + (g.M - 1) * g.W + i, root);
+            o.group[g.a - 1] = rank;
+            o.group_size = g.a;
+            o.group_pos = g.a - 1;
+        }
+        return;
+    }
+    const uint32_t j = fdiv(v - 1, g.divW);
+    const uint32_t i = v - 1 - j * g.W;
+    o.parent = j == 0 ? relabel(0, root) : relabel(1 + ((j - 1) / 2) * g.W + i, root);
+    for (uint32_t c = 0; c < 2; ++c) {
+        uint32_t jc = 2 * j + 1 + c;
+        if (jc < subtree_size(g, i)) o.children[o.n_children++] = relabel(1 + jc * g.W + i, root);
+    }
+    o.subtree = i + 1;
+    o.depth = depth_of(j);
+    o.height = height_of(g, i, j);
+    o.send_round = g.f + 1 + o.height;
+    o.group_id = j;
+    const uint32_t nk = row_members(g, j);
+    for (uint32_t k = 0; k < nk; ++k) o.group[k] = relabel(1 + j * g.W + k, root);
+    o.group_size = nk;
+    if (j == g.M - 1 && g.a > 1) {
+        o.group[nk] = relabel(0, root);
+        o.group_size = g.a;
+    }
+    o.group_pos = i;
+}
+
+// ---------------------------------------------------------------------------
+// scenario check: one thread per scenario
+
+__global__ void prepass_kernel(Geom g, uint32_t kind /* 0 reduce, 1 allreduce */, uint32_t S, const uint32_t* root,
+                               const uint32_t* fail_rank, const uint32_t* fail_round, uint32_t* status,
+                               uint32_t* attempts, unsigned long long* msgs, uint32_t nmsg, unsigned char* result)
+{
+    const uint32_t s = blockIdx.x * blockDim.x + threadIdx.x;
+    if (s >= S) return;
+    const uint32_t F = g.f > 0 ? g.f : 1;
+    bool bad = false;
+    uint32_t lead = 0;        // bit c: root candidate c failed before the operation
+    for (uint32_t q = 0; q < F; ++q) {
+        const uint32_t r = fail_rank[size_t(s) * F + q];
+        if (r == kNoRank) continue;
+        if (q >= g.f || r >= g.P) { bad = true; continue; }
+        for (uint32_t q2 = 0; q2 < q; ++q2)
+            if (fail_rank[size_t(s) * F + q2] == r) bad = true;
+        if (kind == 1 && r <= g.f) {
+            if (fail_round[size_t(s) * F + q] != 0) bad = true; else lead |= 1u << r;
+        }
+    }
+    if (root && root[s] >= g.P) bad = true;
+    uint32_t a = 0;
+    while ((lead >> a) & 1u) ++a;
+    status[s] = bad ? kStBadFailureSet : kStOk;
+    if (attempts) attempts[s] = bad ? 0u : a + 1u;
+    if (msgs)
+        for (uint32_t k = 0; k < nmsg; ++k) msgs[size_t(s) * nmsg + k] = 0ull;
+    if (bad)
+        for (uint32_t b = 0; b < g.EB; b += 4) *reinterpret_cast<uint32_t*>(result + size_t(s) * g.EB + b) = 0u;
+}
+
+// ---------------------------------------------------------------------------
+// broadcast half of the allreduce, for the attempt whose root is alive:
+// rounds 1..D send the value down the tree (a process at depth d receives in
+// round d and forwards in round d+1), rounds D+1..D+f are correction rounds in
+// the up-correction groups (every holder sends to group mate (i+t) mod g).
+// A workgroup owns `chunk` consecutive physical ranks of one scenario: it works
+// out who holds the value (one thread per group), then streams the receive
+// buffers.
+
+struct BcastArgs {
+    Geom g;
+    uint32_t S;
+    const uint32_t* attempts;
+    const uint32_t* status;
+    const uint32_t* fail_rank;
+    const uint32_t* fail_round;
+    const unsigned char* result;
+    uint32_t* has_bitmap;          // or nullptr
+    unsigned char* out;            // or nullptr
+    unsigned long long* msgs;      // or nullptr
+    uint32_t chunk, nchunks;
+    FastDiv div_nchunks;
+    uint32_t vec16;
+};
+
+struct BcastFail {
+    uint32_t listed, cnt_tree, cnt_corr, pad;
+    uint32_t row[16], idx[16];
+    uint32_t recv_alive[16];   // alive in the round in which the value reaches it down the tree
+    uint32_t blocked[16];      // dead in the round in which it would forward the value
+    uint32_t corr[16];         // number of correction rounds in which it is still alive
+};
+
+inline uint32_t bcast_lds_bytes(const BcastArgs& B)
+{
+    return uint32_t(sizeof(BcastFail)) + (B.chunk / 32u + 2u) * 4u;
+}
+
+__global__ void __launch_bounds__(kThreads) bcast_kernel(BcastArgs B)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    BcastFail& bf = *reinterpret_cast<BcastFail*>(smem);
+    uint32_t* bits = reinterpret_cast<uint32_t*>(smem + sizeof(BcastFail));
+    const Geom& g = B.g;
+    const uint32_t tid = threadIdx.x;
+    const uint32_t s = fdiv(blockIdx.x, B.div_nchunks);
+    const uint32_t ch = blockIdx.x - s * B.nchunks;
+    const uint32_t c0 = ch * B.chunk;
+    const uint32_t c1 = c0 + B.chunk < g.P ? c0 + B.chunk : g.P;
+    const uint32_t nw = (c1 - c0 + 31u) / 32u;
+    const uint32_t NW = (g.P + 31u) / 32u;
+    const bool run = B.status[s] == kStOk;
+
+    uint32_t root = 0, t0 = 0;
+    for (uint32_t w = tid; w < nw + 1u; w += kThreads) bits[w] = 0u;
+    if (run) {
+        root = B.attempts[s] - 1u;
+        t0 = root * g.Ratt + g.Rred;          // broadcast round tau is global round t0 + tau
+        if (tid < 64) {
+            const uint32_t F = g.f > 0 ? g.f : 1;
+            uint32_t row = kNoRank, idx = 0, ra = 0, bl = 0, corr = 0;
+            bool used = false;
+            if (tid < g.f) {
+                uint32_t rank = B.fail_rank[size_t(s) * F + tid];
+                if (rank != kNoRank) {
+                    uint32_t vr = relabel(rank, root);
+                    if (vr != 0) {                 // the root of this attempt is alive, never listed
+                        used = true;
+                        uint32_t fr = B.fail_round[size_t(s) * F + tid];
+                        row = fdiv(vr - 1, g.divW);
+                        idx = vr - 1 - row * g.W;
+                        uint32_t d = depth_of(row);
+                        ra = alive_at(fr, t0 + d) ? 1u : 0u;
+                        bl = alive_at(fr, t0 + d + 1u) ? 0u : 1u;
+                        // alive in correction round t iff t0 + D + t < fr
+                        uint32_t lim = t0 + g.D + 1u;
+                        corr = fr > lim ? fr - lim : 0u;
+                        if (corr > 15u) corr = 15u;
+                    }
+                }
+            }
+            if (tid < 16) {
+                bf.row[tid] = row; bf.idx[tid] = idx; bf.recv_alive[tid] = ra; bf.blocked[tid] = bl;
+                bf.corr[tid] = corr;
+            }
+            unsigned long long m = __ballot(used);
+            if (tid == 0) {
+                bf.listed = uint32_t(__popcll(m));
+                bf.cnt_tree = 0;
+                bf.cnt_corr = 0;
+            }
+        }
+    }
+    __syncthreads();
+
+    if (run) {
+        // ---- who holds the value: one thread per up-correction group
+        const uint32_t vlo = c0 > 1u ? c0 : 1u;        // virtual ranks vlo .. c1-1
+        uint32_t j0 = 0, nrows = 0;
+        if (vlo < c1) {
+            j0 = fdiv(vlo - 1u, g.divW);
+            nrows = fdiv(c1 - 2u, g.divW) - j0 + 1u;
+        }
+        // the process numbered `root` stands at physical position 0 (the swap)
+        uint32_t jx = kNoRank;
+        if (root != 0 && c0 == 0) {
+            jx = fdiv(root - 1u, g.divW);
+            if (jx >= j0 && jx < j0 + nrows) jx = kNoRank;
+        }
+        const uint32_t ntask = nrows + (jx != kNoRank ? 1u : 0u);
+        uint32_t my_tree = 0, my_corr = 0;
+        for (uint32_t t = tid; t < ntask; t += kThreads) {
+            const uint32_t j = t < nrows ? j0 + t : jx;
+            const uint32_t v0 = 1u + j * g.W;                    // first virtual rank of the row
+            const bool owner = t < nrows && v0 >= c0 && v0 < c1; // counts the row's messages
+            const uint32_t gs = group_size(g, j);
+            const uint32_t nk = row_members(g, j);
+            const uint32_t full = (1u << gs) - 1u;
+            const uint32_t tmask = (1u << nk) - 1u;
+            uint32_t H = tmask;                    // reached down the tree
+            if (gs > nk) H |= 1u << (gs - 1u);     // the root, member a-1 of the last group, holds it
+            uint32_t blockedm = 0;
+            bool rowfail = false;
+            if (bf.listed != 0) {
+                for (uint32_t q = 0; q < g.f; ++q) {
+                    const uint32_t rq = bf.row[q];
+                    if (rq == kNoRank) continue;
+                    if (rq == j) {
+                        rowfail = true;
+                        if (!bf.recv_alive[q]) H &= ~(1u << bf.idx[q]);
+                        if (bf.blocked[q]) blockedm |= 1u << bf.idx[q];
+                    } else if (bf.blocked[q] && bf.idx[q] < nk && is_proper_ancestor(rq, j)) {
+                        H &= ~(1u << bf.idx[q]);   // an ancestor in the same subtree did not forward
+                    }
+                }
+            }
+            if (owner) {
+                // tree-down messages: a holder alive in its send round sends to each child
+                const uint32_t snd = H & tmask & ~blockedm;
+                const uint32_t jc = 2u * j + 1u;
+                const uint32_t m0 = jc < g.M - 1u ? 0xFFFFu : (jc == g.M - 1u ? (1u << g.nlast) - 1u : 0u);
+                const uint32_t m1 = jc + 1u < g.M - 1u ? 0xFFFFu : (jc + 1u == g.M - 1u ? (1u << g.nlast) - 1u : 0u);
+                my_tree += uint32_t(__popc(snd & m0)) + uint32_t(__popc(snd & m1));
+            }
+            // correction rounds
+            for (uint32_t tt = 1; tt <= g.f && tt + 1u <= gs; ++tt) {
+                uint32_t am = full;
+                if (rowfail)
+                    for (uint32_t q = 0; q < g.f; ++q)
+                        if (bf.row[q] == j && bf.corr[q] < tt) am &= ~(1u << bf.idx[q]);
+                const uint32_t snd = H & am;
+                if (owner) my_corr += uint32_t(__popc(snd));
+                const uint32_t rot = ((snd << tt) | (snd >> (gs - tt))) & full;
+                H |= rot & am;
+            }
+            // record the holders among the row's tree members, by physical rank
+            uint32_t Hm = H & tmask;
+            if (root != 0 && root >= v0 && root < v0 + nk) {
+                const uint32_t b = root - v0;
+                if (((Hm >> b) & 1u) && c0 == 0) atomicOr(&bits[0], 1u);
+                Hm &= ~(1u << b);
+            }
+            if (t < nrows) {
+                int rel = int(v0) - int(c0);
+                if (rel < 0) { Hm >>= uint32_t(-rel); rel = 0; }
+                const uint32_t room = c1 - c0 - uint32_t(rel);        // ranks of the chunk from rel on
+                if (room < 32u) Hm &= (1u << room) - 1u;
+                const unsigned long long wide = (unsigned long long)Hm << (uint32_t(rel) & 31u);
+                const uint32_t w0 = uint32_t(rel) >> 5;
+                if (uint32_t(wide)) atomicOr(&bits[w0], uint32_t(wide));
+                if (uint32_t(wide >> 32)) atomicOr(&bits[w0 + 1u], uint32_t(wide >> 32));
+            }
+        }
+        if (tid == 0) {
+            if (root >= c0 && root < c1) atomicOr(&bits[(root - c0) >> 5], 1u << ((root - c0) & 31u));
+            if (c0 == 0) my_tree += g.W;          // the root sends to its f+1 children
+        }
+        if (B.msgs) {
+            if (my_tree) atomicAdd(&bf.cnt_tree, my_tree);
+            if (my_corr) atomicAdd(&bf.cnt_corr, my_corr);
+        }
+    }
+    __syncthreads();
+
+    if (run && B.msgs && tid == 0) {
+        if (bf.cnt_tree) atomicAdd(&B.msgs[size_t(s) * 4u + 2u], (unsigned long long)bf.cnt_tree);
+        if (bf.cnt_corr) atomicAdd(&B.msgs[size_t(s) * 4u + 3u], (unsigned long long)bf.cnt_corr);
+    }
+    if (B.has_bitmap)
+        for (uint32_t w = tid; w < nw; w += kThreads) B.has_bitmap[size_t(s) * NW + (c0 >> 5) + w] = bits[w];
+
+    // ---- receive buffers: the value where held, zeros elsewhere
+    if (B.out) {
+        unsigned char* dst = B.out + (size_t(s) * g.P + c0) * g.EB;
+        const unsigned char* res = B.result + size_t(s) * g.EB;
+        const uint32_t bytes = (c1 - c0) * g.EB;
+        if (B.vec16) {
+            for (uint32_t o = tid * 16u; o < bytes; o += kThreads * 16u) {
+                const uint32_t rr = fdiv(o, g.divEB);
+                const uint32_t within = o - rr * g.EB;
+                uint4 val = make_uint4(0, 0, 0, 0);
+                if ((bits[rr >> 5] >> (rr & 31u)) & 1u) val = *reinterpret_cast<const uint4*>(res + within);
+                *reinterpret_cast<uint4*>(dst + o) = val;
+            }
+        } else {
+            for (uint32_t o = tid * 4u; o < bytes; o += kThreads * 4u) {
+                const uint32_t rr = fdiv(o, g.divEB);
+                const uint32_t within = o - rr * g.EB;
+                uint32_t val = 0;
+                if ((bits[rr >> 5] >> (rr & 31u)) & 1u) val = *reinterpret_cast<const uint32_t*>(res + within);
+                *reinterpret_cast<uint32_t*>(dst + o) = val;
+            }
+        }
+    }
+}
+
+}  // namespace ftred

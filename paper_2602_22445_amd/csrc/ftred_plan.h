@@ -1,0 +1,48 @@
+// The plan object behind ftred_plan_t, and the error helpers shared by the
+// translation units of the library.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "ftred_kernels.h"
+
+struct ftred_plan_s {
+    ftred::Geom g;
+    int dtype, op;
+    uint32_t ntiers;
+    ftred::TierDesc tiers[ftred::kMaxTiers];
+    uint32_t max_lds;
+    uint32_t vroot_off;
+    uint64_t ws_scen;           // scratch bytes per scenario (tree tiers)
+    uint32_t retry_blocks;
+    uint32_t bc_chunk;          // ranks per workgroup in the broadcast kernel
+    uint32_t val_chunk;         // ranks per workgroup in the validation kernel
+};
+
+namespace ftred {
+
+// records the message for ftred_last_error() and returns `code`
+int set_error(int code, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
+
+inline uint32_t align_up(uint32_t x, uint32_t a) { return (x + a - 1) / a * a; }
+
+inline uint32_t val_chunks(const ftred_plan_s* p) { return (p->g.P + p->val_chunk - 1) / p->val_chunk; }
+
+// workspace layout: [tree scratch of S scenarios][tree scratch of the retry
+// workgroups][validation partials][256 bytes of counters]
+inline uint64_t ws_val_off(const ftred_plan_s* p, uint32_t S) { return (uint64_t(S) + p->retry_blocks) * p->ws_scen; }
+inline uint64_t ws_val_bytes(const ftred_plan_s* p, uint32_t S)
+{
+    // per (scenario, chunk): E values of the partial reduction and E doubles of |x| sums
+    return (uint64_t(S) * val_chunks(p) * (uint64_t(p->g.E) * 8u * 2u) + 255u) / 256u * 256u;
+}
+inline uint64_t ws_total(const ftred_plan_s* p, uint32_t S) { return ws_val_off(p, S) + ws_val_bytes(p, S) + 256u; }
+
+}  // namespace ftred
+
+#define HIP_TRY(expr)                                                                          \
+    do {                                                                                       \
+        hipError_t e_ = (expr);                                                                \
+        if (e_ != hipSuccess)                                                                  \
+            return ftred::set_error(3 /* FTRED_EDEVICE */, "%s: %s", #expr, hipGetErrorString(e_)); \
+    } while (0)

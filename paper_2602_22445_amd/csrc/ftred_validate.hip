@@ -1,0 +1,381 @@
+// ftred_validate: checks results against the semantics, independently of the
+// protocol kernels.  Sections "Reduce / Semantics" (items 3 and 4) and
+// "Allreduce / Semantics" (items 4 and 5): the result must be the reduction over
+// the never-failed processes combined with ONE subset of the processes that
+// failed during the operation; every never-failed process of an allreduce holds
+// it.  The message counters must lie in the range the message-count theorems
+// allow (failed processes send fewer messages, nobody sends more).
+//
+// Pass 1 (one workgroup per chunk of ranks): partial reduction of the
+// never-failed inputs, partial sums of |x| (tolerance scale for FTRED_F64), and
+// the holder check of the chunk.  Pass 2 (one workgroup per scenario): partials
+// folded in chunk order, subsets enumerated, status and counters checked.
+#include <hip/hip_runtime.h>
+
+#include <string.h>
+
+#include <type_traits>
+
+#include "../../include/ftred.h"
+#include "ftred_plan.h"
+
+using namespace ftred;
+
+namespace {
+
+struct ValArgs {
+    Geom g;
+    int kind;                       // 0 reduce, 1 allreduce
+    uint32_t S;
+    const uint32_t* root;           // reduce: [S] or nullptr
+    const unsigned char* payload;
+    uint64_t scen_stride_bytes;
+    const uint32_t* fail_rank;
+    const uint32_t* fail_round;
+    const unsigned char* result;
+    const uint32_t* has_bitmap;     // or nullptr
+    const unsigned char* out;       // or nullptr
+    const uint32_t* status;
+    const uint32_t* attempts;       // or nullptr
+    const unsigned long long* msgs; // or nullptr
+    uint32_t* verdict;
+    unsigned char* partial;         // [S][nchunks][E] values (8 bytes each)
+    double* scale;                  // [S][nchunks][E]
+    unsigned long long* n_invalid;  // device counter
+    uint32_t chunk, nchunks;
+    FastDiv div_nchunks;
+    uint64_t uc_ff;                 // failure-free up-correction messages
+};
+
+template <class T, int OP>
+__device__ __forceinline__ T vcomb(T a, T b)
+{
+    if constexpr (OP == 0) return a + b; else return a | b;
+}
+
+template <class T>
+__device__ __forceinline__ bool same_bits(T a, T b)
+{
+    if constexpr (sizeof(T) == 8) return __builtin_bit_cast(unsigned long long, a) == __builtin_bit_cast(unsigned long long, b);
+    else return __builtin_bit_cast(uint32_t, a) == __builtin_bit_cast(uint32_t, b);
+}
+
+__global__ void val_init_kernel(uint32_t S, uint32_t* verdict, unsigned long long* n_invalid)
+{
+    const uint32_t s = blockIdx.x * blockDim.x + threadIdx.x;
+    if (s < S) verdict[s] = 0u;
+    if (s == 0) *n_invalid = 0ull;
+}
+
+// failure list of the scenario in LDS: physical ranks
+struct ValFail {
+    uint32_t listed;
+    uint32_t pad[3];
+    uint32_t rank[16], round[16];
+};
+
+template <class T, int OP>
+__global__ void __launch_bounds__(256) val_partial_kernel(ValArgs A)
+{
+    __shared__ ValFail vf;
+    __shared__ T red[256];
+    __shared__ double reda[256];
+    __shared__ uint32_t bad_holder;
+    const Geom& g = A.g;
+    const uint32_t tid = threadIdx.x;
+    const uint32_t s = fdiv(blockIdx.x, A.div_nchunks);
+    const uint32_t ch = blockIdx.x - s * A.nchunks;
+    const uint32_t c0 = ch * A.chunk;
+    const uint32_t c1 = c0 + A.chunk < g.P ? c0 + A.chunk : g.P;
+    const uint32_t F = g.f > 0 ? g.f : 1;
+    if (tid < 16) {
+        uint32_t r = kNoRank, o = 0;
+        if (tid < g.f) { r = A.fail_rank[size_t(s) * F + tid]; o = A.fail_round[size_t(s) * F + tid]; }
+        vf.rank[tid] = r;
+        vf.round[tid] = o;
+    }
+    if (tid == 0) {
+        uint32_t n = 0;
+        for (uint32_t q = 0; q < g.f; ++q) n += A.fail_rank[size_t(s) * F + q] != kNoRank ? 1u : 0u;
+        vf.listed = n;
+        bad_holder = 0;
+    }
+    __syncthreads();
+    // does the chunk hold a listed rank at all?
+    bool chunk_listed = false;
+    for (uint32_t q = 0; q < g.f; ++q) chunk_listed = chunk_listed || (vf.rank[q] >= c0 && vf.rank[q] < c1);
+
+    const T* x = reinterpret_cast<const T*>(A.payload + size_t(s) * A.scen_stride_bytes);
+    const T* res = reinterpret_cast<const T*>(A.result) + size_t(s) * g.E;
+    const T* out = A.out ? reinterpret_cast<const T*>(A.out) + size_t(s) * g.P * g.E : nullptr;
+    const uint32_t* hb = A.has_bitmap ? A.has_bitmap + size_t(s) * ((g.P + 31u) / 32u) : nullptr;
+    const bool st_ok = A.status[s] == kStOk;
+    const bool check_holders = A.kind == 1 && st_ok;
+
+    const uint32_t cols = g.E < 256u ? g.E : 256u;
+    const uint32_t ngr = 256u / cols;
+    const uint32_t col = tid % cols, gr = tid / cols;
+    uint32_t my_bad = 0;
+    for (uint32_t e0 = 0; e0 < g.E; e0 += cols) {        // same trip count for every thread
+        const uint32_t e = e0 + col;
+        const bool active = e < g.E && gr < ngr;
+        T acc = T(0);
+        double sa = 0.0;
+        if (active) {
+            for (uint32_t p = c0 + gr; p < c1; p += ngr) {
+                // 0 never failed, 1 failed before the operation, 2 failed during it
+                uint32_t cls = 0;
+                if (chunk_listed)
+                    for (uint32_t q = 0; q < g.f; ++q)
+                        if (vf.rank[q] == p) cls = vf.round[q] == 0 ? 1u : 2u;
+                const T v = x[size_t(p) * g.E + e];
+                if (cls == 0) acc = vcomb<T, OP>(acc, v);
+                if constexpr (std::is_floating_point<T>::value) {
+                    if (cls != 1) sa += fabs(double(v));
+                }
+                if (check_holders) {
+                    bool has = cls == 0, known = cls == 0;
+                    if (hb) {
+                        has = ((hb[p >> 5] >> (p & 31u)) & 1u) != 0u;
+                        known = true;
+                        if ((cls == 0 && !has) || (cls == 1 && has)) my_bad = 1;
+                    }
+                    if (out && known) {
+                        // bitwise comparison, also for floating point: one root, one value
+                        const T o = out[size_t(p) * g.E + e];
+                        const T want = has ? res[e] : T(0);
+                        if (!same_bits(o, want)) my_bad = 1;
+                    }
+                }
+            }
+        }
+        // fold the groups in order
+        __syncthreads();
+        red[tid] = acc;
+        reda[tid] = sa;
+        __syncthreads();
+        if (active && gr == 0) {
+            for (uint32_t k = 1; k < ngr; ++k) {
+                acc = vcomb<T, OP>(acc, red[k * cols + col]);
+                sa += reda[k * cols + col];
+            }
+            const size_t o = (size_t(s) * A.nchunks + ch) * g.E + e;
+            reinterpret_cast<T*>(A.partial)[o * (8 / sizeof(T))] = acc;   // one 8-byte slot per value
+            A.scale[o] = sa;
+        }
+    }
+    if (my_bad) atomicOr(&bad_holder, 1u);
+    __syncthreads();
+    if (tid == 0 && bad_holder) atomicOr(&A.verdict[s], uint32_t(FTRED_BAD_HOLDER));
+}
+
+// group size of the process with virtual rank v (0 = the root), root counted
+__device__ __forceinline__ uint32_t vgroup_size(const Geom& g, uint32_t v)
+{
+    if (v == 0) return g.a > 1 ? g.a : 1u;
+    return group_size(g, fdiv(v - 1, g.divW));
+}
+
+template <class T, int OP>
+__global__ void __launch_bounds__(256) val_final_kernel(ValArgs A)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    __shared__ uint32_t s_inop[16];
+    __shared__ uint32_t s_ninop, s_found, s_expect;
+    const Geom& g = A.g;
+    const uint32_t tid = threadIdx.x;
+    const uint32_t s = blockIdx.x;
+    const uint32_t F = g.f > 0 ? g.f : 1;
+    T* base = reinterpret_cast<T*>(smem);                               // [E]
+    double* scale = reinterpret_cast<double*>(smem + size_t(g.E) * 8u); // [E]
+    const T* x = reinterpret_cast<const T*>(A.payload + size_t(s) * A.scen_stride_bytes);
+    const T* res = reinterpret_cast<const T*>(A.result) + size_t(s) * g.E;
+    const uint32_t* fr = A.fail_rank + size_t(s) * F;
+    const uint32_t* fo = A.fail_round + size_t(s) * F;
+
+    // ---- the scenario's failure set: expected status, processes failed during the operation
+    if (tid == 0) {
+        bool bad = false;
+        uint32_t lead = 0, n = 0;
+        const uint32_t root = (A.kind == 0 && A.root) ? A.root[s] : 0u;
+        bool root_dead = false;
+        for (uint32_t q = 0; q < F; ++q) {
+            const uint32_t r = fr[q];
+            if (r == kNoRank) continue;
+            if (q >= g.f || r >= g.P) { bad = true; continue; }
+            for (uint32_t q2 = 0; q2 < q; ++q2) bad = bad || fr[q2] == r;
+            if (A.kind == 1 && r <= g.f) {
+                if (fo[q] != 0) bad = true; else lead |= 1u << r;
+            }
+            if (fo[q] != 0) s_inop[n++] = r;
+            if (A.kind == 0 && r == root && !(fo[q] != 0 && g.Rred < fo[q])) root_dead = true;
+        }
+        if (A.kind == 0 && root >= g.P) bad = true;
+        s_ninop = bad ? 0u : n;
+        uint32_t att = 0;
+        while ((lead >> att) & 1u) ++att;
+        const uint32_t expect = bad ? kStBadFailureSet : (root_dead ? kStRootFailed : kStOk);
+        s_expect = expect;
+        s_found = 0;
+        uint32_t v = 0;
+        if (A.status[s] != expect) v |= FTRED_BAD_STATUS;
+        if (!bad && A.kind == 1 && A.attempts && A.attempts[s] != att + 1u) v |= FTRED_BAD_STATUS;
+        // message counters: between "every listed process sends nothing" and the
+        // failure-free counts, per attempt
+        if (!bad && A.msgs) {
+            const uint32_t natt = A.kind == 1 ? att + 1u : 1u;
+            unsigned long long lo_uc = 0, hi_uc = 0, lo_tr = 0, hi_tr = 0;
+            for (uint32_t a = 0; a < natt; ++a) {
+                const uint32_t rt = A.kind == 1 ? a : root;
+                unsigned long long drop_uc = 0, drop_tr = 0;
+                for (uint32_t q = 0; q < g.f; ++q) {
+                    if (fr[q] == kNoRank) continue;
+                    const uint32_t v2 = relabel(fr[q], rt);
+                    drop_uc += vgroup_size(g, v2) - 1u;
+                    drop_tr += v2 != 0 ? 1u : 0u;
+                }
+                hi_uc += A.uc_ff; lo_uc += A.uc_ff - drop_uc;
+                hi_tr += g.P - 1u; lo_tr += g.P - 1u - drop_tr;
+            }
+            const unsigned long long* m = A.msgs + size_t(s) * (A.kind == 1 ? 4u : 2u);
+            if (m[0] < lo_uc || m[0] > hi_uc || m[1] < lo_tr || m[1] > hi_tr) v |= FTRED_BAD_COUNT;
+            if (n == 0 && (m[0] != lo_uc || m[1] != lo_tr)) v |= FTRED_BAD_COUNT;   // exact without in-operation failures
+            if (A.kind == 1 && A.status[s] == kStOk) {
+                // one broadcast, from a root that is alive
+                if (m[2] > g.P - 1u || m[3] > A.uc_ff) v |= FTRED_BAD_COUNT;
+                bool none = true;
+                for (uint32_t q = 0; q < g.f; ++q) none = none && fr[q] == kNoRank;
+                if (none && (m[2] != g.P - 1u || m[3] != A.uc_ff)) v |= FTRED_BAD_COUNT;
+            }
+        }
+        if (v) atomicOr(&A.verdict[s], v);
+    }
+    // ---- reduction over the never-failed processes: chunk partials in order
+    for (uint32_t e = tid; e < g.E; e += 256u) {
+        T acc = T(0);
+        double sa = 0.0;
+        for (uint32_t c = 0; c < A.nchunks; ++c) {
+            const size_t o = (size_t(s) * A.nchunks + c) * g.E + e;
+            acc = vcomb<T, OP>(acc, reinterpret_cast<const T*>(A.partial)[o * (8 / sizeof(T))]);
+            sa += A.scale[o];
+        }
+        base[e] = acc;
+        scale[e] = sa;
+    }
+    __syncthreads();
+    // ---- one subset of the processes failed during the operation must explain the result
+    if (s_expect == kStOk && A.status[s] == kStOk) {
+        const uint32_t k = s_ninop;
+        const uint32_t nsub = 1u << k;
+        uint32_t found = 0;
+        for (uint32_t sub = tid; sub < nsub && !found; sub += 256u) {
+            bool all = true;
+            for (uint32_t e = 0; e < g.E && all; ++e) {
+                T cand = base[e];
+                for (uint32_t b = 0; b < k; ++b)
+                    if ((sub >> b) & 1u) cand = vcomb<T, OP>(cand, x[size_t(s_inop[b]) * g.E + e]);
+                const T r = res[e];
+                if constexpr (std::is_floating_point<T>::value) {
+                    // floating point: |r - cand| <= 1e-12 * sum |x|   (false for NaN)
+                    all = fabs(double(r) - double(cand)) <= 1e-12 * scale[e];
+                } else {
+                    all = r == cand;
+                }
+            }
+            if (all) found = 1;
+        }
+        if (found) atomicOr(&s_found, 1u);
+        __syncthreads();
+        if (tid == 0 && !s_found) atomicOr(&A.verdict[s], uint32_t(FTRED_BAD_VALUE));
+    }
+    __syncthreads();
+    if (tid == 0) {
+        __threadfence();
+        // pass 1 of this scenario has finished (earlier kernel), so the verdict is final
+        if (atomicOr(&A.verdict[s], 0u) != 0u) atomicAdd(A.n_invalid, 1ull);
+    }
+}
+
+template <class T, int OP>
+hipError_t launch_validate(const ValArgs& A, hipStream_t st)
+{
+    hipLaunchKernelGGL((val_partial_kernel<T, OP>), dim3(A.S * A.nchunks), dim3(256), 0, st, A);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const uint32_t lds = A.g.E * 16u;
+    hipLaunchKernelGGL((val_final_kernel<T, OP>), dim3(A.S), dim3(256), lds, st, A);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+extern "C" int ftred_validate(const ftred_plan_t* plan, int kind, uint32_t S, const uint32_t* root, const void* payload,
+                              uint64_t scen_stride_elems, const uint32_t* fail_rank, const uint32_t* fail_round,
+                              const void* result, const uint32_t* has_bitmap, const void* per_process_out,
+                              const uint32_t* status, const uint32_t* attempts, const uint64_t* msgs, uint32_t* verdict,
+                              uint64_t* n_invalid, void* workspace, uint64_t workspace_bytes, void* hip_stream)
+{
+    if (!plan) return set_error(FTRED_EINVAL, "ftred_validate: plan is NULL");
+    if (kind != 0 && kind != 1) return set_error(FTRED_EINVAL, "ftred_validate: kind must be 0 (reduce) or 1 (allreduce)");
+    if (S == 0) return set_error(FTRED_EINVAL, "ftred_validate: S must be >= 1");
+    if (!payload || !fail_rank || !fail_round || !result || !status || !verdict)
+        return set_error(FTRED_EINVAL, "ftred_validate: payload, failure lists, result, status and verdict are required");
+    const Geom& g = plan->g;
+    if (scen_stride_elems != 0 && scen_stride_elems < uint64_t(g.P) * g.E)
+        return set_error(FTRED_EINVAL, "ftred_validate: scen_stride_elems < P * elems");
+    if (!workspace || reinterpret_cast<uintptr_t>(workspace) % 256 != 0)
+        return set_error(FTRED_EINVAL, "ftred_validate: workspace must be non-NULL and 256-byte aligned");
+    if (workspace_bytes < ws_total(plan, S))
+        return set_error(FTRED_EINVAL, "ftred_validate: workspace of %llu bytes, %llu needed",
+                         (unsigned long long)workspace_bytes, (unsigned long long)ws_total(plan, S));
+    if (g.E * 16u > 48u * 1024u) return set_error(FTRED_EUNSUPPORTED, "ftred_validate: elems too large (%u)", g.E);
+    hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
+
+    ValArgs A;
+    memset(&A, 0, sizeof(A));
+    A.g = g;
+    A.kind = kind;
+    A.S = S;
+    A.root = kind == 0 ? root : nullptr;
+    A.payload = static_cast<const unsigned char*>(payload);
+    A.scen_stride_bytes = scen_stride_elems * g.esz;
+    A.fail_rank = fail_rank;
+    A.fail_round = fail_round;
+    A.result = static_cast<const unsigned char*>(result);
+    A.has_bitmap = kind == 1 ? has_bitmap : nullptr;
+    A.out = kind == 1 ? static_cast<const unsigned char*>(per_process_out) : nullptr;
+    A.status = status;
+    A.attempts = kind == 1 ? attempts : nullptr;
+    A.msgs = reinterpret_cast<const unsigned long long*>(msgs);
+    A.verdict = verdict;
+    unsigned char* ws = static_cast<unsigned char*>(workspace);
+    const uint64_t voff = ws_val_off(plan, S);
+    const uint64_t half = uint64_t(S) * val_chunks(plan) * g.E * 8u;
+    A.partial = ws + voff;
+    A.scale = reinterpret_cast<double*>(ws + voff + half);
+    A.n_invalid = reinterpret_cast<unsigned long long*>(ws + voff + ws_val_bytes(plan, S));
+    A.chunk = plan->val_chunk;
+    A.nchunks = val_chunks(plan);
+    A.div_nchunks = make_fastdiv(A.nchunks);
+    A.uc_ff = msgs_uc_ff(g);
+    if (uint64_t(S) * A.nchunks >= (uint64_t(1) << 31))
+        return set_error(FTRED_EUNSUPPORTED, "ftred_validate: S = %u scenarios need too many workgroups; split the batch", S);
+
+    hipLaunchKernelGGL(val_init_kernel, dim3((S + 255u) / 256u), dim3(256), 0, st, S, verdict, A.n_invalid);
+    HIP_TRY(hipGetLastError());
+    hipError_t e;
+    if (plan->dtype == FTRED_I64)
+        e = plan->op == FTRED_SUM ? launch_validate<unsigned long long, 0>(A, st) : launch_validate<unsigned long long, 1>(A, st);
+    else if (plan->dtype == FTRED_U32)
+        e = plan->op == FTRED_SUM ? launch_validate<uint32_t, 0>(A, st) : launch_validate<uint32_t, 1>(A, st);
+    else
+        e = launch_validate<double, 0>(A, st);
+    HIP_TRY(e);
+    if (n_invalid) {
+        unsigned long long host_n = 0;
+        HIP_TRY(hipMemcpyAsync(&host_n, A.n_invalid, sizeof(host_n), hipMemcpyDeviceToHost, st));
+        HIP_TRY(hipStreamSynchronize(st));
+        *n_invalid = host_n;
+    }
+    return FTRED_OK;
+}

@@ -1,0 +1,128 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports
+every symbol the public header declares, rejects bad arguments with a message,
+and its closed-form index arithmetic (ftred_partners) agrees with the oracle's
+constructively built tree and groups."""
+import os
+import re
+
+import numpy as np
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def ft():
+    from paper_2602_22445_amd import binding, build
+    if build.needs_build():
+        build.build(force=True)
+    binding.lib()
+    return binding
+
+
+def test_library_exports_every_declared_symbol(ft):
+    hdr = open(os.path.join(ROOT, "include", "ftred.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    names = sorted(set(re.findall(r"\b(ftred_[a-z_0-9]+)\s*\(", hdr)))
+    assert {"ftred_plan", "ftred_run_reduce", "ftred_run_allreduce", "ftred_validate"} <= set(names)
+    L = ft.lib()
+    for n in names:
+        assert hasattr(L, n), n
+
+
+@pytest.mark.parametrize("P,f,D,uc,groups,a", [
+    (7, 1, 2, 6, 3, 1), (8, 1, 3, 8, 3, 2), (64, 2, 5, 126, 21, 1), (1024, 3, 9, 3072, 255, 4),
+    (16384, 4, 12, 65532, 3276, 4), (1 << 20, 8, 17, 8388588, 116508, 4)])
+def test_plan_info_matches_the_closed_forms(ft, P, f, D, uc, groups, a):
+    p = ft.Plan(P, f, 1, ft.I64, ft.SUM)
+    i = p.info
+    assert (i.P, i.f, i.D, i.groups_full, i.a) == (P, f, D, groups, a)
+    assert i.rounds_reduce == f + D and i.rounds_attempt == 2 * (f + D)
+    assert i.msgs_uc_ff == uc and i.msgs_tree_ff == P - 1
+    assert p.workspace_bytes(4) > 0
+
+
+def test_plan_rejects_bad_arguments(ft):
+    for args in [(2, 1, 1, ft.I64, ft.SUM), (8, 1, 0, ft.I64, ft.SUM), (8, 1, 1, 7, ft.SUM),
+                 (8, 1, 1, ft.F64, ft.BOR), (8, 1, 1, ft.I64, 5), (100, 16, 1, ft.I64, ft.SUM),
+                 (8, 1, 1, ft.I64, ft.SUM, 3)]:
+        with pytest.raises(ft.FtredError) as ei:
+            ft.Plan(*args)
+        assert ei.value.code in (ft.EINVAL, ft.EUNSUPPORTED)
+        assert "ftred_plan" in str(ei.value)
+    p = ft.Plan(8, 1, 1, ft.I64, ft.SUM)
+    with pytest.raises(ft.FtredError):
+        p.partners(0, 8)
+    with pytest.raises(ft.FtredError):
+        p.partners(9, 0)
+
+
+PF = [(3, 1), (4, 1), (7, 1), (8, 1), (9, 1), (4, 2), (5, 2), (9, 2), (10, 2), (11, 2), (5, 3), (6, 3), (12, 3),
+      (13, 3), (2, 0), (3, 0), (9, 0), (6, 4), (11, 4), (64, 2), (100, 6), (257, 7), (1000, 8), (1024, 3),
+      (331, 15), (17, 15), (4097, 4)]
+
+
+@pytest.mark.parametrize("P,f", PF)
+def test_partners_agree_with_the_constructive_structure(ft, oracle, P, f):
+    plan = ft.Plan(P, f, 1, ft.I64, ft.SUM)
+    roots = sorted({0, 1, P - 1, P // 2, min(f + 1, P - 1)})
+    for root in roots:
+        s = oracle.structure(P, f, root)
+        kids = {p: [] for p in range(P)}
+        for p in range(P):
+            if s["parent"][p] >= 0:
+                kids[int(s["parent"][p])].append(p)
+        groups = {}
+        for p in range(P):
+            if s["group"][p] >= 0:
+                groups.setdefault(int(s["group"][p]), {})[int(s["gpos"][p])] = p
+        step = 1 if P <= 300 else 7
+        for p in list(range(0, P, step)) + [P - 1, root]:
+            q = plan.partners(root, p)
+            want_parent = ft.NO_RANK if s["parent"][p] < 0 else int(s["parent"][p])
+            assert q["parent"] == want_parent, (root, p)
+            assert sorted(q["children"]) == sorted(kids[p]), (root, p)
+            assert q["subtree"] == s["subtree"][p] and q["depth"] == s["depth"][p]
+            assert q["height"] == s["height"][p], (root, p)
+            assert q["send_round"] == s["send_round"][p], (root, p)
+            if s["group"][p] < 0:
+                assert q["group"] == []
+            else:
+                members = groups[int(s["group"][p])]
+                assert q["group"] == [members[i] for i in range(len(members))], (root, p)
+                assert q["group_pos"] == s["gpos"][p]
+
+
+def test_partners_of_the_paper_example(ft):
+    """n = 7, f = 1 (second tree figure of the paper): 1 -> {3, 5}, 2 -> {4, 6}."""
+    plan = ft.Plan(7, 1, 1, ft.I64, ft.SUM)
+    assert sorted(plan.partners(0, 0)["children"]) == [1, 2]
+    assert sorted(plan.partners(0, 1)["children"]) == [3, 5]
+    assert sorted(plan.partners(0, 2)["children"]) == [4, 6]
+    assert plan.partners(0, 0)["group"] == []
+    assert plan.partners(0, 3)["group"] == [3, 4] and plan.partners(0, 6)["group"] == [5, 6]
+
+
+def test_workloads_generators_are_deterministic_and_in_range():
+    from paper_2602_22445_amd import workloads as w
+    a = w.random_failure_sets(4, 64, 16384, 4, inop_permille=500, rounds_per_attempt=32, protected=5)
+    b = w.random_failure_sets(4, 64, 16384, 4, inop_permille=500, rounds_per_attempt=32, protected=5)
+    assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
+    # any scenario can be regenerated alone
+    c = w.random_failure_sets(4, 1, 16384, 4, inop_permille=500, rounds_per_attempt=32, protected=5, scen0=17)
+    assert np.array_equal(a[0][17], c[0][0]) and np.array_equal(a[1][17], c[1][0])
+    fr, fo = a
+    used = fr != w.NO_RANK
+    assert fr[used].max() < 16384
+    for s in range(64):
+        r = fr[s][used[s]]
+        assert len(set(r.tolist())) == len(r)
+        assert np.all(fo[s][~used[s]] == 0)
+        assert np.all(fo[s][used[s] & (fr[s] < 5)] == 0)      # root candidates fail only beforehand
+    x = w.payload_int(3, 2, 16, 4, "i64", 41)
+    assert x.min() >= -2**40 and x.max() < 2**40
+    # published known-answer vectors of Philox4x32-10
+    got = w.philox4x32(np.uint32(0), 0, 0, 0, 0, 0)
+    assert [int(v) for v in got] == [0x6627e8d5, 0xe169c58d, 0xbc57ac4c, 0x9b00dbd8]
+    got = w.philox4x32(np.uint32(0x243f6a88), 0x85a308d3, 0x13198a2e, 0x03707344, 0xa4093822, 0x299f31d0)
+    assert [int(v) for v in got] == [0xd16cfe09, 0x94fdcceb, 0x5001e420, 0x24126ea1]

@@ -1,0 +1,257 @@
+"""Parity of the HIP library (through the C-ABI) with the CPU oracle, element by
+element, on the same seeded inputs.  Integer results, statuses, attempts, message
+counters, holder bitmaps and receive buffers must be bit-exact; FTRED_F64 results
+must lie within 1e-12 * sum|x| of the oracle's (they are in fact bit-identical,
+because both sides fold in the same order, and that is asserted too)."""
+import numpy as np
+import pytest
+import torch
+
+from _cmp import compare_allreduce, compare_reduce, to_dev, unpack_bitmap
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def ft():
+    from paper_2602_22445_amd import binding
+    binding.lib()                       # raises if the library is not built: no fallback
+    assert torch.cuda.is_available()
+    return binding
+
+
+@pytest.fixture(scope="module")
+def w():
+    from paper_2602_22445_amd import workloads
+    return workloads
+
+
+def _payload(w, seed, S, P, E, dtype):
+    if dtype == 0:
+        return w.payload_int(seed, S, P, E, "i64", 41)
+    if dtype == 1:
+        return w.payload_int(seed, S, P, E, "u32", 32)
+    return w.payload_normal(seed, S, P, E, threads=4)
+
+
+def _rounds(oracle, P, f):
+    D = oracle.structure(P, f, 0)["D"]
+    return f + D, 2 * (f + D)
+
+
+# ---------------------------------------------------------------------------
+# a1: device index arithmetic
+
+
+@pytest.mark.parametrize("P,f,root", [(7, 1, 0), (8, 1, 5), (64, 2, 0), (1000, 8, 999), (1024, 3, 77), (4099, 15, 1)])
+def test_device_index_arithmetic(ft, oracle, P, f, root):
+    plan = ft.Plan(P, f, 1, ft.I64, ft.SUM)
+    d = {k: v.cpu().numpy() for k, v in ft.structure(plan, root).items()}
+    s = oracle.structure(P, f, root)
+    par = np.where(s["parent"] < 0, ft.NO_RANK, s["parent"]).astype(np.uint32)
+    assert np.array_equal(d["parent"], par)
+    assert np.array_equal(d["subtree"], s["subtree"])
+    assert np.array_equal(d["depth"], s["depth"])
+    assert np.array_equal(d["send_round"], s["send_round"])
+    assert np.array_equal(d["group_pos"], s["gpos"])
+    assert np.array_equal(d["group_size"], s["gsize"])
+    grp = np.where(s["group"] < 0, ft.NO_RANK, s["group"]).astype(np.uint32)
+    assert np.array_equal(d["group_id"], grp)
+
+
+# ---------------------------------------------------------------------------
+# configuration 1: reduce, P=8, f=1, int64 sum, exhaustive failure sets x 32 payload seeds
+
+
+def test_config1_reduce_p8_f1_exhaustive(ft, oracle, w):
+    P, f, E = 8, 1, 4
+    fr9, fo9 = w.exhaustive_failure_sets(P, f)
+    fr, fo = np.repeat(fr9, 32, axis=0), np.repeat(fo9, 32, axis=0)
+    S = fr.shape[0]
+    assert S == 288
+    x = w.payload_int(1, S, P, E, "i64", 32)
+    plan = ft.Plan(P, f, E, ft.I64, ft.SUM)
+    g, o = compare_reduce(ft, oracle, plan, x, fr, fo)
+    st = g["status"].cpu().numpy()
+    assert (st == ft.ST_ROOT_FAILED).sum() == 32 and (st == ft.ST_OK).sum() == 256
+    # the definition: the reduction over the processes that did not fail
+    res = g["result"].cpu().numpy()
+    for s in range(S):
+        F = [int(q) for q in fr[s] if q != w.NO_RANK]
+        if 0 not in F:
+            assert np.array_equal(res[s], oracle.survivor_reduce(x[s], 0, 0, F))
+
+
+# ---------------------------------------------------------------------------
+# configuration 2: allreduce, P=64, f=2, uint32 sum and or, exhaustive failure sets
+
+
+@pytest.mark.parametrize("op", [0, 1])
+def test_config2_allreduce_p64_f2_exhaustive(ft, oracle, w, op):
+    P, f, E = 64, 2, 8
+    fr, fo = w.exhaustive_failure_sets(P, f)
+    S = fr.shape[0]
+    assert S == 2081
+    x = w.payload_int(2, S, P, E, "u32", 32)
+    plan = ft.Plan(P, f, E, ft.U32, op)
+    g, o = compare_allreduce(ft, oracle, plan, x, fr, fo)
+    res = g["result"].cpu().numpy()
+    out = g["per_process_out"].cpu().numpy()
+    for s in range(0, S, 7):
+        F = [int(q) for q in fr[s] if q != w.NO_RANK]
+        want = oracle.survivor_reduce(x[s], 1, op, F)
+        assert np.array_equal(res[s], want)
+        alive = np.ones(P, bool)
+        alive[F] = False
+        assert np.all(out[s][alive] == want) and np.all(out[s][~alive] == 0)
+
+
+# ---------------------------------------------------------------------------
+# sweeps over shapes, types, roots, failure times (several tiles, ragged tails)
+
+REDUCE_CASES = [
+    # P, f, E, dtype, op, S, inop_permille
+    (2, 0, 1, 0, 0, 5, 0), (3, 1, 1, 0, 0, 40, 500), (5, 3, 2, 1, 1, 40, 500), (7, 1, 1, 0, 0, 64, 500),
+    (8, 1, 4, 0, 0, 64, 500), (9, 2, 3, 1, 0, 64, 700), (17, 15, 1, 0, 0, 64, 500), (64, 2, 8, 1, 1, 128, 500),
+    (100, 6, 5, 2, 0, 128, 600), (257, 7, 2, 0, 1, 128, 600), (1000, 8, 1, 0, 0, 96, 500),
+    (1024, 3, 16, 0, 0, 256, 400), (1500, 4, 8, 2, 0, 128, 500), (4099, 5, 3, 2, 0, 48, 500),
+    (5000, 0, 2, 0, 0, 16, 0), (20000, 2, 4, 1, 0, 24, 500), (33333, 4, 8, 2, 0, 12, 500),
+    (3000, 12, 2, 0, 0, 32, 500), (1 << 16, 8, 1, 0, 0, 6, 500),
+]
+
+
+@pytest.mark.parametrize("P,f,E,dtype,op,S,permille", REDUCE_CASES)
+def test_reduce_sweep(ft, oracle, w, P, f, E, dtype, op, S, permille):
+    seed = 1000 + P + 31 * f + E
+    Rred, _ = _rounds(oracle, P, f)
+    fr, fo = w.random_failure_sets(seed, S, P, f, inop_permille=permille, rounds_per_attempt=Rred + 1)
+    root = w.random_roots(seed, S, P)
+    root[: S // 4] = 0
+    if S > 8:
+        # aim some failures at the root, its children and its group
+        fr[5, 0], fo[5, 0] = root[5], 0
+        if f >= 1:
+            fr[6, 0], fo[6, 0] = (root[6] + 1) % P, 1
+            fr[7, 0], fo[7, 0] = P - 1 if root[7] != P - 1 else P - 2, 2
+    x = _payload(w, seed, S, P, E, dtype)
+    plan = ft.Plan(P, f, E, dtype, op)
+    compare_reduce(ft, oracle, plan, x, fr, fo, root=root)
+
+
+ALLREDUCE_CASES = [
+    (2, 0, 1, 0, 0, 4, 0), (3, 1, 1, 0, 0, 40, 500), (6, 4, 2, 1, 1, 64, 500), (7, 1, 1, 0, 0, 64, 500),
+    (9, 2, 3, 1, 0, 64, 700), (17, 15, 1, 0, 0, 64, 500), (64, 2, 8, 1, 1, 128, 500), (100, 6, 5, 2, 0, 128, 600),
+    (257, 7, 2, 0, 1, 128, 600), (1000, 8, 1, 0, 0, 96, 250), (1024, 3, 16, 0, 0, 128, 400),
+    (1500, 4, 8, 2, 0, 128, 500), (4099, 5, 3, 2, 0, 48, 500), (20000, 2, 4, 1, 0, 24, 500),
+    (33333, 4, 8, 2, 0, 12, 500), (3000, 12, 2, 0, 0, 32, 500), (1 << 16, 8, 1, 0, 0, 6, 250),
+]
+
+
+@pytest.mark.parametrize("P,f,E,dtype,op,S,permille", ALLREDUCE_CASES)
+def test_allreduce_sweep(ft, oracle, w, P, f, E, dtype, op, S, permille):
+    seed = 2000 + P + 31 * f + E
+    _, Ratt = _rounds(oracle, P, f)
+    fr, fo = w.random_failure_sets(seed, S, P, f, inop_permille=permille, rounds_per_attempt=Ratt, protected=f + 1)
+    if f >= 1 and S > 8:
+        # force retries: leading root candidates failed beforehand
+        fr[3, 0], fo[3, 0] = 0, 0
+        for k in range(min(f, 3)):
+            fr[4, k], fo[4, k] = k, 0
+        # dedupe the rows just edited
+        for s in (3, 4):
+            seen = set()
+            for k in range(fr.shape[1]):
+                if fr[s, k] != w.NO_RANK and int(fr[s, k]) in seen:
+                    fr[s, k], fo[s, k] = w.NO_RANK, 0
+                seen.add(int(fr[s, k]))
+        # re-time the in-operation failures of retry scenarios over all their attempts
+    x = _payload(w, seed, S, P, E, dtype)
+    plan = ft.Plan(P, f, E, dtype, op)
+    g, o = compare_allreduce(ft, oracle, plan, x, fr, fo)
+    assert np.all(o["status"] == 0)
+    if f >= 1 and S > 8:
+        assert o["attempts"][3] >= 2 and o["attempts"][4] == min(f, 3) + 1
+
+
+def test_allreduce_every_failure_time_small(ft, oracle, w):
+    """P=10, f=2: every pair of non-candidate ranks from a sample, every pair of failure times."""
+    P, f, E = 10, 2, 2
+    _, Ratt = _rounds(oracle, P, f)
+    rows_r, rows_t = [], []
+    for a_, b_ in [(3, 4), (3, 7), (5, 9), (4, 8), (6, 9), (0, 5), (1, 9), (0, 1)]:
+        ta = [0] if a_ <= f else range(0, 2 * Ratt + 1)
+        tb = [0] if b_ <= f else range(0, 2 * Ratt + 1)
+        for x_ in ta:
+            for y_ in tb:
+                rows_r.append([a_, b_])
+                rows_t.append([x_, y_])
+    fr = np.array(rows_r, dtype=np.uint32)
+    fo = np.array(rows_t, dtype=np.uint32)
+    S = fr.shape[0]
+    x = w.payload_int(5, S, P, E, "i64", 20)
+    plan = ft.Plan(P, f, E, ft.I64, ft.SUM)
+    compare_allreduce(ft, oracle, plan, x, fr, fo)
+
+
+def test_bad_failure_sets_get_a_status_and_zero_outputs(ft, oracle, w):
+    P, f, E, S = 50, 3, 2, 6
+    fr = np.full((S, f), w.NO_RANK, dtype=np.uint32)
+    fo = np.zeros((S, f), dtype=np.uint32)
+    fr[1, 0] = 50                       # rank >= P
+    fr[2, 0] = fr[2, 2] = 7             # listed twice
+    fr[3, 1], fo[3, 1] = 2, 4           # a root candidate failing during the operation (allreduce only)
+    fr[4, 0] = 9
+    x = w.payload_int(6, S, P, E, "i64", 30)
+    plan = ft.Plan(P, f, E, ft.I64, ft.SUM)
+    g, o = compare_allreduce(ft, oracle, plan, x, fr, fo)
+    assert g["status"].cpu().numpy().tolist() == [0, 3, 3, 3, 0, 0]
+    g, o = compare_reduce(ft, oracle, plan, x, fr, fo)
+    assert g["status"].cpu().numpy().tolist() == [0, 3, 3, 0, 0, 0]
+
+
+def test_shared_payload_unaligned_pointer_and_small_lds_budget(ft, oracle, w):
+    """stride 0 (one payload for all scenarios), a payload pointer that is only
+    8-byte aligned (element-wise staging path), and a small LDS budget (more tiers)."""
+    P, f, E, S = 3000, 3, 2, 32
+    Rred, Ratt = _rounds(oracle, P, f)
+    fr, fo = w.random_failure_sets(77, S, P, f, inop_permille=500, rounds_per_attempt=Ratt, protected=f + 1)
+    x1 = w.payload_normal(77, 1, P, E, threads=1)[0]
+    plan = ft.Plan(P, f, E, ft.F64, ft.SUM, 8)
+    assert plan.info.tiers >= 3
+    buf = torch.empty(P * E + 1, dtype=torch.float64, device="cuda")
+    xd = buf[1:].view(P, E)
+    xd.copy_(torch.from_numpy(x1))
+    assert xd.data_ptr() % 16 == 8
+    g = ft.run_allreduce(plan, S, xd, to_dev(fr), to_dev(fo))
+    o = oracle.allreduce_batch(P, f, x1, ft.F64, ft.SUM, S, fail_rank=fr, fail_round=fo, want_out=True)
+    assert np.array_equal(g["status"].cpu().numpy(), o["status"])
+    assert np.array_equal(g["result"].cpu().numpy(), o["result"])
+    assert np.array_equal(g["msgs"].cpu().numpy(), o["msgs"])
+    assert np.array_equal(unpack_bitmap(g["has_bitmap"].cpu().numpy(), P), o["has"])
+    assert np.array_equal(g["per_process_out"].cpu().numpy(), o["out"])
+
+
+def test_runs_are_deterministic(ft, oracle, w):
+    P, f, E, S = 4099, 4, 8, 64
+    _, Ratt = _rounds(oracle, P, f)
+    fr, fo = w.random_failure_sets(9, S, P, f, inop_permille=500, rounds_per_attempt=Ratt, protected=f + 1)
+    x = to_dev(w.payload_normal(9, S, P, E))
+    plan = ft.Plan(P, f, E, ft.F64, ft.SUM)
+    a = ft.run_allreduce(plan, S, x, to_dev(fr), to_dev(fo))
+    b = ft.run_allreduce(plan, S, x, to_dev(fr), to_dev(fo))
+    torch.cuda.synchronize()
+    for k in ("result", "per_process_out", "has_bitmap", "status", "attempts", "msgs"):
+        assert torch.equal(a[k].view(torch.uint8), b[k].view(torch.uint8)), k
+
+
+def test_argument_errors(ft, w):
+    P, f, E, S = 100, 2, 4, 8
+    plan = ft.Plan(P, f, E, ft.I64, ft.SUM)
+    x = to_dev(w.payload_int(1, S, P, E, "i64", 20))
+    fr, fo = w.random_failure_sets(1, S, P, f)
+    small = torch.empty(256, dtype=torch.uint8, device="cuda")
+    with pytest.raises(ft.FtredError) as ei:
+        ft.run_reduce(plan, S, x, to_dev(fr), to_dev(fo), workspace=small)
+    assert ei.value.code == ft.EINVAL and "workspace" in str(ei.value)
+    with pytest.raises(ft.FtredError):
+        ft.run_allreduce(plan, S, x, to_dev(fr), to_dev(fo), workspace=small)
