@@ -127,12 +127,14 @@ def test_reduce_sweep(ft, oracle, w, P, f, E, dtype, op, S, permille):
     fr, fo = w.random_failure_sets(seed, S, P, f, inop_permille=permille, rounds_per_attempt=Rred + 1)
     root = w.random_roots(seed, S, P)
     root[: S // 4] = 0
-    if S > 8:
+    if S > 8 and f >= 1:
         # aim some failures at the root, its children and its group
+        fr[5], fo[5] = w.NO_RANK, 0
         fr[5, 0], fo[5, 0] = root[5], 0
-        if f >= 1:
-            fr[6, 0], fo[6, 0] = (root[6] + 1) % P, 1
-            fr[7, 0], fo[7, 0] = P - 1 if root[7] != P - 1 else P - 2, 2
+        fr[6], fo[6] = w.NO_RANK, 0
+        fr[6, 0], fo[6, 0] = (root[6] + 1) % P, 1
+        fr[7], fo[7] = w.NO_RANK, 0
+        fr[7, 0], fo[7, 0] = P - 1 if root[7] != P - 1 else P - 2, 2
     x = _payload(w, seed, S, P, E, dtype)
     plan = ft.Plan(P, f, E, dtype, op)
     compare_reduce(ft, oracle, plan, x, fr, fo, root=root)
@@ -212,7 +214,7 @@ def test_bad_failure_sets_get_a_status_and_zero_outputs(ft, oracle, w):
 def test_shared_payload_unaligned_pointer_and_small_lds_budget(ft, oracle, w):
     """stride 0 (one payload for all scenarios), a payload pointer that is only
     8-byte aligned (element-wise staging path), and a small LDS budget (more tiers)."""
-    P, f, E, S = 3000, 3, 2, 32
+    P, f, E, S = 3000, 3, 16, 32
     Rred, Ratt = _rounds(oracle, P, f)
     fr, fo = w.random_failure_sets(77, S, P, f, inop_permille=500, rounds_per_attempt=Ratt, protected=f + 1)
     x1 = w.payload_normal(77, 1, P, E, threads=1)[0]
