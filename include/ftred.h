@@ -204,6 +204,28 @@ int ftred_gen_failures(const ftred_plan_t *plan, uint64_t seed, uint32_t S, uint
 int ftred_gen_payload_int(const ftred_plan_t *plan, uint64_t seed, uint32_t S, uint32_t scen0,
                           uint32_t bits, void *payload, void *hip_stream);
 
+/* Per-kernel timing with HIP events, for benchmarks: between ftred_timing_begin and
+   ftred_timing_end every kernel the library launches is bracketed by two events
+   recorded on the stream it is launched on (up to max_records launches; later ones
+   are not timed).  ftred_timing_end waits for the recorded events, adds up the
+   elapsed milliseconds and the number of launches per phase (arrays of
+   FTRED_PH_COUNT entries, host, either may be NULL), frees the events and switches
+   timing off.  Process-wide, not thread-safe; callers that time several streams
+   get the sum over them. */
+enum {
+    FTRED_PH_CHECK = 0,        /* scenario check */
+    FTRED_PH_RETRY = 1,        /* attempts with a failed root */
+    FTRED_PH_TREE_DEEP = 2,    /* up-correction + deepest tier of the tree phase (reads the payload) */
+    FTRED_PH_TREE_UPPER = 3,   /* upper tiers and the root's choice */
+    FTRED_PH_BCAST = 4,        /* broadcast: holders and receive buffers */
+    FTRED_PH_VAL_PARTIAL = 5,  /* validation pass 1 */
+    FTRED_PH_VAL_FINAL = 6,    /* validation pass 2 */
+    FTRED_PH_GEN = 7,          /* scenario / payload generation */
+    FTRED_PH_COUNT = 8
+};
+int ftred_timing_begin(uint32_t max_records);
+int ftred_timing_end(double *ms, uint64_t *launches);
+
 #ifdef __cplusplus
 }
 #endif

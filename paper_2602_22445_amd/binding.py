@@ -76,6 +76,8 @@ def lib():
                                      ctypes.POINTER(_u64), _vp, _u64, _vp]
         L.ftred_gen_failures.argtypes = [_vp, _u64, _u32, _u32, _u32, _u32, _u32, _vp, _vp, _vp, _vp]
         L.ftred_gen_payload_int.argtypes = [_vp, _u64, _u32, _u32, _u32, _vp, _vp]
+        L.ftred_timing_begin.argtypes = [_u32]
+        L.ftred_timing_end.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(_u64)]
         _lib = L
     return _lib
 
@@ -170,19 +172,24 @@ def run_reduce(plan, S, payload, fail_rank, fail_round, root=None, want_msgs=Tru
 
 
 def run_allreduce(plan, S, payload, fail_rank, fail_round, want_bitmap=True, want_out=True, want_msgs=True,
-                  workspace=None, out=None, stream=None):
-    """ftred_run_allreduce.  Returns dict(result, has_bitmap, per_process_out, status, attempts, msgs)."""
+                  workspace=None, out=None, buffers=None, stream=None):
+    """ftred_run_allreduce.  Returns dict(result, has_bitmap, per_process_out, status, attempts, msgs).
+    buffers: the dict of an earlier call, to write into the same tensors again."""
     stride = _payload_stride(plan, payload, S)
     _fail(plan, S, fail_rank, fail_round)
     dev = payload.device
     dt = TORCH_DTYPE[plan.dtype]
-    result = torch.empty((S, plan.elems), dtype=dt, device=dev)
-    status = torch.empty(S, dtype=torch.uint32, device=dev)
-    attempts = torch.empty(S, dtype=torch.uint32, device=dev)
-    bitmap = torch.empty((S, (plan.P + 31) // 32), dtype=torch.uint32, device=dev) if want_bitmap else None
-    if out is None and want_out:
-        out = torch.empty((S, plan.P, plan.elems), dtype=dt, device=dev)
-    msgs = torch.empty((S, 4), dtype=torch.uint64, device=dev) if want_msgs else None
+    if buffers is not None:
+        result, status, attempts = buffers["result"], buffers["status"], buffers["attempts"]
+        bitmap, out, msgs = buffers["has_bitmap"], buffers["per_process_out"], buffers["msgs"]
+    else:
+        result = torch.empty((S, plan.elems), dtype=dt, device=dev)
+        status = torch.empty(S, dtype=torch.uint32, device=dev)
+        attempts = torch.empty(S, dtype=torch.uint32, device=dev)
+        bitmap = torch.empty((S, (plan.P + 31) // 32), dtype=torch.uint32, device=dev) if want_bitmap else None
+        if out is None and want_out:
+            out = torch.empty((S, plan.P, plan.elems), dtype=dt, device=dev)
+        msgs = torch.empty((S, 4), dtype=torch.uint64, device=dev) if want_msgs else None
     ws = workspace if workspace is not None else plan.workspace(S, dev)
     _check(lib().ftred_run_allreduce(plan.handle, S, _ptr(payload), stride, _ptr(fail_rank), _ptr(fail_round),
                                      _ptr(result), _ptr(bitmap), _ptr(out), _ptr(status), _ptr(attempts),
@@ -191,12 +198,13 @@ def run_allreduce(plan, S, payload, fail_rank, fail_round, want_bitmap=True, wan
 
 
 def validate(plan, kind, S, payload, fail_rank, fail_round, result, status, root=None, has_bitmap=None,
-             per_process_out=None, attempts=None, msgs=None, workspace=None, count=True, stream=None):
+             per_process_out=None, attempts=None, msgs=None, workspace=None, count=True, verdict=None, stream=None):
     """ftred_validate.  Returns dict(verdict[S], n_invalid or None)."""
     stride = _payload_stride(plan, payload, S)
     _fail(plan, S, fail_rank, fail_round)
     dev = payload.device
-    verdict = torch.empty(S, dtype=torch.uint32, device=dev)
+    if verdict is None:
+        verdict = torch.empty(S, dtype=torch.uint32, device=dev)
     ws = workspace if workspace is not None else plan.workspace(S, dev)
     n = _u64(0)
     _check(lib().ftred_validate(plan.handle, kind, S, _ptr(root), _ptr(payload), stride, _ptr(fail_rank),
@@ -230,3 +238,19 @@ def gen_payload_int(plan, seed, S, bits, scen0=0, out=None, stream=None):
                                            _stream(stream)))
         done += n
     return out
+
+
+PHASES = ("check", "retry", "tree_deep", "tree_upper", "bcast", "val_partial", "val_final", "gen")
+
+
+def timing_begin(max_records=65536):
+    """ftred_timing_begin."""
+    _check(lib().ftred_timing_begin(max_records))
+
+
+def timing_end():
+    """ftred_timing_end.  Returns {phase: (milliseconds, launches)}."""
+    ms = (ctypes.c_double * len(PHASES))()
+    n = (_u64 * len(PHASES))()
+    _check(lib().ftred_timing_end(ms, n))
+    return {name: (float(ms[i]), int(n[i])) for i, name in enumerate(PHASES)}

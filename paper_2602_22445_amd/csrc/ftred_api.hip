@@ -34,6 +34,80 @@ int ftred::set_error(int code, const char* fmt, ...)
 extern "C" const char* ftred_last_error(void) { return g_err; }
 
 // ---------------------------------------------------------------------------
+// timing of kernel launches with event pairs
+
+namespace {
+struct TimingState {
+    bool on = false;
+    uint32_t cap = 0, used = 0;
+    hipEvent_t* ev = nullptr;      // 2 per record
+    int* phase = nullptr;
+    bool open = false;
+} g_tm;
+}  // namespace
+
+void ftred::tm_mark(int phase, hipStream_t st, bool start)
+{
+    if (!g_tm.on) return;
+    if (start) {
+        g_tm.open = false;
+        if (g_tm.used >= g_tm.cap) return;
+        if (hipEventRecord(g_tm.ev[2 * g_tm.used], st) != hipSuccess) return;
+        g_tm.phase[g_tm.used] = phase;
+        g_tm.open = true;
+    } else if (g_tm.open) {
+        (void)hipEventRecord(g_tm.ev[2 * g_tm.used + 1], st);
+        ++g_tm.used;
+        g_tm.open = false;
+    }
+}
+
+extern "C" int ftred_timing_begin(uint32_t max_records)
+{
+    if (g_tm.on) return fail(FTRED_EINVAL, "ftred_timing_begin: timing is already on");
+    if (max_records == 0 || max_records > (1u << 20)) return fail(FTRED_EINVAL, "ftred_timing_begin: max_records must be 1..2^20");
+    g_tm.ev = new (std::nothrow) hipEvent_t[2 * size_t(max_records)];
+    g_tm.phase = new (std::nothrow) int[max_records];
+    if (!g_tm.ev || !g_tm.phase) return fail(FTRED_ENOMEM, "ftred_timing_begin: out of host memory");
+    for (uint32_t i = 0; i < 2 * max_records; ++i) {
+        hipError_t e = hipEventCreate(&g_tm.ev[i]);
+        if (e != hipSuccess) {
+            for (uint32_t k = 0; k < i; ++k) (void)hipEventDestroy(g_tm.ev[k]);
+            delete[] g_tm.ev; delete[] g_tm.phase;
+            g_tm.ev = nullptr; g_tm.phase = nullptr;
+            return fail(FTRED_EDEVICE, "hipEventCreate: %s", hipGetErrorString(e));
+        }
+    }
+    g_tm.cap = max_records;
+    g_tm.used = 0;
+    g_tm.open = false;
+    g_tm.on = true;
+    return FTRED_OK;
+}
+
+extern "C" int ftred_timing_end(double* ms, uint64_t* launches)
+{
+    if (!g_tm.on) return fail(FTRED_EINVAL, "ftred_timing_end: timing is not on");
+    g_tm.on = false;
+    int rc = FTRED_OK;
+    if (ms) for (int i = 0; i < FTRED_PH_COUNT; ++i) ms[i] = 0.0;
+    if (launches) for (int i = 0; i < FTRED_PH_COUNT; ++i) launches[i] = 0;
+    for (uint32_t r = 0; r < g_tm.used; ++r) {
+        float t = 0.f;
+        hipError_t e = hipEventSynchronize(g_tm.ev[2 * r + 1]);
+        if (e == hipSuccess) e = hipEventElapsedTime(&t, g_tm.ev[2 * r], g_tm.ev[2 * r + 1]);
+        if (e != hipSuccess) { rc = fail(FTRED_EDEVICE, "ftred_timing_end: %s", hipGetErrorString(e)); break; }
+        if (ms) ms[g_tm.phase[r]] += double(t);
+        if (launches) launches[g_tm.phase[r]] += 1;
+    }
+    for (uint32_t i = 0; i < 2 * g_tm.cap; ++i) (void)hipEventDestroy(g_tm.ev[i]);
+    delete[] g_tm.ev; delete[] g_tm.phase;
+    g_tm.ev = nullptr; g_tm.phase = nullptr;
+    g_tm.cap = g_tm.used = 0;
+    return rc;
+}
+
+// ---------------------------------------------------------------------------
 // plan
 
 extern "C" int ftred_plan(ftred_plan_t** out, uint32_t P, uint32_t f, uint32_t elems, int dtype, int op,
@@ -280,9 +354,12 @@ extern "C" int ftred_run_reduce(const ftred_plan_t* plan, uint32_t S, const uint
     hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
     const Geom& g = plan->g;
 
-    hipLaunchKernelGGL(prepass_kernel, dim3((S + 255u) / 256u), dim3(256), 0, st, g, 0u, S, root, fail_rank, fail_round,
-                       status, static_cast<uint32_t*>(nullptr), reinterpret_cast<unsigned long long*>(msgs), 2u,
-                       static_cast<unsigned char*>(result));
+    {
+        TimedLaunch tl(FTRED_PH_CHECK, st);
+        hipLaunchKernelGGL(prepass_kernel, dim3((S + 255u) / 256u), dim3(256), 0, st, g, 0u, S, root, fail_rank,
+                           fail_round, status, static_cast<uint32_t*>(nullptr),
+                           reinterpret_cast<unsigned long long*>(msgs), 2u, static_cast<unsigned char*>(result));
+    }
     HIP_TRY(hipGetLastError());
 
     RunArgs A;
@@ -294,6 +371,7 @@ extern "C" int ftred_run_reduce(const ftred_plan_t* plan, uint32_t S, const uint
     A.nmsg = 2;
     for (uint32_t t = 0; t < plan->ntiers; ++t) {
         A.tier = t;
+        TimedLaunch tl(t == 0 ? FTRED_PH_TREE_DEEP : FTRED_PH_TREE_UPPER, st);
         HIP_TRY(dispatch_tier(plan, A, S << plan->tiers[t].dlo, plan->tiers[t].lds_bytes, st));
     }
     return FTRED_OK;
@@ -316,9 +394,12 @@ extern "C" int ftred_run_allreduce(const ftred_plan_t* plan, uint32_t S, const v
     hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
     const Geom& g = plan->g;
 
-    hipLaunchKernelGGL(prepass_kernel, dim3((S + 255u) / 256u), dim3(256), 0, st, g, 1u, S,
-                       static_cast<const uint32_t*>(nullptr), fail_rank, fail_round, status, attempts,
-                       reinterpret_cast<unsigned long long*>(msgs), 4u, static_cast<unsigned char*>(result));
+    {
+        TimedLaunch tl(FTRED_PH_CHECK, st);
+        hipLaunchKernelGGL(prepass_kernel, dim3((S + 255u) / 256u), dim3(256), 0, st, g, 1u, S,
+                           static_cast<const uint32_t*>(nullptr), fail_rank, fail_round, status, attempts,
+                           reinterpret_cast<unsigned long long*>(msgs), 4u, static_cast<unsigned char*>(result));
+    }
     HIP_TRY(hipGetLastError());
 
     RunArgs A;
@@ -334,11 +415,13 @@ extern "C" int ftred_run_allreduce(const ftred_plan_t* plan, uint32_t S, const v
         RunArgs R = A;
         R.ws = A.ws + uint64_t(S) * plan->ws_scen;
         uint32_t blocks = plan->retry_blocks < S ? plan->retry_blocks : S;
+        TimedLaunch tl(FTRED_PH_RETRY, st);
         HIP_TRY(dispatch_retry(plan, R, blocks, plan->max_lds, st));
     }
     // the attempt that succeeds
     for (uint32_t t = 0; t < plan->ntiers; ++t) {
         A.tier = t;
+        TimedLaunch tl(t == 0 ? FTRED_PH_TREE_DEEP : FTRED_PH_TREE_UPPER, st);
         HIP_TRY(dispatch_tier(plan, A, S << plan->tiers[t].dlo, plan->tiers[t].lds_bytes, st));
     }
     // broadcast down the tree and correction rounds
@@ -362,7 +445,10 @@ extern "C" int ftred_run_allreduce(const ftred_plan_t* plan, uint32_t S, const v
     if (uint64_t(S) * B.nchunks >= (uint64_t(1) << 31))
         return fail(FTRED_EUNSUPPORTED, "ftred_run_allreduce: S = %u scenarios need too many workgroups; split the batch", S);
     const uint32_t lds = bcast_lds_bytes(B);
-    hipLaunchKernelGGL(bcast_kernel, dim3(S * B.nchunks), dim3(kThreads), lds, st, B);
+    {
+        TimedLaunch tl(FTRED_PH_BCAST, st);
+        hipLaunchKernelGGL(bcast_kernel, dim3(S * B.nchunks), dim3(kThreads), lds, st, B);
+    }
     HIP_TRY(hipGetLastError());
     return FTRED_OK;
 }

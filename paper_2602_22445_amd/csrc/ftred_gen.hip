@@ -103,9 +103,12 @@ extern "C" int ftred_gen_failures(const ftred_plan_t* plan, uint64_t seed, uint3
     if (inop_permille > 0 && rounds_per_attempt == 0)
         return set_error(FTRED_EINVAL, "ftred_gen_failures: rounds_per_attempt must be >= 1 with failures during the operation");
     hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
-    hipLaunchKernelGGL(gen_failures_kernel, dim3((S + 127u) / 128u), dim3(128), 0, st, plan->g, uint32_t(seed),
-                       uint32_t(seed >> 32), S, scen0, inop_permille, rounds_per_attempt, protected_ranks, root_out,
-                       fail_rank, fail_round);
+    {
+        TimedLaunch tl(FTRED_PH_GEN, st);
+        hipLaunchKernelGGL(gen_failures_kernel, dim3((S + 127u) / 128u), dim3(128), 0, st, plan->g, uint32_t(seed),
+                           uint32_t(seed >> 32), S, scen0, inop_permille, rounds_per_attempt, protected_ranks,
+                           root_out, fail_rank, fail_round);
+    }
     HIP_TRY(hipGetLastError());
     return FTRED_OK;
 }
@@ -123,6 +126,7 @@ extern "C" int ftred_gen_payload_int(const ftred_plan_t* plan, uint64_t seed, ui
     const uint32_t nblk = (n + 1u) / 2u;
     hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
     dim3 grid((nblk + 255u) / 256u, S);
+    TimedLaunch tl(FTRED_PH_GEN, st);
     if (plan->dtype == FTRED_I64)
         hipLaunchKernelGGL(gen_payload_kernel<long long>, grid, dim3(256), 0, st, uint32_t(seed), uint32_t(seed >> 32),
                            scen0, n, nblk, bits, static_cast<long long*>(payload));

@@ -38,6 +38,14 @@ inline uint64_t ws_val_bytes(const ftred_plan_s* p, uint32_t S)
 }
 inline uint64_t ws_total(const ftred_plan_s* p, uint32_t S) { return ws_val_off(p, S) + ws_val_bytes(p, S) + 256u; }
 
+// event-pair timing of kernel launches (ftred_timing_begin / ftred_timing_end)
+void tm_mark(int phase, hipStream_t st, bool start);
+struct TimedLaunch {
+    int phase; hipStream_t st;
+    TimedLaunch(int ph, hipStream_t s) : phase(ph), st(s) { tm_mark(phase, st, true); }
+    ~TimedLaunch() { tm_mark(phase, st, false); }
+};
+
 }  // namespace ftred
 
 #define HIP_TRY(expr)                                                                          \

@@ -299,11 +299,17 @@ __global__ void __launch_bounds__(256) val_final_kernel(ValArgs A)
 template <class T, int OP>
 hipError_t launch_validate(const ValArgs& A, hipStream_t st)
 {
-    hipLaunchKernelGGL((val_partial_kernel<T, OP>), dim3(A.S * A.nchunks), dim3(256), 0, st, A);
+    {
+        TimedLaunch tl(FTRED_PH_VAL_PARTIAL, st);
+        hipLaunchKernelGGL((val_partial_kernel<T, OP>), dim3(A.S * A.nchunks), dim3(256), 0, st, A);
+    }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const uint32_t lds = A.g.E * 16u;
-    hipLaunchKernelGGL((val_final_kernel<T, OP>), dim3(A.S), dim3(256), lds, st, A);
+    {
+        TimedLaunch tl(FTRED_PH_VAL_FINAL, st);
+        hipLaunchKernelGGL((val_final_kernel<T, OP>), dim3(A.S), dim3(256), lds, st, A);
+    }
     return hipGetLastError();
 }
 
@@ -361,7 +367,10 @@ extern "C" int ftred_validate(const ftred_plan_t* plan, int kind, uint32_t S, co
     if (uint64_t(S) * A.nchunks >= (uint64_t(1) << 31))
         return set_error(FTRED_EUNSUPPORTED, "ftred_validate: S = %u scenarios need too many workgroups; split the batch", S);
 
-    hipLaunchKernelGGL(val_init_kernel, dim3((S + 255u) / 256u), dim3(256), 0, st, S, verdict, A.n_invalid);
+    {
+        TimedLaunch tl(FTRED_PH_VAL_FINAL, st);
+        hipLaunchKernelGGL(val_init_kernel, dim3((S + 255u) / 256u), dim3(256), 0, st, S, verdict, A.n_invalid);
+    }
     HIP_TRY(hipGetLastError());
     hipError_t e;
     if (plan->dtype == FTRED_I64)
