@@ -33,6 +33,8 @@ def main():
     ap.add_argument("--scenarios", type=int, default=4096)
     ap.add_argument("--lds-kib", type=int, default=0, help="LDS budget of the tree kernels (0 = default)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy (reference for HBM counters under rocprofv3)")
     ap.add_argument("--cpu-sample", type=int, default=1024, help="scenarios timed on the CPU oracle")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -85,6 +87,12 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    if args.calibrate_copy:
+        src = payload[:1024].view(torch.float32)          # 1 GiB read, 1 GiB written
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del dst
 
     # ---- timed region: exactly K steps, HIP events around every kernel launch
     ft.timing_begin(args.steps * 16)

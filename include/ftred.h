@@ -95,8 +95,10 @@ typedef struct ftred_info {
 /* Create a plan for P processes, failure bound f, `elems` values of `dtype` per
    process and reduction `op`.  Requires P >= f + 2 (the root needs f+1 children:
    definition of the I(f)-tree), f <= FTRED_MAX_F, elems >= 1, P * elems * size
-   < 2^31 bytes, no BOR on FTRED_F64.  flags: 0, or an LDS budget in KiB (8..60)
-   for the tree kernels' tiles.  Host call; no device work. */
+   < 2^31 bytes, no BOR on FTRED_F64.  flags: 0 for the defaults; tuning knobs of
+   the tree kernels otherwise: bits 0..7 = LDS budget in KiB of the deepest tier's
+   tiles (4..24), bits 8..11 = 1 + log2 of the tiles one workgroup walks through.
+   Host call; no device work. */
 int ftred_plan(ftred_plan_t **out, uint32_t P, uint32_t f, uint32_t elems, int dtype, int op, uint32_t flags);
 int ftred_plan_info(const ftred_plan_t *plan, ftred_info_t *info /* host, written */);
 void ftred_plan_destroy(ftred_plan_t *plan);

@@ -125,11 +125,14 @@ extern "C" int ftred_plan(ftred_plan_t** out, uint32_t P, uint32_t f, uint32_t e
     const uint32_t esz = dtype == FTRED_U32 ? 4u : 8u;
     if (uint64_t(P) * elems * esz >= (uint64_t(1) << 31))
         return fail(FTRED_EUNSUPPORTED, "ftred_plan: P * elems * size must stay below 2^31 bytes");
-    uint32_t budget = 40u * 1024u;
-    if (flags != 0) {
-        if (flags < 8 || flags > 60) return fail(FTRED_EINVAL, "ftred_plan: flags = LDS budget in KiB, 8..60");
-        budget = flags * 1024u;
+    uint32_t budget = 24u * 1024u, kwalk = 3;
+    if ((flags & 0xFFu) != 0) {
+        if ((flags & 0xFFu) < 4 || (flags & 0xFFu) > 24)
+            return fail(FTRED_EINVAL, "ftred_plan: flags bits 0..7 = LDS budget of the deepest tier in KiB, 4..24");
+        budget = (flags & 0xFFu) * 1024u;
     }
+    if (((flags >> 8) & 0xFu) != 0) kwalk = ((flags >> 8) & 0xFu) - 1u;
+    if ((flags >> 13) != 0) return fail(FTRED_EINVAL, "ftred_plan: unknown flag bits");
     ftred_plan_t* p = new (std::nothrow) ftred_plan_t;
     if (!p) return fail(FTRED_ENOMEM, "ftred_plan: out of host memory");
     memset(p, 0, sizeof(*p));
@@ -138,17 +141,26 @@ extern "C" int ftred_plan(ftred_plan_t** out, uint32_t P, uint32_t f, uint32_t e
     p->op = op;
     const Geom& g = p->g;
 
-    // tiers of the tree phase, deepest first
-    const uint32_t cap_rows = budget / (g.RB + 4u);
-    if (cap_rows < 3) {
+    // tiers of the tree phase, deepest first.  The deepest tier reads the payload
+    // and wants many workgroups per CU (small tiles); the upper tiers are small.
+    const uint32_t stage_rows = kStageBytes / g.RB;               // rows the prefetch registers hold
+    uint32_t cap0 = budget / (g.RB + 4u);
+    uint32_t cap1 = (56u * 1024u) / (g.RB + 4u);
+    if (cap0 > stage_rows) cap0 = stage_rows;
+    if (cap1 > 2u * stage_rows + 1u) cap1 = 2u * stage_rows + 1u;
+    if (cap0 < 1 || cap1 < 3) {
         delete p;
         return fail(FTRED_EUNSUPPORTED, "ftred_plan: one up-correction group (%u bytes) does not fit the LDS tile", g.RB);
     }
-    const uint32_t hcap0 = ilog2(cap_rows + 1u) - 1u;            // 2^(h+1) - 1 <= cap_rows
-    const uint32_t hcap1 = ilog2(cap_rows + 1u) - 2u;            // 2^(h+2) - 1 <= cap_rows
+    const uint32_t hcap0 = ilog2(cap0 + 1u) - 1u;            // 2^(h+1) - 1 <= cap0
+    const uint32_t hcap1 = ilog2(cap1 + 1u) - 2u;            // 2^(h+2) - 1 <= cap1
     uint32_t nt = 0;
+    // the wavefront kernel leaves some subtrees to the LDS-tile kernel, which must be
+    // able to stage a whole subtree of height kWaveH
+    p->use_wave = (g.L > uint32_t(kWaveH) && !(flags & 0x1000u) && ((2u << kWaveH) - 1u) <= cap0) ? 1u : 0u;
     {
         uint32_t h0 = hcap0 < g.L ? hcap0 : g.L;
+        if (p->use_wave) h0 = uint32_t(kWaveH);
         TierDesc& t = p->tiers[nt++];
         t.dlo = g.L - h0; t.dhi = g.L; t.child_in = 0;
         int d = int(t.dlo) - 1;
@@ -173,6 +185,8 @@ extern "C" int ftred_plan(ftred_plan_t** out, uint32_t P, uint32_t f, uint32_t e
         td.lds_rows = ((2u << h) - 1u) + (td.child_in ? (2u << h) : 0u);
         td.lds_bytes = uint32_t(sizeof(FailTab)) + align_up(td.lds_rows * 4u, 16) + td.lds_rows * g.RB;
         if (td.lds_bytes > p->max_lds) p->max_lds = td.lds_bytes;
+        td.kshift = td.dlo < kwalk ? td.dlo : kwalk;
+        td.gshift = td.dlo - td.kshift;
         if (t > 0) { td.in_off = p->tiers[t - 1].out_off; td.in_meta_off = p->tiers[t - 1].out_meta_off; }
         if (!td.is_top) {
             td.out_off = off;
@@ -180,6 +194,11 @@ extern "C" int ftred_plan(ftred_plan_t** out, uint32_t P, uint32_t f, uint32_t e
             td.out_meta_off = off;
             off += align_up((1u << td.dlo) * 4u, 16);
         }
+    }
+    if (p->use_wave) {
+        p->wl = make_wave_layout(g, p->tiers[0].dlo);
+        const uint32_t wshift = p->tiers[0].dlo - p->wl.slot_shift;
+        p->wave_gshift = wshift >= 2 ? wshift - 2u : 0u;
     }
     p->ws_scen = align_up(off, 256);
     p->retry_blocks = 64;
@@ -289,6 +308,37 @@ static hipError_t dispatch_tier(const ftred_plan_t* p, const RunArgs& A, uint32_
     return launch_tier_f64_sum(A, grid, lds, st);
 }
 
+static hipError_t dispatch_list(const ftred_plan_t* p, const RunArgs& A, uint32_t grid, uint32_t lds, hipStream_t st)
+{
+    if (p->dtype == FTRED_I64) return p->op == FTRED_SUM ? launch_list_i64_sum(A, grid, lds, st) : launch_list_i64_bor(A, grid, lds, st);
+    if (p->dtype == FTRED_U32) return p->op == FTRED_SUM ? launch_list_u32_sum(A, grid, lds, st) : launch_list_u32_bor(A, grid, lds, st);
+    return launch_list_f64_sum(A, grid, lds, st);
+}
+
+static hipError_t dispatch_wave(const ftred_plan_t* p, const RunArgs& A, uint32_t grid, hipStream_t st)
+{
+    if (p->dtype == FTRED_I64) return p->op == FTRED_SUM ? launch_wave_i64_sum(A, p->wl, grid, st) : launch_wave_i64_bor(A, p->wl, grid, st);
+    if (p->dtype == FTRED_U32) return p->op == FTRED_SUM ? launch_wave_u32_sum(A, p->wl, grid, st) : launch_wave_u32_bor(A, p->wl, grid, st);
+    return launch_wave_f64_sum(A, p->wl, grid, st);
+}
+
+// all tiers of one tree phase; `extra` = retry entries that ride along as extra scenarios
+static int launch_tiers(const ftred_plan_t* plan, RunArgs& A, uint32_t S, uint32_t extra, hipStream_t st)
+{
+    for (uint32_t t = 0; t < plan->ntiers; ++t) {
+        A.tier = t;
+        TimedLaunch tl(t == 0 ? FTRED_PH_TREE_DEEP : FTRED_PH_TREE_UPPER, st);
+        if (t == 0 && plan->use_wave) {
+            // pure subtrees: one wavefront each; the others: listed, then the general kernel
+            HIP_TRY(dispatch_wave(plan, A, (S + extra) << plan->wave_gshift, st));
+            uint64_t cap = (uint64_t(S) + extra) * (plan->g.f + 3u);
+            HIP_TRY(dispatch_list(plan, A, uint32_t(cap < 4096u ? cap : 4096u), plan->tiers[0].lds_bytes, st));
+        } else
+            HIP_TRY(dispatch_tier(plan, A, (S + extra) << plan->tiers[t].gshift, plan->tiers[t].lds_bytes, st));
+    }
+    return FTRED_OK;
+}
+
 static hipError_t dispatch_retry(const ftred_plan_t* p, const RunArgs& A, uint32_t grid, uint32_t lds, hipStream_t st)
 {
     if (p->dtype == FTRED_I64) return p->op == FTRED_SUM ? launch_retry_i64_sum(A, grid, lds, st) : launch_retry_i64_bor(A, grid, lds, st);
@@ -313,7 +363,7 @@ static int check_common(const char* who, const ftred_plan_t* plan, uint32_t S, c
         return fail(FTRED_EINVAL, "%s: workspace of %llu bytes, %llu needed", who, (unsigned long long)workspace_bytes,
                     (unsigned long long)ftred_workspace_bytes(plan, S));
     for (uint32_t t = 0; t < plan->ntiers; ++t)
-        if ((uint64_t(S) << plan->tiers[t].dlo) >= (uint64_t(1) << 31))
+        if (((uint64_t(S) + kRetrySlots) << plan->tiers[t].gshift) >= (uint64_t(1) << 31))
             return fail(FTRED_EUNSUPPORTED, "%s: S = %u scenarios need too many workgroups; split the batch", who, S);
     return FTRED_OK;
 }
@@ -335,6 +385,9 @@ static void fill_run_args(RunArgs& A, const ftred_plan_t* p, uint32_t S, const v
     A.vec16 = (g.EB % 16 == 0 && reinterpret_cast<uintptr_t>(payload) % 16 == 0 && A.scen_stride_bytes % 16 == 0) ? 1u : 0u;
     A.ntiers = p->ntiers;
     for (uint32_t t = 0; t < p->ntiers; ++t) A.tiers[t] = p->tiers[t];
+    A.fix_list = reinterpret_cast<uint32_t*>(A.ws + ws_fix_off(p, S));
+    A.fix_count = reinterpret_cast<uint32_t*>(A.ws + ws_ctr_off(p, S) + 12u);
+    A.fix_kshift = p->use_wave ? p->wl.slot_shift : 0u;
 }
 
 // ---------------------------------------------------------------------------
@@ -356,9 +409,12 @@ extern "C" int ftred_run_reduce(const ftred_plan_t* plan, uint32_t S, const uint
 
     {
         TimedLaunch tl(FTRED_PH_CHECK, st);
+        hipLaunchKernelGGL(zero_words_kernel, dim3(1), dim3(64), 0, st,
+                           reinterpret_cast<uint32_t*>(static_cast<unsigned char*>(workspace) + ws_ctr_off(plan, S) + 8u), 2u);
         hipLaunchKernelGGL(prepass_kernel, dim3((S + 255u) / 256u), dim3(256), 0, st, g, 0u, S, root, fail_rank,
                            fail_round, status, static_cast<uint32_t*>(nullptr),
-                           reinterpret_cast<unsigned long long*>(msgs), 2u, static_cast<unsigned char*>(result));
+                           reinterpret_cast<unsigned long long*>(msgs), 2u, static_cast<unsigned char*>(result),
+                           static_cast<uint32_t*>(nullptr), static_cast<uint32_t*>(nullptr));
     }
     HIP_TRY(hipGetLastError());
 
@@ -369,12 +425,7 @@ extern "C" int ftred_run_reduce(const ftred_plan_t* plan, uint32_t S, const uint
     A.result = static_cast<unsigned char*>(result);
     A.msgs = reinterpret_cast<unsigned long long*>(msgs);
     A.nmsg = 2;
-    for (uint32_t t = 0; t < plan->ntiers; ++t) {
-        A.tier = t;
-        TimedLaunch tl(t == 0 ? FTRED_PH_TREE_DEEP : FTRED_PH_TREE_UPPER, st);
-        HIP_TRY(dispatch_tier(plan, A, S << plan->tiers[t].dlo, plan->tiers[t].lds_bytes, st));
-    }
-    return FTRED_OK;
+    return launch_tiers(plan, A, S, 0, st);
 }
 
 // ---------------------------------------------------------------------------
@@ -394,11 +445,16 @@ extern "C" int ftred_run_allreduce(const ftred_plan_t* plan, uint32_t S, const v
     hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
     const Geom& g = plan->g;
 
+    unsigned char* wsb = static_cast<unsigned char*>(workspace);
+    uint32_t* retry_list = reinterpret_cast<uint32_t*>(wsb + ws_list_off(plan, S));
+    uint32_t* retry_count = reinterpret_cast<uint32_t*>(wsb + ws_ctr_off(plan, S) + 8u);
     {
         TimedLaunch tl(FTRED_PH_CHECK, st);
+        hipLaunchKernelGGL(zero_words_kernel, dim3(1), dim3(64), 0, st, retry_count, 2u);     // and the fix-list count
         hipLaunchKernelGGL(prepass_kernel, dim3((S + 255u) / 256u), dim3(256), 0, st, g, 1u, S,
                            static_cast<const uint32_t*>(nullptr), fail_rank, fail_round, status, attempts,
-                           reinterpret_cast<unsigned long long*>(msgs), 4u, static_cast<unsigned char*>(result));
+                           reinterpret_cast<unsigned long long*>(msgs), 4u, static_cast<unsigned char*>(result),
+                           retry_list, retry_count);
     }
     HIP_TRY(hipGetLastError());
 
@@ -409,21 +465,20 @@ extern "C" int ftred_run_allreduce(const ftred_plan_t* plan, uint32_t S, const v
     A.result = static_cast<unsigned char*>(result);
     A.msgs = reinterpret_cast<unsigned long long*>(msgs);
     A.nmsg = 4;
+    const uint32_t slots = g.f > 0 ? kRetrySlots : 0u;
+    A.retry_list = retry_list;
+    A.retry_count = retry_count;
+    A.retry_slots = slots;
+    A.retry_ws = wsb + ws_retry_off(plan, S);
 
-    // attempts whose root had failed beforehand (none in most batches): own scratch
+    // attempts whose root had failed beforehand run as extra "scenarios" of the tier
+    // launches; beyond kRetrySlots of them (unusual) the retry kernel takes over
     if (g.f > 0) {
-        RunArgs R = A;
-        R.ws = A.ws + uint64_t(S) * plan->ws_scen;
-        uint32_t blocks = plan->retry_blocks < S ? plan->retry_blocks : S;
         TimedLaunch tl(FTRED_PH_RETRY, st);
-        HIP_TRY(dispatch_retry(plan, R, blocks, plan->max_lds, st));
+        HIP_TRY(dispatch_retry(plan, A, plan->retry_blocks, plan->max_lds, st));
     }
-    // the attempt that succeeds
-    for (uint32_t t = 0; t < plan->ntiers; ++t) {
-        A.tier = t;
-        TimedLaunch tl(t == 0 ? FTRED_PH_TREE_DEEP : FTRED_PH_TREE_UPPER, st);
-        HIP_TRY(dispatch_tier(plan, A, S << plan->tiers[t].dlo, plan->tiers[t].lds_bytes, st));
-    }
+    rc = launch_tiers(plan, A, S, slots, st);
+    if (rc != FTRED_OK) return rc;
     // broadcast down the tree and correction rounds
     BcastArgs B;
     memset(&B, 0, sizeof(B));

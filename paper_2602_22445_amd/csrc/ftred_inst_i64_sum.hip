@@ -2,7 +2,9 @@
 // (all compile-time group widths); kept in a file of its own so that the
 // instantiations compile in parallel.
 #include "ftred_kernels.h"
+#include "ftred_wave.h"
 
 namespace ftred {
 FTRED_DEFINE_LAUNCHERS(i64_sum, unsigned long long, 0)
+FTRED_DEFINE_WAVE_LAUNCHER(i64_sum, unsigned long long, 0)
 }  // namespace ftred

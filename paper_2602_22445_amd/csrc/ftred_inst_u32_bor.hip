@@ -2,7 +2,9 @@
 // (all compile-time group widths); kept in a file of its own so that the
 // instantiations compile in parallel.
 #include "ftred_kernels.h"
+#include "ftred_wave.h"
 
 namespace ftred {
 FTRED_DEFINE_LAUNCHERS(u32_bor, uint32_t, 1)
+FTRED_DEFINE_WAVE_LAUNCHER(u32_bor, uint32_t, 1)
 }  // namespace ftred

@@ -28,7 +28,12 @@ namespace ftred {
 
 constexpr int kThreads = 256;
 constexpr int kMaxTiers = 8;
-constexpr int kCopyBatch = 8;      // loads in flight per thread while staging a cone
+constexpr int kCopyBatch = 8;           // loads in flight per thread in plain copies
+constexpr uint32_t kStageBytes = 24576; // most input bytes one cone stages (prefetch registers: 96 B per thread)
+constexpr uint32_t kRetrySlots = 64;    // failed attempts that run inside the tier launches
+
+// 16 bytes as a native vector (stays in registers where a struct type may not)
+typedef uint32_t vec16_t __attribute__((ext_vector_type(4)));
 
 enum : uint32_t { kStOk = 0, kStRootFailed = 1, kStNoCleanSubtree = 2, kStBadFailureSet = 3 };
 
@@ -68,6 +73,8 @@ struct TierDesc {
     uint32_t out_off, out_meta_off;
     uint32_t lds_rows;          // rows of LDS the tier stages
     uint32_t lds_bytes;         // dynamic LDS of the launch
+    uint32_t kshift;            // a workgroup walks through 2^kshift consecutive cones
+    uint32_t gshift;            // workgroups per scenario = 2^gshift = 2^(dlo - kshift)
 };
 
 struct RunArgs {
@@ -89,6 +96,15 @@ struct RunArgs {
     uint32_t vec16;              // 1: rows are 16-byte aligned in HBM: 16-byte staging
     uint32_t ntiers;
     uint32_t tier;               // tier run by this launch
+    const uint32_t* retry_list;  // pairs (scenario, attempt) of attempts whose root had failed, or nullptr
+    const uint32_t* retry_count; // entries in retry_list
+    uint32_t retry_slots;        // entries run by the tier launches (the rest by the retry kernel)
+    uint32_t pad0;
+    unsigned char* retry_ws;     // scratch of the retry entries, ws_stride bytes each
+    uint32_t* fix_list;          // pairs (scenario or S + retry entry, first cone): subtrees of the deepest
+    uint32_t* fix_count;         //   tier left to the general kernel by the wavefront kernel
+    uint32_t fix_kshift;         // cones per entry = 2^fix_kshift
+    uint32_t pad1;
     TierDesc tiers[kMaxTiers];
 };
 
@@ -145,7 +161,7 @@ __device__ __forceinline__ void load_failtab(FailTab& ft, const Geom& g, const u
 template <class T, int OP, int WP>
 __device__ __forceinline__ void process_item(const Geom& g, const FailTab& ft, T* rows, uint32_t* meta,
                                              uint32_t li, uint32_t j, uint32_t e, bool kids_in_lds,
-                                             T* vroot_out, uint32_t& uc_cnt, uint32_t& tree_cnt)
+                                             bool check_fail, T* vroot_out, uint32_t& uc_cnt, uint32_t& tree_cnt)
 {
     const uint32_t W = g.W, E = g.E, RE = W * E;
     const bool last = (j == g.M - 1);
@@ -161,7 +177,7 @@ __device__ __forceinline__ void process_item(const Geom& g, const FailTab& ft, T
     unsigned long long tl = 0x1111111111111111ull * (unsigned long long)(gs - 1);
     uint32_t sent = (1u << nk) - 1u;
     bool rowfail = false;
-    if (ft.listed != 0) {
+    if (check_fail) {
         for (uint32_t q = 0; q < ft.n; ++q) {
             if (ft.row[q] == j) {
                 rowfail = true;
@@ -259,6 +275,13 @@ __device__ __forceinline__ void process_item(const Geom& g, const FailTab& ft, T
     }
 }
 
+// Workgroup barrier that orders LDS traffic only: prefetch loads of the next cone
+// stay in flight across it (a full __syncthreads would wait for them).
+__device__ __forceinline__ void lds_barrier()
+{
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
 // Copy `bytes` from src (HBM) to dst (LDS) in pieces of sizeof(V), kCopyBatch loads
 // in flight per thread.
 template <class V>
@@ -280,109 +303,138 @@ __device__ __forceinline__ void copy_to_lds(unsigned char* dst, const unsigned c
     }
 }
 
-// Stage a cone's inputs into LDS.  The LDS image is contiguous: LDS row li at
-// li * RB; LDS row li lies on level l = ilog2(li + 1) of the cone and is global
-// row (r << l) + li, r = the cone's top row.  Global row jg starts at byte
-// (1 + jg * W) * EB of the scenario's payload (virtual rank 1 + jg * W).
-// Virtual rank `root` (if the root is not process 0) holds process 0's input and
-// the position virtual rank P would have holds the root's input (member a-1 of
-// the last group): both are patched in afterwards, to disjoint LDS bytes.
+// Staging of a cone's inputs through registers, so that the loads of the next
+// cone are in flight while the current one is reduced.
+//
+// The LDS image of a cone is contiguous: LDS row li at li * RB; LDS row li lies on
+// level l = ilog2(li + 1) of the cone and is global row (r << l) + li, r = the
+// cone's top row = 2^dlo - 1 + cone.  Global row jg starts at byte (1 + jg*W)*EB of
+// the scenario's payload (virtual rank 1 + jg*W).  So the source offset of a chunk
+// is  base + cone * step  with per-chunk constants base, step = RB << l.
+// Rows >= M start at or beyond P*EB, so one clip against the payload size covers
+// missing rows and the short last row.  Virtual rank `root` (when the root is not
+// process 0) and the position virtual rank P would have (the root as member a-1 of
+// the last group) are patched in afterwards.
 template <class V>
-__device__ __forceinline__ void stage_inputs(const Geom& g, unsigned char* lrows, const unsigned char* pay,
-                                             uint32_t r, uint32_t h, uint32_t root)
+struct Stage {
+    static constexpr int NB = int(kStageBytes / (sizeof(V) * kThreads));
+    V reg[NB];
+    uint32_t base[NB];
+    uint32_t step[NB];
+    uint32_t okm_lo, okm_hi;      // chunk u was loaded
+
+    __device__ __forceinline__ void init(const Geom& g, uint32_t dlo, uint32_t h)
+    {
+        const uint32_t CH = uint32_t(sizeof(V));
+        const uint32_t n = (((2u << h) - 1u) * g.RB) / CH;
+        const uint32_t top0 = (1u << dlo) - 1u;
+#pragma unroll
+        for (int u = 0; u < NB; ++u) {
+            const uint32_t ci = threadIdx.x + uint32_t(u) * kThreads;
+            uint32_t b = 0xFFFFFFFFu, st = 0u;         // never passes the clip
+            if (ci < n) {
+                const uint32_t off = ci * CH;
+                const uint32_t li = fdiv(off, g.divRB);
+                const uint32_t l = ilog2(li + 1u);
+                b = (1u + ((top0 << l) + li) * g.W) * g.EB + (off - li * g.RB);
+                st = g.RB << l;
+            }
+            base[u] = b;
+            step[u] = st;
+        }
+        okm_lo = okm_hi = 0;
+    }
+
+    __device__ __forceinline__ void issue(const Geom& g, const unsigned char* pay, uint32_t cone, uint32_t root)
+    {
+        const uint32_t CH = uint32_t(sizeof(V));
+        const uint32_t pay_bytes = g.P * g.EB;
+        const uint32_t skip_lo = root != 0 ? root * g.EB : 0xFFFFFFFFu;
+        unsigned long long okm = 0;
+#pragma unroll
+        for (int u = 0; u < NB; ++u) {
+            const uint32_t sb = base[u] + cone * step[u];
+            // base = 0xFFFFFFFF marks "no chunk"; real offsets stay below 2^32 - CH
+            const bool ok = base[u] != 0xFFFFFFFFu && sb + CH <= pay_bytes && (sb - skip_lo >= g.EB);
+            reg[u] = *reinterpret_cast<const V*>(pay + (ok ? sb : 0u));    // always a valid address
+            okm |= (unsigned long long)(ok ? 1u : 0u) << u;
+        }
+        okm_lo = uint32_t(okm);
+        okm_hi = uint32_t(okm >> 32);
+    }
+
+    __device__ __forceinline__ void commit(unsigned char* lrows) const
+    {
+        const uint32_t CH = uint32_t(sizeof(V));
+        const unsigned long long okm = (unsigned long long)okm_lo | ((unsigned long long)okm_hi << 32);
+#pragma unroll
+        for (int u = 0; u < NB; ++u) {
+            const uint32_t ci = threadIdx.x + uint32_t(u) * kThreads;
+            if ((okm >> u) & 1ull) *reinterpret_cast<V*>(lrows + size_t(ci) * CH) = reg[u];
+        }
+    }
+};
+
+// LDS row of global row jr inside the cone with top row r and height h, or kNoRank
+__device__ __forceinline__ uint32_t local_row(uint32_t jr, uint32_t r, uint32_t h)
+{
+    const uint32_t d = ilog2(jr + 1u), dr = ilog2(r + 1u);
+    if (d < dr || d - dr > h || ((jr + 1u) >> (d - dr)) != r + 1u) return kNoRank;
+    return jr - (r << (d - dr));
+}
+
+// Patches after commit(): disjoint LDS bytes, written by the first threads.
+template <class V>
+__device__ __forceinline__ void stage_patches(const Geom& g, unsigned char* lrows, const unsigned char* pay,
+                                              uint32_t r, uint32_t h, uint32_t root)
 {
     const uint32_t CH = uint32_t(sizeof(V));
-    const uint32_t nx = (2u << h) - 1u;
-    const uint32_t n = (nx * g.RB) / CH;
-    const uint32_t pay_bytes = g.P * g.EB;
-    const uint32_t skip_lo = root != 0 ? root * g.EB : 0xFFFFFFFFu;
-    const uint32_t skip_hi = root != 0 ? skip_lo + g.EB : 0xFFFFFFFFu;
-    for (uint32_t c0 = threadIdx.x; c0 < n; c0 += kThreads * kCopyBatch) {
-        V reg[kCopyBatch];
-        uint32_t okm = 0;
-#pragma unroll
-        for (int u = 0; u < kCopyBatch; ++u) {
-            uint32_t ci = c0 + uint32_t(u) * kThreads;
-            uint32_t src = 0;                      // always a valid address
-            if (ci < n) {
-                uint32_t off = ci * CH;
-                uint32_t li = fdiv(off, g.divRB);
-                uint32_t within = off - li * g.RB;
-                uint32_t l = ilog2(li + 1);
-                uint32_t jg = (r << l) + li;
-                uint32_t sb = (1u + jg * g.W) * g.EB + within;
-                if (jg < g.M && sb + CH <= pay_bytes && !(sb >= skip_lo && sb < skip_hi)) {
-                    okm |= 1u << u;
-                    src = sb;
-                }
-            }
-            reg[u] = *reinterpret_cast<const V*>(pay + src);
-        }
-#pragma unroll
-        for (int u = 0; u < kCopyBatch; ++u) {
-            uint32_t ci = c0 + uint32_t(u) * kThreads;
-            if ((okm >> u) & 1u) *reinterpret_cast<V*>(lrows + size_t(ci) * CH) = reg[u];
-        }
-    }
-    // patches: one process's payload each
     const uint32_t tid = threadIdx.x;
-    const uint32_t dlo_rows = r + 1;       // (r + 1) = 2^dlo + cone
-    if (root != 0) {
-        uint32_t jr = fdiv(root - 1, g.divW);
-        uint32_t ir = root - 1 - jr * g.W;
-        uint32_t d = ilog2(jr + 1), dr = ilog2(dlo_rows);
-        if (d >= dr && d - dr <= h && ((jr + 1) >> (d - dr)) == dlo_rows) {
-            uint32_t li = jr - (r << (d - dr));
-            unsigned char* dst = lrows + size_t(li) * g.RB + ir * g.EB;
+    if (root != 0) {          // virtual rank `root` is process 0
+        const uint32_t jr = fdiv(root - 1u, g.divW);
+        const uint32_t li = local_row(jr, r, h);
+        if (li != kNoRank) {
+            unsigned char* dst = lrows + size_t(li) * g.RB + (root - 1u - jr * g.W) * g.EB;
             for (uint32_t o = tid * CH; o < g.EB; o += kThreads * CH)
-                *reinterpret_cast<V*>(dst + o) = *reinterpret_cast<const V*>(pay + o);     // process 0
+                *reinterpret_cast<V*>(dst + o) = *reinterpret_cast<const V*>(pay + o);
         }
     }
-    if (g.a > 1) {
-        uint32_t jr = g.M - 1;
-        uint32_t d = ilog2(jr + 1), dr = ilog2(dlo_rows);
-        if (d >= dr && d - dr <= h && ((jr + 1) >> (d - dr)) == dlo_rows) {
-            uint32_t li = jr - (r << (d - dr));
-            unsigned char* dst = lrows + size_t(li) * g.RB + (g.a - 1) * g.EB;
+    if (g.a > 1) {            // the root as member a-1 of the last group
+        const uint32_t li = local_row(g.M - 1u, r, h);
+        if (li != kNoRank) {
+            unsigned char* dst = lrows + size_t(li) * g.RB + (g.a - 1u) * g.EB;
             const unsigned char* src = pay + size_t(root) * g.EB;
             for (uint32_t o = tid * CH; o < g.EB; o += kThreads * CH)
-                *reinterpret_cast<V*>(dst + o) = *reinterpret_cast<const V*>(src + o);     // the root
+                *reinterpret_cast<V*>(dst + o) = *reinterpret_cast<const V*>(src + o);
         }
     }
 }
 
-// One cone of one tier of one reduce.  All threads of the workgroup call it.
-// Requires: ft loaded and a barrier passed.  Ends with a barrier.
+// does the cone (top row r, height h) hold a row with a listed process?
+__device__ __forceinline__ bool cone_has_failure(const FailTab& ft, uint32_t r, uint32_t h)
+{
+    bool any = false;
+    if (ft.listed != 0)
+        for (uint32_t q = 0; q < ft.n; ++q)
+            if (ft.row[q] != kNoRank && local_row(ft.row[q], r, h) != kNoRank) any = true;
+    return any;
+}
+
+// The rounds of one staged cone, deepest level first, then the hand-over to the
+// tier above or the root's choice.  LDS-only barriers; ends with one.
 template <class T, int OP, int WP>
-__device__ __forceinline__ void run_cone(const RunArgs& A, const TierDesc& td, const FailTab& ft,
-                                         unsigned char* lrows_b, uint32_t* lmeta, uint32_t s, uint32_t root,
-                                         uint32_t cone, const unsigned char* pay, unsigned char* wsS,
-                                         bool discard, uint32_t& uc_cnt, uint32_t& tree_cnt)
+__device__ __forceinline__ void cone_rounds(const RunArgs& A, const TierDesc& td, const FailTab& ft, T* rows,
+                                            uint32_t* lmeta, uint32_t s, uint32_t root, uint32_t cone,
+                                            const unsigned char* pay, unsigned char* wsS, bool discard,
+                                            uint32_t& uc_cnt, uint32_t& tree_cnt)
 {
     const Geom& g = A.g;
     const uint32_t tid = threadIdx.x;
     const uint32_t h = td.dhi - td.dlo;
-    const uint32_t r = (1u << td.dlo) - 1u + cone;       // top row of the cone
-    const uint32_t nx = (2u << h) - 1u;
-    T* rows = reinterpret_cast<T*>(lrows_b);
-
-    // ---- stage: inputs of the cone, and the messages of the level below it
-    if (A.vec16) stage_inputs<uint4>(g, lrows_b, pay, r, h, root);
-    else stage_inputs<T>(g, lrows_b, pay, r, h, root);
-    if (td.child_in) {
-        const uint32_t per = 2u << h;                       // rows of the level below, per cone
-        const uint32_t first = ((r + 1u) << (h + 1)) - 1u;  // its first global row
-        uint32_t cc = first < g.M ? (g.M - first < per ? g.M - first : per) : 0u;
-        const unsigned char* src = wsS + td.in_off + size_t(cone) * per * g.RB;
-        if (A.vec16) copy_to_lds<uint4>(lrows_b + size_t(nx) * g.RB, src, cc * g.RB);
-        else copy_to_lds<T>(lrows_b + size_t(nx) * g.RB, src, cc * g.RB);
-        const uint32_t* msrc = reinterpret_cast<const uint32_t*>(wsS + td.in_meta_off) + size_t(cone) * per;
-        for (uint32_t i = tid; i < cc; i += kThreads) lmeta[nx + i] = msrc[i];
-    }
-    __syncthreads();
-
-    // ---- rounds: deepest level first
+    const uint32_t r = (1u << td.dlo) - 1u + cone;
+    const bool check_fail = cone_has_failure(ft, r, h);
     T* vroot_out = reinterpret_cast<T*>(wsS + A.vroot_off);
+
     for (int l = int(h); l >= 0; --l) {
         const uint32_t lfirst = (1u << l) - 1u;
         const uint32_t gfirst = ((r + 1u) << l) - 1u;
@@ -392,21 +444,20 @@ __device__ __forceinline__ void run_cone(const RunArgs& A, const TierDesc& td, c
             const uint32_t nitems = cnt * g.E;
             const bool kids = (uint32_t(l) < h) || td.child_in;
             for (uint32_t it = tid; it < nitems; it += kThreads) {
-                uint32_t lr = fdiv(it, g.divE);
-                uint32_t e = it - lr * g.E;
-                process_item<T, OP, WP>(g, ft, rows, lmeta, lfirst + lr, gfirst + lr, e, kids, vroot_out,
-                                        uc_cnt, tree_cnt);
+                const uint32_t lr = fdiv(it, g.divE);
+                const uint32_t e = it - lr * g.E;
+                process_item<T, OP, WP>(g, ft, rows, lmeta, lfirst + lr, gfirst + lr, e, kids, check_fail,
+                                        vroot_out, uc_cnt, tree_cnt);
             }
         }
-        __syncthreads();
+        lds_barrier();
     }
 
-    // ---- hand over: to the tier above, or the root's choice
     if (!td.is_top) {
         unsigned char* dst = wsS + td.out_off + size_t(cone) * g.RB;
         if (A.vec16) {
             for (uint32_t o = tid * 16u; o < g.RB; o += kThreads * 16u)
-                *reinterpret_cast<uint4*>(dst + o) = *reinterpret_cast<const uint4*>(lrows_b + o);
+                *reinterpret_cast<vec16_t*>(dst + o) = *reinterpret_cast<const vec16_t*>(reinterpret_cast<unsigned char*>(rows) + o);
         } else {
             for (uint32_t o = tid; o < g.W * g.E; o += kThreads) reinterpret_cast<T*>(dst)[o] = rows[o];
         }
@@ -425,11 +476,13 @@ __device__ __forceinline__ void run_cone(const RunArgs& A, const TierDesc& td, c
         for (uint32_t e = tid; e < g.E; e += kThreads) {
             T val = T(0);
             if (st == kStOk) {
-                uint32_t ks = uint32_t(__ffs(int(okm))) - 1u;
+                const uint32_t ks = uint32_t(__ffs(int(okm))) - 1u;
                 val = rows[ks * g.E + e];
                 if (ks + 1u >= g.a) {
-                    T vr = g.a > 1 ? vroot_out[e]
-                                   : reinterpret_cast<const T*>(pay + size_t(root) * g.EB)[e];
+                    T vr;
+                    if (g.a == 1) vr = reinterpret_cast<const T*>(pay + size_t(root) * g.EB)[e];   // the root's input
+                    else if (A.ntiers == 1) vr = rows[size_t(g.M - 1u) * g.W * g.E + (g.a - 1u) * g.E + e];
+                    else vr = vroot_out[e];       // written by the deepest tier, an earlier launch
                     val = comb<T, OP>(vr, val);
                 }
             }
@@ -437,49 +490,154 @@ __device__ __forceinline__ void run_cone(const RunArgs& A, const TierDesc& td, c
         }
         if (tid == 0) A.status[s] = st;
     }
-    __syncthreads();
+    lds_barrier();
 }
 
-template <class T, int OP, int WP>
-__global__ void __launch_bounds__(kThreads) tier_kernel(RunArgs A)
+// messages of the level below an upper tier's cone, from scratch into LDS
+template <class T>
+__device__ __forceinline__ void stage_children(const RunArgs& A, const TierDesc& td, unsigned char* lrows_b,
+                                               uint32_t* lmeta, const unsigned char* wsS, uint32_t cone)
 {
-    extern __shared__ __align__(16) unsigned char smem[];
-    const TierDesc& td = A.tiers[A.tier];
-    const uint32_t ncones = 1u << td.dlo;
-    const uint32_t s = blockIdx.x >> td.dlo;
-    const uint32_t cone = blockIdx.x & (ncones - 1u);
-    if (ncones - 1u + cone >= A.g.M) return;                 // no such row
-    if (A.status[s] == kStBadFailureSet) return;
-    uint32_t root = 0, base = 0;
-    if (A.attempts) {
-        root = A.attempts[s] - 1u;
-        base = root * A.g.Ratt;
-    } else if (A.root) {
-        root = A.root[s];
-    }
-    FailTab& ft = *reinterpret_cast<FailTab*>(smem);
-    uint32_t* lmeta = reinterpret_cast<uint32_t*>(smem + sizeof(FailTab));
-    unsigned char* lrows = smem + sizeof(FailTab) + ((size_t(td.lds_rows) * 4u + 15u) & ~size_t(15));
-    load_failtab(ft, A.g, A.fail_rank, A.fail_round, s, root, base);
-    __syncthreads();
+    const Geom& g = A.g;
+    const uint32_t h = td.dhi - td.dlo;
+    const uint32_t r = (1u << td.dlo) - 1u + cone;
+    const uint32_t nx = (2u << h) - 1u;
+    const uint32_t per = 2u << h;                       // rows of the level below, per cone
+    const uint32_t first = ((r + 1u) << (h + 1)) - 1u;  // its first global row
+    const uint32_t cc = first < g.M ? (g.M - first < per ? g.M - first : per) : 0u;
+    const unsigned char* src = wsS + td.in_off + size_t(cone) * per * g.RB;
+    if (A.vec16) copy_to_lds<vec16_t>(lrows_b + size_t(nx) * g.RB, src, cc * g.RB);
+    else copy_to_lds<T>(lrows_b + size_t(nx) * g.RB, src, cc * g.RB);
+    const uint32_t* msrc = reinterpret_cast<const uint32_t*>(wsS + td.in_meta_off) + size_t(cone) * per;
+    for (uint32_t i = threadIdx.x; i < cc; i += kThreads) lmeta[nx + i] = msrc[i];
+}
+
+// A workgroup's walk through its cones of one tier of one (scenario, attempt).
+template <class T, int OP, int WP, class V>
+__device__ __forceinline__ void walk_cones(const RunArgs& A, const TierDesc& td, FailTab& ft, unsigned char* lrows,
+                                           uint32_t* lmeta, uint32_t s, uint32_t root, uint32_t base,
+                                           uint32_t c_lo, uint32_t c_hi, const unsigned char* pay,
+                                           unsigned char* wsS, bool discard)
+{
+    const Geom& g = A.g;
+    const uint32_t h = td.dhi - td.dlo;
+    Stage<V> stg;
+    stg.init(g, td.dlo, h);
+    stg.issue(g, pay, c_lo, root);                 // in flight while the failure list is resolved
+    load_failtab(ft, g, A.fail_rank, A.fail_round, s, root, base);
     uint32_t uc_cnt = 0, tree_cnt = 0;
-    run_cone<T, OP, WP>(A, td, ft, lrows, lmeta, s, root, cone, A.payload + size_t(s) * A.scen_stride_bytes,
-                        A.ws + size_t(s) * A.ws_stride, false, uc_cnt, tree_cnt);
+    for (uint32_t cone = c_lo; cone < c_hi; ++cone) {
+        const uint32_t r = (1u << td.dlo) - 1u + cone;
+        stg.commit(lrows);
+        stage_patches<V>(g, lrows, pay, r, h, root);
+        if (td.child_in) stage_children<T>(A, td, lrows, lmeta, wsS, cone);
+        __syncthreads();
+        if (cone + 1 < c_hi) stg.issue(g, pay, cone + 1, root);    // prefetch
+        cone_rounds<T, OP, WP>(A, td, ft, reinterpret_cast<T*>(lrows), lmeta, s, root, cone, pay, wsS, discard,
+                               uc_cnt, tree_cnt);
+    }
     if (A.msgs) {
         if (uc_cnt) atomicAdd(&ft.cnt_uc, uc_cnt);
         if (tree_cnt) atomicAdd(&ft.cnt_tree, tree_cnt);
         __syncthreads();
         if (threadIdx.x == 0) {
-            atomicAdd(&A.msgs[size_t(s) * A.nmsg + 0], (unsigned long long)ft.cnt_uc);
-            atomicAdd(&A.msgs[size_t(s) * A.nmsg + 1], (unsigned long long)ft.cnt_tree);
+            if (ft.cnt_uc) atomicAdd(&A.msgs[size_t(s) * A.nmsg + 0], (unsigned long long)ft.cnt_uc);
+            if (ft.cnt_tree) atomicAdd(&A.msgs[size_t(s) * A.nmsg + 1], (unsigned long long)ft.cnt_tree);
         }
     }
 }
 
-// Attempts of an allreduce whose root had failed before the operation: the
-// reduce messages are sent (to a root that never answers), no broadcast follows.
-// Rare; one workgroup walks through a whole attempt, tier after tier, with a
-// private scratch area.  gridDim.x workgroups stride over the scenarios.
+template <class T, int OP, int WP, bool VEC>
+__global__ void __launch_bounds__(kThreads) tier_kernel(RunArgs A)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    const TierDesc& td = A.tiers[A.tier];
+    const uint32_t sv = blockIdx.x >> td.gshift;                      // scenario, or S + retry entry
+    const uint32_t grp = blockIdx.x & ((1u << td.gshift) - 1u);
+    uint32_t c_lo = grp << td.kshift;
+    uint32_t c_hi = c_lo + (1u << td.kshift);
+    const uint32_t top0 = (1u << td.dlo) - 1u;
+    if (top0 + c_lo >= A.g.M) return;                                 // no such rows
+    if (top0 + c_hi > A.g.M) c_hi = A.g.M - top0;
+
+    uint32_t s = sv, root = 0, base = 0;
+    bool discard = false;
+    unsigned char* wsS;
+    if (sv >= A.S) {
+        // an attempt whose root had failed beforehand: messages are sent, nothing is delivered
+        const uint32_t k = sv - A.S;
+        uint32_t n = *A.retry_count;
+        if (k >= n) return;
+        s = A.retry_list[2u * k];
+        root = A.retry_list[2u * k + 1u];
+        base = root * A.g.Ratt;
+        discard = true;
+        wsS = A.retry_ws + size_t(k) * A.ws_stride;
+    } else {
+        if (A.status[s] == kStBadFailureSet) return;
+        if (A.attempts) {
+            root = A.attempts[s] - 1u;
+            base = root * A.g.Ratt;
+        } else if (A.root) {
+            root = A.root[s];
+        }
+        wsS = A.ws + size_t(s) * A.ws_stride;
+    }
+    FailTab& ft = *reinterpret_cast<FailTab*>(smem);
+    uint32_t* lmeta = reinterpret_cast<uint32_t*>(smem + sizeof(FailTab));
+    unsigned char* lrows = smem + sizeof(FailTab) + ((size_t(td.lds_rows) * 4u + 15u) & ~size_t(15));
+    const unsigned char* pay = A.payload + size_t(s) * A.scen_stride_bytes;
+    if constexpr (VEC) walk_cones<T, OP, WP, vec16_t>(A, td, ft, lrows, lmeta, s, root, base, c_lo, c_hi, pay, wsS, discard);
+    else walk_cones<T, OP, WP, T>(A, td, ft, lrows, lmeta, s, root, base, c_lo, c_hi, pay, wsS, discard);
+}
+
+// The deepest tier's cones that the wavefront kernel handed over (failures, the
+// short last group, relabelled ranks, ragged bottom level): workgroups stride over
+// the list.
+template <class T, int OP, int WP, bool VEC>
+__global__ void __launch_bounds__(kThreads) tier_list_kernel(RunArgs A)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    const TierDesc& td = A.tiers[0];
+    FailTab& ft = *reinterpret_cast<FailTab*>(smem);
+    uint32_t* lmeta = reinterpret_cast<uint32_t*>(smem + sizeof(FailTab));
+    unsigned char* lrows = smem + sizeof(FailTab) + ((size_t(td.lds_rows) * 4u + 15u) & ~size_t(15));
+    const uint32_t n = *A.fix_count;
+    const uint32_t top0 = (1u << td.dlo) - 1u;
+    for (uint32_t i = blockIdx.x; i < n; i += gridDim.x) {
+        const uint32_t sv = A.fix_list[2u * i];
+        uint32_t c_lo = A.fix_list[2u * i + 1u];
+        uint32_t c_hi = c_lo + (1u << A.fix_kshift);
+        if (top0 + c_hi > A.g.M) c_hi = A.g.M - top0;
+        uint32_t s = sv, root = 0, base = 0;
+        bool discard = false;
+        unsigned char* wsS;
+        if (sv >= A.S) {
+            const uint32_t k = sv - A.S;
+            s = A.retry_list[2u * k];
+            root = A.retry_list[2u * k + 1u];
+            base = root * A.g.Ratt;
+            discard = true;
+            wsS = A.retry_ws + size_t(k) * A.ws_stride;
+        } else {
+            if (A.attempts) {
+                root = A.attempts[s] - 1u;
+                base = root * A.g.Ratt;
+            } else if (A.root) {
+                root = A.root[s];
+            }
+            wsS = A.ws + size_t(s) * A.ws_stride;
+        }
+        const unsigned char* pay = A.payload + size_t(s) * A.scen_stride_bytes;
+        __syncthreads();              // the previous entry is done with LDS
+        if constexpr (VEC) walk_cones<T, OP, WP, vec16_t>(A, td, ft, lrows, lmeta, s, root, base, c_lo, c_hi, pay, wsS, discard);
+        else walk_cones<T, OP, WP, T>(A, td, ft, lrows, lmeta, s, root, base, c_lo, c_hi, pay, wsS, discard);
+    }
+}
+
+// Failed attempts beyond the kRetrySlots that run inside the tier launches (a
+// batch with that many failed roots is unusual): one workgroup walks through a
+// whole attempt, tier after tier, with its own scratch.
 template <class T, int OP, int WP>
 __global__ void __launch_bounds__(kThreads) retry_kernel(RunArgs A)
 {
@@ -490,34 +648,20 @@ __global__ void __launch_bounds__(kThreads) retry_kernel(RunArgs A)
     for (uint32_t t = 0; t < A.ntiers; ++t)
         if (A.tiers[t].lds_rows > max_rows) max_rows = A.tiers[t].lds_rows;
     unsigned char* lrows = smem + sizeof(FailTab) + ((size_t(max_rows) * 4u + 15u) & ~size_t(15));
-    unsigned char* wsB = A.ws + size_t(blockIdx.x) * A.ws_stride;
-    for (uint32_t s = blockIdx.x; s < A.S; s += gridDim.x) {
-        if (A.status[s] == kStBadFailureSet) continue;
-        const uint32_t natt = A.attempts[s];
-        for (uint32_t att = 0; att + 1 < natt; ++att) {
-            const uint32_t root = att, base = att * A.g.Ratt;
-            __syncthreads();
-            load_failtab(ft, A.g, A.fail_rank, A.fail_round, s, root, base);
-            __syncthreads();
-            uint32_t uc_cnt = 0, tree_cnt = 0;
-            for (uint32_t t = 0; t < A.ntiers; ++t) {
-                const TierDesc& td = A.tiers[t];
-                const uint32_t ncones = 1u << td.dlo;
-                for (uint32_t cone = 0; cone < ncones; ++cone) {
-                    if (ncones - 1u + cone >= A.g.M) break;
-                    run_cone<T, OP, WP>(A, td, ft, lrows, lmeta, s, root, cone,
-                                        A.payload + size_t(s) * A.scen_stride_bytes, wsB, true, uc_cnt, tree_cnt);
-                }
-            }
-            if (A.msgs) {
-                if (uc_cnt) atomicAdd(&ft.cnt_uc, uc_cnt);
-                if (tree_cnt) atomicAdd(&ft.cnt_tree, tree_cnt);
-                __syncthreads();
-                if (threadIdx.x == 0) {
-                    atomicAdd(&A.msgs[size_t(s) * A.nmsg + 0], (unsigned long long)ft.cnt_uc);
-                    atomicAdd(&A.msgs[size_t(s) * A.nmsg + 1], (unsigned long long)ft.cnt_tree);
-                }
-            }
+    unsigned char* wsB = A.retry_ws + size_t(A.retry_slots + blockIdx.x) * A.ws_stride;
+    const uint32_t n = *A.retry_count;
+    for (uint32_t k = A.retry_slots + blockIdx.x; k < n; k += gridDim.x) {
+        const uint32_t s = A.retry_list[2u * k];
+        const uint32_t root = A.retry_list[2u * k + 1u];
+        const uint32_t base = root * A.g.Ratt;
+        const unsigned char* pay = A.payload + size_t(s) * A.scen_stride_bytes;
+        for (uint32_t t = 0; t < A.ntiers; ++t) {
+            const TierDesc& td = A.tiers[t];
+            const uint32_t top0 = (1u << td.dlo) - 1u;
+            uint32_t c_hi = 1u << td.dlo;
+            if (top0 + c_hi > A.g.M) c_hi = A.g.M - top0;
+            __syncthreads();          // scratch rows of the tier below are complete and visible
+            walk_cones<T, OP, WP, T>(A, td, ft, lrows, lmeta, s, root, base, 0, c_hi, pay, wsB, true);   // element-wise staging
         }
     }
 }
@@ -525,6 +669,7 @@ __global__ void __launch_bounds__(kThreads) retry_kernel(RunArgs A)
 // launchers, one set per (value type, operator), defined in ftred_inst_*.hip
 #define FTRED_DECLARE_LAUNCHERS(NAME)                                                         \
     hipError_t launch_tier_##NAME(const RunArgs& A, uint32_t grid, uint32_t lds, hipStream_t st); \
+    hipError_t launch_list_##NAME(const RunArgs& A, uint32_t grid, uint32_t lds, hipStream_t st); \
     hipError_t launch_retry_##NAME(const RunArgs& A, uint32_t grid, uint32_t lds, hipStream_t st);
 
 FTRED_DECLARE_LAUNCHERS(i64_sum)
@@ -537,8 +682,27 @@ FTRED_DECLARE_LAUNCHERS(f64_sum)
     template <int WP>                                                                              \
     static hipError_t tier_wp_##NAME(const RunArgs& A, uint32_t grid, uint32_t lds, hipStream_t st) \
     {                                                                                              \
-        hipLaunchKernelGGL((tier_kernel<T, OP, WP>), dim3(grid), dim3(kThreads), lds, st, A);       \
+        if (A.vec16) hipLaunchKernelGGL((tier_kernel<T, OP, WP, true>), dim3(grid), dim3(kThreads), lds, st, A); \
+        else hipLaunchKernelGGL((tier_kernel<T, OP, WP, false>), dim3(grid), dim3(kThreads), lds, st, A);        \
         return hipGetLastError();                                                                  \
+    }                                                                                              \
+    template <int WP>                                                                              \
+    static hipError_t list_wp_##NAME(const RunArgs& A, uint32_t grid, uint32_t lds, hipStream_t st) \
+    {                                                                                              \
+        if (A.vec16) hipLaunchKernelGGL((tier_list_kernel<T, OP, WP, true>), dim3(grid), dim3(kThreads), lds, st, A); \
+        else hipLaunchKernelGGL((tier_list_kernel<T, OP, WP, false>), dim3(grid), dim3(kThreads), lds, st, A);        \
+        return hipGetLastError();                                                                  \
+    }                                                                                              \
+    hipError_t launch_list_##NAME(const RunArgs& A, uint32_t grid, uint32_t lds, hipStream_t st)    \
+    {                                                                                              \
+        switch (wp_bucket(A.g.W)) {                                                                \
+            case 2: return list_wp_##NAME<2>(A, grid, lds, st);                                    \
+            case 3: return list_wp_##NAME<3>(A, grid, lds, st);                                    \
+            case 4: return list_wp_##NAME<4>(A, grid, lds, st);                                    \
+            case 5: return list_wp_##NAME<5>(A, grid, lds, st);                                    \
+            case 9: return list_wp_##NAME<9>(A, grid, lds, st);                                    \
+            default: return list_wp_##NAME<16>(A, grid, lds, st);                                  \
+        }                                                                                          \
     }                                                                                              \
     template <int WP>                                                                              \
     static hipError_t retry_wp_##NAME(const RunArgs& A, uint32_t grid, uint32_t lds, hipStream_t st) \

@@ -65,9 +65,16 @@ FT_HD void partners_of(const Geom& g, uint32_t root, uint32_t rank, PartnerInfo&
 // ---------------------------------------------------------------------------
 // scenario check: one thread per scenario
 
+__global__ void zero_words_kernel(uint32_t* p, uint32_t n)
+{
+    const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0u;
+}
+
 __global__ void prepass_kernel(Geom g, uint32_t kind /* 0 reduce, 1 allreduce */, uint32_t S, const uint32_t* root,
                                const uint32_t* fail_rank, const uint32_t* fail_round, uint32_t* status,
-                               uint32_t* attempts, unsigned long long* msgs, uint32_t nmsg, unsigned char* result)
+                               uint32_t* attempts, unsigned long long* msgs, uint32_t nmsg, unsigned char* result,
+                               uint32_t* retry_list, uint32_t* retry_count)
 {
     const uint32_t s = blockIdx.x * blockDim.x + threadIdx.x;
     if (s >= S) return;
@@ -89,6 +96,12 @@ __global__ void prepass_kernel(Geom g, uint32_t kind /* 0 reduce, 1 allreduce */
     while ((lead >> a) & 1u) ++a;
     status[s] = bad ? kStBadFailureSet : kStOk;
     if (attempts) attempts[s] = bad ? 0u : a + 1u;
+    if (retry_list && !bad)
+        for (uint32_t att = 0; att < a; ++att) {        // attempts whose root had failed beforehand
+            const uint32_t k = atomicAdd(retry_count, 1u);
+            retry_list[2u * k] = s;
+            retry_list[2u * k + 1u] = att;
+        }
     if (msgs)
         for (uint32_t k = 0; k < nmsg; ++k) msgs[size_t(s) * nmsg + k] = 0ull;
     if (bad)

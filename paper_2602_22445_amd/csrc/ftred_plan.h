@@ -5,6 +5,7 @@
 #include <stdint.h>
 
 #include "ftred_kernels.h"
+#include "ftred_wave.h"
 
 struct ftred_plan_s {
     ftred::Geom g;
@@ -15,6 +16,9 @@ struct ftred_plan_s {
     uint32_t vroot_off;
     uint64_t ws_scen;           // scratch bytes per scenario (tree tiers)
     uint32_t retry_blocks;
+    uint32_t use_wave;          // the deepest tier runs as one wavefront per subtree
+    ftred::WaveLayout wl;
+    uint32_t wave_gshift;       // workgroups of the wavefront tier per scenario = 2^wave_gshift
     uint32_t bc_chunk;          // ranks per workgroup in the broadcast kernel
     uint32_t val_chunk;         // ranks per workgroup in the validation kernel
 };
@@ -29,14 +33,34 @@ inline uint32_t align_up(uint32_t x, uint32_t a) { return (x + a - 1) / a * a; }
 inline uint32_t val_chunks(const ftred_plan_s* p) { return (p->g.P + p->val_chunk - 1) / p->val_chunk; }
 
 // workspace layout: [tree scratch of S scenarios][tree scratch of the retry
-// workgroups][validation partials][256 bytes of counters]
-inline uint64_t ws_val_off(const ftred_plan_s* p, uint32_t S) { return (uint64_t(S) + p->retry_blocks) * p->ws_scen; }
+// entries: kRetrySlots + retry_blocks][validation partials][retry list][fix list][256 bytes
+// of counters: +0 invalid scenarios (u64), +8 retry entries (u32), +12 fix-list
+// entries (u32)]
+inline uint64_t ws_retry_off(const ftred_plan_s* p, uint32_t S) { return uint64_t(S) * p->ws_scen; }
+inline uint64_t ws_val_off(const ftred_plan_s* p, uint32_t S)
+{
+    return (uint64_t(S) + kRetrySlots + p->retry_blocks) * p->ws_scen;
+}
 inline uint64_t ws_val_bytes(const ftred_plan_s* p, uint32_t S)
 {
     // per (scenario, chunk): E values of the partial reduction and E doubles of |x| sums
     return (uint64_t(S) * val_chunks(p) * (uint64_t(p->g.E) * 8u * 2u) + 255u) / 256u * 256u;
 }
-inline uint64_t ws_total(const ftred_plan_s* p, uint32_t S) { return ws_val_off(p, S) + ws_val_bytes(p, S) + 256u; }
+inline uint64_t ws_list_off(const ftred_plan_s* p, uint32_t S) { return ws_val_off(p, S) + ws_val_bytes(p, S); }
+inline uint64_t ws_list_bytes(const ftred_plan_s* p, uint32_t S)
+{
+    // at most f failed attempts per scenario, two words each
+    return (uint64_t(S) * p->g.f * 8u + 255u) / 256u * 256u;
+}
+// subtrees the wavefront kernel leaves to the general kernel: at most f + 3
+// wavefronts per scenario or retry entry, two words each
+inline uint64_t ws_fix_off(const ftred_plan_s* p, uint32_t S) { return ws_list_off(p, S) + ws_list_bytes(p, S); }
+inline uint64_t ws_fix_bytes(const ftred_plan_s* p, uint32_t S)
+{
+    return ((uint64_t(S) + kRetrySlots) * (p->g.f + 3u) * 8u + 255u) / 256u * 256u;
+}
+inline uint64_t ws_ctr_off(const ftred_plan_s* p, uint32_t S) { return ws_fix_off(p, S) + ws_fix_bytes(p, S); }
+inline uint64_t ws_total(const ftred_plan_s* p, uint32_t S) { return ws_ctr_off(p, S) + 256u; }
 
 // event-pair timing of kernel launches (ftred_timing_begin / ftred_timing_end)
 void tm_mark(int phase, hipStream_t st, bool start);

@@ -359,7 +359,7 @@ extern "C" int ftred_validate(const ftred_plan_t* plan, int kind, uint32_t S, co
     const uint64_t half = uint64_t(S) * val_chunks(plan) * g.E * 8u;
     A.partial = ws + voff;
     A.scale = reinterpret_cast<double*>(ws + voff + half);
-    A.n_invalid = reinterpret_cast<unsigned long long*>(ws + voff + ws_val_bytes(plan, S));
+    A.n_invalid = reinterpret_cast<unsigned long long*>(ws + ws_ctr_off(plan, S));
     A.chunk = plan->val_chunk;
     A.nchunks = val_chunks(plan);
     A.div_nchunks = make_fastdiv(A.nchunks);

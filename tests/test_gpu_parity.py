@@ -211,15 +211,19 @@ def test_bad_failure_sets_get_a_status_and_zero_outputs(ft, oracle, w):
     assert g["status"].cpu().numpy().tolist() == [0, 3, 3, 0, 0, 0]
 
 
-def test_shared_payload_unaligned_pointer_and_small_lds_budget(ft, oracle, w):
+@pytest.mark.parametrize("flags,min_tiers", [(0, 2), (0x1000 | 8, 3), (0x1000, 2), (0x100 | 0x1000 | 16, 2)])
+def test_shared_payload_unaligned_pointer_and_tree_kernel_variants(ft, oracle, w, flags, min_tiers):
     """stride 0 (one payload for all scenarios), a payload pointer that is only
-    8-byte aligned (element-wise staging path), and a small LDS budget (more tiers)."""
+    8-byte aligned (element-wise staging), and the variants of the tree kernels:
+    wavefront-per-subtree deepest tier (default), LDS-tile deepest tier (flag
+    0x1000) with a small LDS budget (more tiers) and one tile per workgroup."""
     P, f, E, S = 3000, 3, 16, 32
     Rred, Ratt = _rounds(oracle, P, f)
     fr, fo = w.random_failure_sets(77, S, P, f, inop_permille=500, rounds_per_attempt=Ratt, protected=f + 1)
+    fr[2, 0], fo[2, 0] = 0, 0               # a retry
     x1 = w.payload_normal(77, 1, P, E, threads=1)[0]
-    plan = ft.Plan(P, f, E, ft.F64, ft.SUM, 8)
-    assert plan.info.tiers >= 3
+    plan = ft.Plan(P, f, E, ft.F64, ft.SUM, flags)
+    assert plan.info.tiers >= min_tiers
     buf = torch.empty(P * E + 1, dtype=torch.float64, device="cuda")
     xd = buf[1:].view(P, E)
     xd.copy_(torch.from_numpy(x1))
@@ -227,10 +231,22 @@ def test_shared_payload_unaligned_pointer_and_small_lds_budget(ft, oracle, w):
     g = ft.run_allreduce(plan, S, xd, to_dev(fr), to_dev(fo))
     o = oracle.allreduce_batch(P, f, x1, ft.F64, ft.SUM, S, fail_rank=fr, fail_round=fo, want_out=True)
     assert np.array_equal(g["status"].cpu().numpy(), o["status"])
+    assert np.array_equal(g["attempts"].cpu().numpy(), o["attempts"]) and o["attempts"][2] == 2
     assert np.array_equal(g["result"].cpu().numpy(), o["result"])
     assert np.array_equal(g["msgs"].cpu().numpy(), o["msgs"])
     assert np.array_equal(unpack_bitmap(g["has_bitmap"].cpu().numpy(), P), o["has"])
     assert np.array_equal(g["per_process_out"].cpu().numpy(), o["out"])
+
+
+@pytest.mark.parametrize("P,f,E,dtype,op,S,permille", [c for c in ALLREDUCE_CASES if c[0] >= 64])
+def test_allreduce_sweep_lds_tile_kernel(ft, oracle, w, P, f, E, dtype, op, S, permille):
+    """The same sweep with the LDS-tile kernel as the deepest tier (flag 0x1000)."""
+    seed = 2000 + P + 31 * f + E
+    _, Ratt = _rounds(oracle, P, f)
+    fr, fo = w.random_failure_sets(seed, S, P, f, inop_permille=permille, rounds_per_attempt=Ratt, protected=f + 1)
+    x = _payload(w, seed, S, P, E, dtype)
+    plan = ft.Plan(P, f, E, dtype, op, 0x1000)
+    compare_allreduce(ft, oracle, plan, x, fr, fo)
 
 
 def test_runs_are_deterministic(ft, oracle, w):
