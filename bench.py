@@ -31,11 +31,11 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--scenarios", type=int, default=4096)
-    ap.add_argument("--lds-kib", type=int, default=0, help="LDS budget of the tree kernels (0 = default)")
+    ap.add_argument("--lds-kib", type=int, default=0, help="ftred_plan flags (tuning knobs of the tree kernels; 0 = default)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (reference for HBM counters under rocprofv3)")
-    ap.add_argument("--cpu-sample", type=int, default=1024, help="scenarios timed on the CPU oracle")
+    ap.add_argument("--cpu-sample", type=int, default=2048, help="scenarios timed on the CPU oracle")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (scenarios are independent; nothing is sharded); "
@@ -144,7 +144,7 @@ def main():
         "config": {"workload": "allreduce P=16384 f=4 elems=8xf64 N(0,1) S=%d scenarios, k~U(0..4) failures, "
                                "1/2 pre-operational, 1/2 in-operation at a uniform round; per-process receive "
                                "buffers materialised; step = generate failures + allreduce + validate" % S,
-                   "scenarios": S, "lds_kib": args.lds_kib or 40},
+                   "scenarios": S, "plan_flags": args.lds_kib},
         "process_rounds_per_step": process_rounds,
         "hbm_GBs_whole_step_algorithmic": path_bytes / (elapsed / args.steps) / 1e9,
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
