@@ -157,7 +157,7 @@ extern "C" int ftred_plan(ftred_plan_t** out, uint32_t P, uint32_t f, uint32_t e
     uint32_t nt = 0;
     // the wavefront kernel leaves some subtrees to the LDS-tile kernel, which must be
     // able to stage a whole subtree of height kWaveH
-    p->use_wave = (g.L > uint32_t(kWaveH) && !(flags & 0x1000u) && ((2u << kWaveH) - 1u) <= cap0) ? 1u : 0u;
+    p->use_wave = (g.L > uint32_t(kWaveH) && !(flags & 0x1000u) && wave_width_ok(g.W) && ((2u << kWaveH) - 1u) <= cap0) ? 1u : 0u;
     {
         uint32_t h0 = hcap0 < g.L ? hcap0 : g.L;
         if (p->use_wave) h0 = uint32_t(kWaveH);
@@ -197,8 +197,7 @@ extern "C" int ftred_plan(ftred_plan_t** out, uint32_t P, uint32_t f, uint32_t e
     }
     if (p->use_wave) {
         p->wl = make_wave_layout(g, p->tiers[0].dlo);
-        const uint32_t wshift = p->tiers[0].dlo - p->wl.slot_shift;
-        p->wave_gshift = wshift >= 2 ? wshift - 2u : 0u;
+        p->wave_gshift = p->tiers[0].dlo - p->wl.slot_shift;      // one wavefront per workgroup
     }
     p->ws_scen = align_up(off, 256);
     p->retry_blocks = 64;
@@ -387,7 +386,7 @@ static void fill_run_args(RunArgs& A, const ftred_plan_t* p, uint32_t S, const v
     for (uint32_t t = 0; t < p->ntiers; ++t) A.tiers[t] = p->tiers[t];
     A.fix_list = reinterpret_cast<uint32_t*>(A.ws + ws_fix_off(p, S));
     A.fix_count = reinterpret_cast<uint32_t*>(A.ws + ws_ctr_off(p, S) + 12u);
-    A.fix_kshift = p->use_wave ? p->wl.slot_shift : 0u;
+    A.fix_kshift = 0u;                  // the lane-per-subtree kernel hands over single subtrees
 }
 
 // ---------------------------------------------------------------------------

@@ -620,6 +620,7 @@ __global__ void __launch_bounds__(kThreads) tier_list_kernel(RunArgs A)
             discard = true;
             wsS = A.retry_ws + size_t(k) * A.ws_stride;
         } else {
+            if (A.status[s] == kStBadFailureSet) continue;
             if (A.attempts) {
                 root = A.attempts[s] - 1u;
                 base = root * A.g.Ratt;

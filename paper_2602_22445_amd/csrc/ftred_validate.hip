@@ -74,12 +74,31 @@ struct ValFail {
     uint32_t rank[16], round[16];
 };
 
-template <class T, int OP>
+// V values per load (V * sizeof(T) = 16 bytes, or V = 1): streaming loads that
+// bypass nothing but are marked non-temporal, the data is read once
+template <class T, int V>
+__device__ __forceinline__ void load_values(const T* p, T (&v)[V])
+{
+    if constexpr (V == 1) {
+        v[0] = __builtin_nontemporal_load(p);
+    } else {
+        static_assert(V * sizeof(T) == 16, "one 16-byte load");
+        struct Pack { T v[V]; };
+        const vec16_t r = __builtin_nontemporal_load(reinterpret_cast<const vec16_t*>(p));
+        const Pack k = __builtin_bit_cast(Pack, r);
+#pragma unroll
+        for (int j = 0; j < V; ++j) v[j] = k.v[j];
+    }
+}
+
+constexpr int kValBatch = 8;          // ranks per thread in flight
+
+template <class T, int OP, int V>
 __global__ void __launch_bounds__(256) val_partial_kernel(ValArgs A)
 {
     __shared__ ValFail vf;
-    __shared__ T red[256];
-    __shared__ double reda[256];
+    __shared__ T red[V][256];
+    __shared__ double reda[V][256];
     __shared__ uint32_t bad_holder;
     const Geom& g = A.g;
     const uint32_t tid = threadIdx.x;
@@ -94,12 +113,7 @@ __global__ void __launch_bounds__(256) val_partial_kernel(ValArgs A)
         vf.rank[tid] = r;
         vf.round[tid] = o;
     }
-    if (tid == 0) {
-        uint32_t n = 0;
-        for (uint32_t q = 0; q < g.f; ++q) n += A.fail_rank[size_t(s) * F + q] != kNoRank ? 1u : 0u;
-        vf.listed = n;
-        bad_holder = 0;
-    }
+    if (tid == 0) bad_holder = 0;
     __syncthreads();
     // does the chunk hold a listed rank at all?
     bool chunk_listed = false;
@@ -111,57 +125,96 @@ __global__ void __launch_bounds__(256) val_partial_kernel(ValArgs A)
     const uint32_t* hb = A.has_bitmap ? A.has_bitmap + size_t(s) * ((g.P + 31u) / 32u) : nullptr;
     const bool st_ok = A.status[s] == kStOk;
     const bool check_holders = A.kind == 1 && st_ok;
+    uint32_t my_bad = 0;
 
-    const uint32_t cols = g.E < 256u ? g.E : 256u;
+    // a chunk without listed ranks: every process must hold the result; the words of
+    // the bitmap are checked here, once (chunks start at multiples of 32 ranks)
+    if (check_holders && hb && !chunk_listed) {
+        const uint32_t w0 = c0 >> 5, nw = (c1 - c0 + 31u) >> 5;
+        if (tid < nw) {
+            const uint32_t left = c1 - c0 - tid * 32u;
+            const uint32_t mask = left >= 32u ? 0xFFFFFFFFu : ((1u << left) - 1u);
+            if ((hb[w0 + tid] & mask) != mask) my_bad = 1;
+        }
+    }
+
+    const uint32_t EV = g.E / uint32_t(V);               // columns of V values
+    const uint32_t cols = EV < 256u ? EV : 256u;
     const uint32_t ngr = 256u / cols;
     const uint32_t col = tid % cols, gr = tid / cols;
-    uint32_t my_bad = 0;
-    for (uint32_t e0 = 0; e0 < g.E; e0 += cols) {        // same trip count for every thread
-        const uint32_t e = e0 + col;
-        const bool active = e < g.E && gr < ngr;
-        T acc = T(0);
-        double sa = 0.0;
+    for (uint32_t e0 = 0; e0 < EV; e0 += cols) {         // same trip count for every thread
+        const uint32_t ev = e0 + col;
+        const uint32_t e = ev * uint32_t(V);
+        const bool active = ev < EV && gr < ngr;
+        T acc[V];
+        double sa[V];
+#pragma unroll
+        for (int j = 0; j < V; ++j) { acc[j] = T(0); sa[j] = 0.0; }
         if (active) {
-            for (uint32_t p = c0 + gr; p < c1; p += ngr) {
-                // 0 never failed, 1 failed before the operation, 2 failed during it
-                uint32_t cls = 0;
-                if (chunk_listed)
-                    for (uint32_t q = 0; q < g.f; ++q)
-                        if (vf.rank[q] == p) cls = vf.round[q] == 0 ? 1u : 2u;
-                const T v = x[size_t(p) * g.E + e];
-                if (cls == 0) acc = vcomb<T, OP>(acc, v);
-                if constexpr (std::is_floating_point<T>::value) {
-                    if (cls != 1) sa += fabs(double(v));
+            T want[V];
+#pragma unroll
+            for (int j = 0; j < V; ++j) want[j] = res[e + j];
+            for (uint32_t p0 = c0 + gr; p0 < c1; p0 += uint32_t(kValBatch) * ngr) {
+                T xv[kValBatch][V], ov[kValBatch][V];
+#pragma unroll
+                for (int u = 0; u < kValBatch; ++u) {
+                    const uint32_t p = p0 + uint32_t(u) * ngr;
+                    const size_t at = size_t(p < c1 ? p : c0) * g.E + e;       // past the end: any valid address
+                    load_values<T, V>(x + at, xv[u]);
+                    if (check_holders && out) load_values<T, V>(out + at, ov[u]);
                 }
-                if (check_holders) {
-                    bool has = cls == 0, known = cls == 0;
-                    if (hb) {
-                        has = ((hb[p >> 5] >> (p & 31u)) & 1u) != 0u;
-                        known = true;
-                        if ((cls == 0 && !has) || (cls == 1 && has)) my_bad = 1;
+#pragma unroll
+                for (int u = 0; u < kValBatch; ++u) {
+                    const uint32_t p = p0 + uint32_t(u) * ngr;
+                    if (p >= c1) continue;
+                    // 0 never failed, 1 failed before the operation, 2 failed during it
+                    uint32_t cls = 0;
+                    if (chunk_listed)
+                        for (uint32_t q = 0; q < g.f; ++q)
+                            if (vf.rank[q] == p) cls = vf.round[q] == 0 ? 1u : 2u;
+#pragma unroll
+                    for (int j = 0; j < V; ++j) {
+                        if (cls == 0) acc[j] = vcomb<T, OP>(acc[j], xv[u][j]);
+                        if constexpr (std::is_floating_point<T>::value) {
+                            if (cls != 1) sa[j] += fabs(double(xv[u][j]));
+                        }
                     }
-                    if (out && known) {
-                        // bitwise comparison, also for floating point: one root, one value
-                        const T o = out[size_t(p) * g.E + e];
-                        const T want = has ? res[e] : T(0);
-                        if (!same_bits(o, want)) my_bad = 1;
+                    if (check_holders) {
+                        bool has = cls == 0, known = cls == 0;
+                        if (hb && chunk_listed) {
+                            has = ((hb[p >> 5] >> (p & 31u)) & 1u) != 0u;
+                            known = true;
+                            if ((cls == 0 && !has) || (cls == 1 && has)) my_bad = 1;
+                        }
+                        if (out && known) {
+                            // bitwise comparison, also for floating point: one root, one value
+#pragma unroll
+                            for (int j = 0; j < V; ++j)
+                                if (!same_bits(ov[u][j], has ? want[j] : T(0))) my_bad = 1;
+                        }
                     }
                 }
             }
         }
         // fold the groups in order
         __syncthreads();
-        red[tid] = acc;
-        reda[tid] = sa;
+#pragma unroll
+        for (int j = 0; j < V; ++j) { red[j][tid] = acc[j]; reda[j][tid] = sa[j]; }
         __syncthreads();
         if (active && gr == 0) {
             for (uint32_t k = 1; k < ngr; ++k) {
-                acc = vcomb<T, OP>(acc, red[k * cols + col]);
-                sa += reda[k * cols + col];
+#pragma unroll
+                for (int j = 0; j < V; ++j) {
+                    acc[j] = vcomb<T, OP>(acc[j], red[j][k * cols + col]);
+                    sa[j] += reda[j][k * cols + col];
+                }
             }
-            const size_t o = (size_t(s) * A.nchunks + ch) * g.E + e;
-            reinterpret_cast<T*>(A.partial)[o * (8 / sizeof(T))] = acc;   // one 8-byte slot per value
-            A.scale[o] = sa;
+#pragma unroll
+            for (int j = 0; j < V; ++j) {
+                const size_t o = (size_t(s) * A.nchunks + ch) * g.E + e + uint32_t(j);
+                reinterpret_cast<T*>(A.partial)[o * (8 / sizeof(T))] = acc[j];   // one 8-byte slot per value
+                A.scale[o] = sa[j];
+            }
         }
     }
     if (my_bad) atomicOr(&bad_holder, 1u);
@@ -301,7 +354,13 @@ hipError_t launch_validate(const ValArgs& A, hipStream_t st)
 {
     {
         TimedLaunch tl(FTRED_PH_VAL_PARTIAL, st);
-        hipLaunchKernelGGL((val_partial_kernel<T, OP>), dim3(A.S * A.nchunks), dim3(256), 0, st, A);
+        // 16-byte loads where rows, scenarios and base addresses allow them
+        constexpr int VMAX = 16 / int(sizeof(T));
+        const bool wide = A.g.E % uint32_t(VMAX) == 0 && A.scen_stride_bytes % 16u == 0 &&
+                          reinterpret_cast<uintptr_t>(A.payload) % 16u == 0 &&
+                          (!A.out || reinterpret_cast<uintptr_t>(A.out) % 16u == 0);
+        if (wide) hipLaunchKernelGGL((val_partial_kernel<T, OP, VMAX>), dim3(A.S * A.nchunks), dim3(256), 0, st, A);
+        else hipLaunchKernelGGL((val_partial_kernel<T, OP, 1>), dim3(A.S * A.nchunks), dim3(256), 0, st, A);
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
