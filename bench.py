@@ -128,6 +128,17 @@ def main():
     for k in alg_bytes:
         kernels[k]["alg_GBs"] = round(alg_bytes[k] / (kernels[k]["ms_avg"] * 1e-3) / 1e9, 1)
     path_bytes = 4 * S * P * B             # the four passes above
+    # HBM bytes per launch from the counter runs kept under profiles/, while the kernels are still the
+    # ones the counters were taken with
+    traffic = None
+    tfile = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles",
+                         "hbm_traffic_allreduce_P16384_f4_S4096.txt")
+    if os.path.exists(tfile) and S == 4096 and args.lds_kib == 0:
+        from paper_2602_22445_amd import profile_summary
+        per_kernel, sha = profile_summary.read_traffic(tfile)
+        kname = {"tree_deep": "wave_tier_kernel", "bcast": "bcast_kernel", "val_partial": "val_partial_kernel"}[dom]
+        if sha == profile_summary.source_hash() and kname in per_kernel:
+            traffic = per_kernel[kname]
     out = {
         "metric": "simulated process-rounds/sec and HBM GB/s (P=16384, f=4 allreduce), 1 GPU",
         "value": value,
@@ -148,7 +159,7 @@ def main():
         "process_rounds_per_step": process_rounds,
         "hbm_GBs_whole_step_algorithmic": path_bytes / (elapsed / args.steps) / 1e9,
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None},
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic},
         "kernels": kernels,
         "input_setup_s": round(t_in, 2),
     }
