@@ -194,3 +194,76 @@ def allreduce_batch(P, f, payload, dtype, op, S, fail_rank=(), fail_round=(), th
         raise ValueError("oracle_allreduce_batch: invalid arguments")
     return dict(result=result, status=status, attempts=attempts, msgs=msgs, rounds=rounds,
                 has=has, out=out, threads=used)
+
+
+def _child_info(child, nfail):
+    """[S][f+1][3 + nfail] words -> per scenario a list of (state, counter, ids) per child of the root."""
+    out = []
+    for rows in child:
+        one = []
+        for row in rows:
+            if row[2] == NO_RANK:
+                raise AssertionError("a failure list outgrew the number of listed failures")
+            one.append((int(row[0]), int(row[1]), [int(q) for q in row[3:3 + int(row[2])]]))
+        out.append(one)
+    return out
+
+
+def _info_lists(info_nids, info_ids):
+    """[S][nfail] padded id arrays -> list of python lists (order as appended)."""
+    out = []
+    for n, ids in zip(info_nids, info_ids):
+        if n == NO_RANK:
+            raise AssertionError("a failure list outgrew the number of listed failures")
+        out.append([int(q) for q in ids[:int(n)]])
+    return out
+
+
+def reduce_info_batch(P, f, payload, dtype, op, S, root=None, fail_rank=(), fail_round=(), threads=0):
+    """S independent reduces with the first and second failure-information scheme
+    tracked (section "Failure information"): info_count[S] = the counter carried by
+    the message the root selected, info_ids = its list of failed processes (one
+    python list per scenario, physical ranks in the order appended)."""
+    lib = _load()
+    npdt, x, elems, stride, fr, fo, nfail = _batch_common(P, payload, dtype, S, fail_rank, fail_round)
+    rt = None if root is None else np.ascontiguousarray(np.asarray(root, dtype=np.uint32).reshape(S))
+    result = np.zeros((S, elems), npdt)
+    status = np.zeros(S, np.uint32)
+    msgs = np.zeros((S, 2), np.uint64)
+    count = np.zeros(S, np.uint32)
+    nids = np.zeros(S, np.uint32)
+    ids = np.zeros((S, nfail), np.uint32)
+    child = np.zeros((S, f + 1, 3 + nfail), np.uint32)
+    used = lib.oracle_reduce_info_batch(ctypes.c_uint32(P), ctypes.c_uint32(f), ctypes.c_uint32(elems),
+                                        ctypes.c_int(dtype), ctypes.c_int(op), ctypes.c_uint32(S), _p(rt),
+                                        _p(x), ctypes.c_uint64(stride), ctypes.c_uint32(nfail), _p(fr), _p(fo),
+                                        _p(result), _p(status), _p(msgs), _p(count), _p(nids), _p(ids),
+                                        _p(child), ctypes.c_int(threads))
+    if used < 0:
+        raise ValueError("oracle_reduce_info_batch: invalid arguments")
+    return dict(result=result, status=status, msgs=msgs, info_count=count, info_ids=_info_lists(nids, ids),
+                info_child=_child_info(child, nfail), threads=used)
+
+
+def allreduce_info_batch(P, f, payload, dtype, op, S, fail_rank=(), fail_round=(), threads=0):
+    """As reduce_info_batch for the allreduce: the failure information of the
+    reduce whose result every survivor holds."""
+    lib = _load()
+    npdt, x, elems, stride, fr, fo, nfail = _batch_common(P, payload, dtype, S, fail_rank, fail_round)
+    result = np.zeros((S, elems), npdt)
+    status = np.zeros(S, np.uint32)
+    attempts = np.zeros(S, np.uint32)
+    msgs = np.zeros((S, 4), np.uint64)
+    count = np.zeros(S, np.uint32)
+    nids = np.zeros(S, np.uint32)
+    ids = np.zeros((S, nfail), np.uint32)
+    child = np.zeros((S, f + 1, 3 + nfail), np.uint32)
+    used = lib.oracle_allreduce_info_batch(ctypes.c_uint32(P), ctypes.c_uint32(f), ctypes.c_uint32(elems),
+                                           ctypes.c_int(dtype), ctypes.c_int(op), ctypes.c_uint32(S),
+                                           _p(x), ctypes.c_uint64(stride), ctypes.c_uint32(nfail), _p(fr), _p(fo),
+                                           _p(result), _p(status), _p(attempts), _p(msgs), _p(count), _p(nids),
+                                           _p(ids), _p(child), ctypes.c_int(threads))
+    if used < 0:
+        raise ValueError("oracle_allreduce_info_batch: invalid arguments")
+    return dict(result=result, status=status, attempts=attempts, msgs=msgs, info_count=count,
+                info_ids=_info_lists(nids, ids), info_child=_child_info(child, nfail), threads=used)

@@ -23,6 +23,14 @@
  *   - failure information: the single "failed" bit, set in the tree phase when
  *     a child's value is missing, untouched in up-correction
  *                                             (section "Failure information")
+ *   - the two richer schemes of the same section (entry points *_info): every
+ *     process appends the id of each process it cannot receive a value from,
+ *     in the up-correction phase and in the tree phase, to a list; the list
+ *     travels with the tree message and a parent adds its children's lists to
+ *     its own (first scheme); only the length of that list travels (second
+ *     scheme).  Both are tracked side by side; which child the root selects
+ *     depends on the failed bit alone, so the value is the same in all schemes.
+ *     Reported: list and length carried by the message the root selects.
  *   - I(f)-tree: the root has f+1 children whose subtrees differ in size by at
  *     most one; process a is in subtree k iff (a-1) mod (f+1) == k-1
  *                                  (Definition and proof of the first theorem)
@@ -231,6 +239,9 @@ typedef struct msg {
     int kind;
     uint32_t src, dst;       /* virtual ranks */
     int flag;                /* failure information: the single failed bit */
+    uint32_t count;          /* second scheme: length of the sender's list */
+    uint32_t nids;           /* first scheme: the list itself (virtual ranks) */
+    uint32_t *ids;
     unsigned char *data;
 } msg_t;
 
@@ -260,6 +271,18 @@ typedef struct {
     unsigned char *trace_sent, *trace_flag; /* [P] or NULL */
     unsigned char *trace_msg; /* [P][bytes] or NULL */
     int disable_uc;
+    /* failure information, first and second scheme (tracked iff track_info) */
+    int track_info;
+    uint32_t flcap;          /* capacity of one list */
+    uint32_t *fl;            /* [P][flcap] ids a process could not receive a value from, and its children's lists */
+    uint32_t *fn;            /* [P] entries in fl */
+    uint32_t *fcount;        /* [P] the counter of the second scheme */
+    int info_overflow;       /* a list outgrew flcap (never, if concatenated lists are disjoint) */
+    uint32_t sel_count, sel_nids, sel_child;
+    uint32_t *sel_ids;       /* [flcap] list carried by the message the root selected */
+    /* what the root holds from each of its f+1 children at the end: state 0 = no message,
+       1 = message without the failed bit, 2 = message with the failed bit */
+    uint32_t *ch_state, *ch_count, *ch_nids, *ch_ids;   /* [f+1], [f+1], [f+1], [f+1][flcap] */
 } sim_t;
 
 static int alive(const sim_t *s, uint32_t v, uint32_t round)
@@ -306,6 +329,14 @@ static void net_send(sim_t *s, int kind, uint32_t src, uint32_t dst, const void 
 {
     msg_t *m = arena_alloc(s, sizeof(msg_t));
     m->next = NULL; m->kind = kind; m->src = src; m->dst = dst; m->flag = flag;
+    m->count = 0; m->nids = 0; m->ids = NULL;
+    if (s->track_info && kind == MSG_TREE) {
+        /* the sender's list (first scheme) and its length counter (second scheme) */
+        m->count = s->fcount[src];
+        m->nids = s->fn[src];
+        m->ids = arena_alloc(s, sizeof(uint32_t) * (m->nids + 1));
+        memcpy(m->ids, s->fl + (size_t)src * s->flcap, sizeof(uint32_t) * m->nids);
+    }
     m->data = arena_alloc(s, s->bytes);
     memcpy(m->data, data, s->bytes);
     if (s->inflight_tail) s->inflight_tail->next = m; else s->inflight_head = m;
@@ -348,6 +379,14 @@ static msg_t *inbox_take(sim_t *s, uint32_t v, int kind, uint32_t src)
     return NULL;
 }
 
+/* the first message of this kind from src, left in the inbox (or NULL) */
+static const msg_t *inbox_peek(const sim_t *s, uint32_t v, int kind, uint32_t src)
+{
+    const msg_t *m = s->inbox[v].head;
+    while (m && !(m->kind == kind && m->src == src)) m = m->next;
+    return m;
+}
+
 /* remove and return the first message of this kind (any sender) */
 static msg_t *inbox_take_any(sim_t *s, uint32_t v, int kind)
 {
@@ -363,6 +402,13 @@ static msg_t *inbox_take_any(sim_t *s, uint32_t v, int kind)
         prev = m; m = m->next;
     }
     return NULL;
+}
+
+/* process v could not receive a value from process id: append it to v's list */
+static void info_append(sim_t *s, uint32_t v, uint32_t id)
+{
+    if (s->fn[v] < s->flcap) s->fl[(size_t)v * s->flcap + s->fn[v]++] = id;
+    else s->info_overflow = 1;
 }
 
 static void clear_inboxes(sim_t *s)
@@ -387,6 +433,11 @@ static int run_reduce(sim_t *s, uint32_t base, void *result)
     /* every process starts from its input; "senddata" is the input itself */
     memcpy(s->data, s->input, (size_t)P * s->bytes);
     clear_inboxes(s);
+    if (s->track_info) {
+        memset(s->fn, 0, sizeof(uint32_t) * P);
+        memset(s->fcount, 0, sizeof(uint32_t) * P);
+        s->sel_count = s->sel_nids = 0;
+    }
 
     for (r = 1; r <= R; ++r) {
         const uint32_t now = base + r;
@@ -411,8 +462,17 @@ static int run_reduce(sim_t *s, uint32_t base, void *result)
                     if (m) {
                         combine(s->dtype, s->op, s->elems, fold, m->data);
                         if (m->flag) flag = 1;
+                        if (s->track_info) {       /* the parent adds the child's list to its own */
+                            uint32_t i;
+                            for (i = 0; i < m->nids; ++i) info_append(s, v, m->ids[i]);
+                            s->fcount[v] += m->count;
+                        }
                     } else {
                         flag = 1;    /* no value from this child */
+                        if (s->track_info) {
+                            info_append(s, v, t->kids[2 * (size_t)v + c]);
+                            s->fcount[v] += 1;
+                        }
                     }
                 }
                 net_send(s, MSG_TREE, v, (uint32_t)t->parent[v], fold, flag);
@@ -426,9 +486,20 @@ static int run_reduce(sim_t *s, uint32_t base, void *result)
         if (r <= f) {
             for (v = 0; v < P; ++v) {
                 msg_t *m;
+                int got = 0;
                 if (!alive(s, v, now)) continue;
-                while ((m = inbox_take_any(s, v, MSG_UC)) != NULL)
+                while ((m = inbox_take_any(s, v, MSG_UC)) != NULL) {
                     combine(s->dtype, s->op, s->elems, s->data + (size_t)v * s->bytes, m->data);
+                    got = 1;
+                }
+                if (s->track_info && !s->disable_uc && t->group[v] >= 0 && !got) {
+                    /* the member that sends to v in this round (R2) sent nothing */
+                    uint32_t g = (uint32_t)t->group[v], gs = t->gsize[g];
+                    if (r <= gs - 1) {
+                        info_append(s, v, t->gmembers[(size_t)g * gcap + (t->gpos[v] + gs - r) % gs]);
+                        s->fcount[v] += 1;
+                    }
+                }
             }
         }
         if (r == f && s->trace_v) memcpy(s->trace_v, s->data, (size_t)P * s->bytes);
@@ -438,6 +509,16 @@ static int run_reduce(sim_t *s, uint32_t base, void *result)
 
     /* --- the root, at the end of the last round --- */
     if (!alive(s, 0, base + R)) return OR_ST_ROOT_FAILED;
+    if (s->track_info) {
+        /* the failure information the root received, child by child */
+        for (c = 0; c < t->nkids[0]; ++c) {
+            const msg_t *m = inbox_peek(s, 0, MSG_TREE, t->root_kids[c]);
+            s->ch_state[c] = !m ? 0u : (m->flag ? 2u : 1u);
+            s->ch_count[c] = m ? m->count : 0u;
+            s->ch_nids[c] = m ? m->nids : 0u;
+            if (m) memcpy(s->ch_ids + (size_t)c * s->flcap, m->ids, sizeof(uint32_t) * m->nids);
+        }
+    }
     for (c = 0; c < t->nkids[0]; ++c) {
         uint32_t child = t->root_kids[c];
         msg_t *m = inbox_take(s, 0, MSG_TREE, child);
@@ -458,6 +539,12 @@ static int run_reduce(sim_t *s, uint32_t base, void *result)
         } else {
             memcpy(result, s->data, s->bytes);                   /* the root's value */
             combine(s->dtype, s->op, s->elems, result, m->data);
+        }
+        if (s->track_info) {
+            s->sel_child = c;
+            s->sel_count = m->count;
+            s->sel_nids = m->nids;
+            memcpy(s->sel_ids, m->ids, sizeof(uint32_t) * m->nids);
         }
         return OR_ST_OK;
     }
@@ -553,10 +640,48 @@ static void sim_init(sim_t *s, const topo_t *t, uint32_t elems, int dtype, int o
                (const unsigned char *)payload + (size_t)t->phys_of_virt[v] * s->bytes, s->bytes);
 }
 
+/* switch on the first and second failure-information scheme for this simulation */
+static void sim_track_info(sim_t *s)
+{
+    const uint32_t P = s->t->P;
+    s->track_info = 1;
+    s->flcap = 2 * s->nfail + 4;
+    s->fl = malloc(sizeof(uint32_t) * (size_t)P * s->flcap);
+    s->fn = calloc(P, sizeof(uint32_t));
+    s->fcount = calloc(P, sizeof(uint32_t));
+    s->sel_ids = calloc(s->flcap, sizeof(uint32_t));
+    s->ch_state = calloc(s->t->f + 1, sizeof(uint32_t));
+    s->ch_count = calloc(s->t->f + 1, sizeof(uint32_t));
+    s->ch_nids = calloc(s->t->f + 1, sizeof(uint32_t));
+    s->ch_ids = calloc((size_t)(s->t->f + 1) * s->flcap, sizeof(uint32_t));
+}
+
+/* the selected message's failure information, ids as physical ranks; nids = ORACLE_NO_RANK if a list overflowed */
+static void info_report(const sim_t *s, uint32_t nfail, uint32_t *info_count, uint32_t *info_nids, uint32_t *info_ids,
+                        uint32_t *child /* [f+1][3 + nfail]: state, counter, list length, list; or NULL */)
+{
+    uint32_t i, c;
+    for (i = 0; i < nfail; ++i) info_ids[i] = ORACLE_NO_RANK;
+    *info_count = s->sel_count;
+    *info_nids = s->info_overflow || s->sel_nids > nfail ? ORACLE_NO_RANK : s->sel_nids;
+    for (i = 0; i < s->sel_nids && i < nfail; ++i) info_ids[i] = s->t->phys_of_virt[s->sel_ids[i]];
+    if (!child) return;
+    for (c = 0; c <= s->t->f; ++c) {
+        uint32_t *row = child + (size_t)c * (3 + nfail);
+        row[0] = s->ch_state[c];
+        row[1] = s->ch_count[c];
+        row[2] = s->ch_nids[c] > nfail ? ORACLE_NO_RANK : s->ch_nids[c];
+        for (i = 0; i < nfail; ++i)
+            row[3 + i] = i < s->ch_nids[c] ? s->t->phys_of_virt[s->ch_ids[(size_t)c * s->flcap + i]] : ORACLE_NO_RANK;
+    }
+}
+
 static void sim_free(sim_t *s)
 {
     free(s->input); free(s->data); free(s->inbox); free(s->has); free(s->held);
     free(s->trace_v); free(s->trace_sent); free(s->trace_flag); free(s->trace_msg);
+    free(s->fl); free(s->fn); free(s->fcount); free(s->sel_ids);
+    free(s->ch_state); free(s->ch_count); free(s->ch_nids); free(s->ch_ids);
     arena_release(s);
 }
 
@@ -599,11 +724,12 @@ int oracle_structure(uint32_t P, uint32_t f, uint32_t root,
    and tree_msg[P][elems] = whether, with which failed bit and with which value
    each process sent its tree message.  disable_uc != 0 skips the up-correction
    sends (control experiment: the plain tree).  Returns 0, -1 on bad arguments. */
-int oracle_reduce(uint32_t P, uint32_t f, uint32_t elems, int dtype, int op, int disable_uc,
-                  uint32_t root, const void *payload,
-                  uint32_t nfail, const uint32_t *fail_rank, const uint32_t *fail_round,
-                  void *result, uint32_t *status, uint64_t *msgs, uint32_t *rounds,
-                  void *v_after_uc, uint8_t *tree_sent, uint8_t *tree_flag, void *tree_msg)
+static int reduce_impl(uint32_t P, uint32_t f, uint32_t elems, int dtype, int op, int disable_uc,
+                       uint32_t root, const void *payload,
+                       uint32_t nfail, const uint32_t *fail_rank, const uint32_t *fail_round,
+                       void *result, uint32_t *status, uint64_t *msgs, uint32_t *rounds,
+                       void *v_after_uc, uint8_t *tree_sent, uint8_t *tree_flag, void *tree_msg,
+                       uint32_t *info_count, uint32_t *info_nids, uint32_t *info_ids, uint32_t *info_child)
 {
     topo_t t;
     sim_t s;
@@ -613,6 +739,11 @@ int oracle_reduce(uint32_t P, uint32_t f, uint32_t elems, int dtype, int op, int
     if (topo_build(&t, P, f, root) != 0) { topo_free(&t); return -1; }
     *rounds = f + t.D;
     msgs[0] = msgs[1] = 0;
+    if (info_count) {
+        *info_count = *info_nids = 0;
+        for (v = 0; v < nfail; ++v) info_ids[v] = ORACLE_NO_RANK;
+        if (info_child) memset(info_child, 0, sizeof(uint32_t) * (f + 1) * (3 + nfail));
+    }
     if (check_failures(P, nfail, fail_rank) != 0) {
         *status = OR_ST_BAD_FAILURE_SET;
         topo_free(&t);
@@ -621,6 +752,7 @@ int oracle_reduce(uint32_t P, uint32_t f, uint32_t elems, int dtype, int op, int
     fv = malloc(sizeof(uint32_t) * (nfail + 1));
     sim_init(&s, &t, elems, dtype, op, payload, nfail, fail_rank, fail_round, fv);
     s.disable_uc = disable_uc;
+    if (info_count) sim_track_info(&s);
     if (v_after_uc) s.trace_v = calloc(P, s.bytes);
     if (tree_sent) s.trace_sent = calloc(P, 1);
     if (tree_flag) s.trace_flag = calloc(P, 1);
@@ -631,6 +763,7 @@ int oracle_reduce(uint32_t P, uint32_t f, uint32_t elems, int dtype, int op, int
     *status = (uint32_t)st;
     msgs[0] = s.sent[MSG_UC];
     msgs[1] = s.sent[MSG_TREE];
+    if (info_count && st == OR_ST_OK) info_report(&s, nfail, info_count, info_nids, info_ids, info_child);
     for (v = 0; v < P; ++v) {
         uint32_t p = t.phys_of_virt[v];
         if (v_after_uc) memcpy((unsigned char *)v_after_uc + (size_t)p * s.bytes, s.trace_v + (size_t)v * s.bytes, s.bytes);
@@ -644,6 +777,37 @@ int oracle_reduce(uint32_t P, uint32_t f, uint32_t elems, int dtype, int op, int
     return 0;
 }
 
+int oracle_reduce(uint32_t P, uint32_t f, uint32_t elems, int dtype, int op, int disable_uc,
+                  uint32_t root, const void *payload,
+                  uint32_t nfail, const uint32_t *fail_rank, const uint32_t *fail_round,
+                  void *result, uint32_t *status, uint64_t *msgs, uint32_t *rounds,
+                  void *v_after_uc, uint8_t *tree_sent, uint8_t *tree_flag, void *tree_msg)
+{
+    return reduce_impl(P, f, elems, dtype, op, disable_uc, root, payload, nfail, fail_rank, fail_round, result,
+                       status, msgs, rounds, v_after_uc, tree_sent, tree_flag, tree_msg, NULL, NULL, NULL, NULL);
+}
+
+/* One reduce with the first and second failure-information scheme tracked
+   (section "Failure information").  As oracle_reduce, plus: *info_count = the
+   counter of the second scheme and info_ids[nfail] / *info_nids = the list of the
+   first scheme (physical ranks, in the order appended, padded with
+   ORACLE_NO_RANK) carried by the message the root selected; zeros / padding unless
+   *status == OK.  *info_nids == ORACLE_NO_RANK reports a list that outgrew the
+   number of listed failures (concatenated lists were not disjoint).
+   info_child (may be NULL): [f+1][3 + nfail] words, for each child of the root in
+   the order of the subtrees: state (0 no message, 1 message without the failed
+   bit, 2 with it), counter, list length, list (physical ranks, padded). */
+int oracle_reduce_info(uint32_t P, uint32_t f, uint32_t elems, int dtype, int op,
+                       uint32_t root, const void *payload,
+                       uint32_t nfail, const uint32_t *fail_rank, const uint32_t *fail_round,
+                       void *result, uint32_t *status, uint64_t *msgs, uint32_t *rounds,
+                       uint32_t *info_count, uint32_t *info_nids, uint32_t *info_ids, uint32_t *info_child)
+{
+    if (!info_count || !info_nids || !info_ids) return -1;
+    return reduce_impl(P, f, elems, dtype, op, 0, root, payload, nfail, fail_rank, fail_round, result,
+                       status, msgs, rounds, NULL, NULL, NULL, NULL, info_count, info_nids, info_ids, info_child);
+}
+
 /* One allreduce.  Roots tried: physical ranks 0,1,..,f.  A failure listed for
    one of these ranks with fail_round != 0 is outside the semantics (the roots
    may fail only before the operation) => BAD_FAILURE_SET.  Global rounds keep
@@ -652,11 +816,12 @@ int oracle_reduce(uint32_t P, uint32_t f, uint32_t elems, int dtype, int op, int
    out[P][elems] (the value held, zeros where has == 0; may be NULL);
    *attempts; msgs[4] = {up-correction, tree, broadcast tree, broadcast correction}
    summed over all attempts; *rounds = attempts * 2(f+D). */
-int oracle_allreduce(uint32_t P, uint32_t f, uint32_t elems, int dtype, int op,
-                     const void *payload,
-                     uint32_t nfail, const uint32_t *fail_rank, const uint32_t *fail_round,
-                     void *result, uint32_t *status, uint32_t *attempts, uint64_t *msgs,
-                     uint32_t *rounds, uint8_t *has, void *out)
+static int allreduce_impl(uint32_t P, uint32_t f, uint32_t elems, int dtype, int op,
+                          const void *payload,
+                          uint32_t nfail, const uint32_t *fail_rank, const uint32_t *fail_round,
+                          void *result, uint32_t *status, uint32_t *attempts, uint64_t *msgs,
+                          uint32_t *rounds, uint8_t *has, void *out,
+                          uint32_t *info_count, uint32_t *info_nids, uint32_t *info_ids, uint32_t *info_child)
 {
     uint32_t a, i, v, base = 0;
     size_t bytes;
@@ -670,6 +835,11 @@ int oracle_allreduce(uint32_t P, uint32_t f, uint32_t elems, int dtype, int op,
     if (out) memset(out, 0, (size_t)P * bytes);
     msgs[0] = msgs[1] = msgs[2] = msgs[3] = 0;
     *attempts = 0; *rounds = 0;
+    if (info_count) {
+        *info_count = *info_nids = 0;
+        for (i = 0; i < nfail; ++i) info_ids[i] = ORACLE_NO_RANK;
+        if (info_child) memset(info_child, 0, sizeof(uint32_t) * (f + 1) * (3 + nfail));
+    }
     if (check_failures(P, nfail, fail_rank) != 0) { *status = OR_ST_BAD_FAILURE_SET; return 0; }
     for (i = 0; i < nfail; ++i)
         if (fail_rank[i] != ORACLE_NO_RANK && fail_rank[i] <= f && fail_round[i] != 0) {
@@ -685,6 +855,7 @@ int oracle_allreduce(uint32_t P, uint32_t f, uint32_t elems, int dtype, int op,
         topo_build(&t, P, f, a);
         Ra = 2 * (f + t.D);
         sim_init(&s, &t, elems, dtype, op, payload, nfail, fail_rank, fail_round, fv);
+        if (info_count) sim_track_info(&s);
         *attempts = a + 1;
         rst = run_reduce(&s, base, result);
         msgs[0] += s.sent[MSG_UC];
@@ -705,6 +876,7 @@ int oracle_allreduce(uint32_t P, uint32_t f, uint32_t elems, int dtype, int op,
             st = OR_ST_NO_CLEAN_SUBTREE;
         } else if (n_ok == n_alive && n_alive > 0 && rst == OR_ST_OK) {
             st = OR_ST_OK;
+            if (info_count) info_report(&s, nfail, info_count, info_nids, info_ids, info_child);   /* of the reduce that counted */
             for (v = 0; v < P; ++v) {
                 uint32_t p = t.phys_of_virt[v];
                 has[p] = s.has[v];
@@ -725,6 +897,30 @@ int oracle_allreduce(uint32_t P, uint32_t f, uint32_t elems, int dtype, int op,
     *status = (uint32_t)st;
     free(fv);
     return 0;
+}
+
+int oracle_allreduce(uint32_t P, uint32_t f, uint32_t elems, int dtype, int op,
+                     const void *payload,
+                     uint32_t nfail, const uint32_t *fail_rank, const uint32_t *fail_round,
+                     void *result, uint32_t *status, uint32_t *attempts, uint64_t *msgs,
+                     uint32_t *rounds, uint8_t *has, void *out)
+{
+    return allreduce_impl(P, f, elems, dtype, op, payload, nfail, fail_rank, fail_round, result, status, attempts,
+                          msgs, rounds, has, out, NULL, NULL, NULL, NULL);
+}
+
+/* One allreduce with the failure information of oracle_reduce_info, taken from
+   the reduce of the attempt whose result every survivor holds. */
+int oracle_allreduce_info(uint32_t P, uint32_t f, uint32_t elems, int dtype, int op,
+                          const void *payload,
+                          uint32_t nfail, const uint32_t *fail_rank, const uint32_t *fail_round,
+                          void *result, uint32_t *status, uint32_t *attempts, uint64_t *msgs,
+                          uint32_t *rounds, uint8_t *has, void *out,
+                          uint32_t *info_count, uint32_t *info_nids, uint32_t *info_ids, uint32_t *info_child)
+{
+    if (!info_count || !info_nids || !info_ids) return -1;
+    return allreduce_impl(P, f, elems, dtype, op, payload, nfail, fail_rank, fail_round, result, status, attempts,
+                          msgs, rounds, has, out, info_count, info_nids, info_ids, info_child);
 }
 
 /* Batches: scenario i uses payload + i*payload_stride_bytes (stride 0 = one
@@ -784,6 +980,75 @@ int oracle_allreduce_batch(uint32_t P, uint32_t f, uint32_t elems, int dtype, in
                                   attempts + i, msgs + 4 * (size_t)i, rounds + i, h,
                                   out ? (unsigned char *)out + (size_t)i * P * bytes : NULL);
         if (!has) free(h);
+        if (rc != 0) {
+#pragma omp atomic write
+            bad = 1;
+        }
+    }
+    return bad ? -1 : used;
+}
+
+/* Batches of oracle_reduce_info / oracle_allreduce_info: info_count[S],
+   info_nids[S], info_ids[S][nfail], info_child[S][f+1][3 + nfail] (or NULL). */
+int oracle_reduce_info_batch(uint32_t P, uint32_t f, uint32_t elems, int dtype, int op,
+                             uint32_t S, const uint32_t *root,
+                             const void *payload, uint64_t payload_stride_bytes,
+                             uint32_t nfail, const uint32_t *fail_rank, const uint32_t *fail_round,
+                             void *result, uint32_t *status, uint64_t *msgs,
+                             uint32_t *info_count, uint32_t *info_nids, uint32_t *info_ids,
+                             uint32_t *info_child, int threads)
+{
+    int64_t i;
+    int bad = 0, used = 1;
+    size_t bytes = elems * elem_size(dtype);
+#ifdef _OPENMP
+    if (threads > 0) omp_set_num_threads(threads);
+    used = omp_get_max_threads();
+#endif
+#pragma omp parallel for schedule(dynamic, 1)
+    for (i = 0; i < (int64_t)S; ++i) {
+        uint32_t rounds;
+        int rc = oracle_reduce_info(P, f, elems, dtype, op, root ? root[i] : 0,
+                                    (const unsigned char *)payload + (size_t)i * payload_stride_bytes,
+                                    nfail, fail_rank + (size_t)i * nfail, fail_round + (size_t)i * nfail,
+                                    (unsigned char *)result + (size_t)i * bytes, status + i,
+                                    msgs + 2 * (size_t)i, &rounds,
+                                    info_count + i, info_nids + i, info_ids + (size_t)i * nfail,
+                                    info_child ? info_child + (size_t)i * (f + 1) * (3 + nfail) : NULL);
+        if (rc != 0) {
+#pragma omp atomic write
+            bad = 1;
+        }
+    }
+    return bad ? -1 : used;
+}
+
+int oracle_allreduce_info_batch(uint32_t P, uint32_t f, uint32_t elems, int dtype, int op,
+                                uint32_t S, const void *payload, uint64_t payload_stride_bytes,
+                                uint32_t nfail, const uint32_t *fail_rank, const uint32_t *fail_round,
+                                void *result, uint32_t *status, uint32_t *attempts, uint64_t *msgs,
+                                uint32_t *info_count, uint32_t *info_nids, uint32_t *info_ids,
+                             uint32_t *info_child, int threads)
+{
+    int64_t i;
+    int bad = 0, used = 1;
+    size_t bytes = elems * elem_size(dtype);
+#ifdef _OPENMP
+    if (threads > 0) omp_set_num_threads(threads);
+    used = omp_get_max_threads();
+#endif
+#pragma omp parallel for schedule(dynamic, 1)
+    for (i = 0; i < (int64_t)S; ++i) {
+        uint8_t *h = malloc(P);
+        uint32_t rounds;
+        int rc = oracle_allreduce_info(P, f, elems, dtype, op,
+                                       (const unsigned char *)payload + (size_t)i * payload_stride_bytes,
+                                       nfail, fail_rank + (size_t)i * nfail, fail_round + (size_t)i * nfail,
+                                       (unsigned char *)result + (size_t)i * bytes, status + i,
+                                       attempts + i, msgs + 4 * (size_t)i, &rounds, h, NULL,
+                                       info_count + i, info_nids + i, info_ids + (size_t)i * nfail,
+                                    info_child ? info_child + (size_t)i * (f + 1) * (3 + nfail) : NULL);
+        free(h);
         if (rc != 0) {
 #pragma omp atomic write
             bad = 1;
