@@ -173,6 +173,36 @@ int ftred_run_allreduce(const ftred_plan_t *plan, uint32_t S,
                         uint32_t *status, uint32_t *attempts, uint64_t *msgs,
                         void *workspace, uint64_t workspace_bytes, void *hip_stream);
 
+/* The same operations with the two richer failure descriptions of section
+   "Failure information" carried by the tree messages beside the failed bit: the
+   list of the processes a sender and its descendants could not receive a value
+   from, in the up-correction phase and in the tree phase (first scheme), and the
+   length of that list (second scheme).  The value, the status and the counters
+   are those of ftred_run_reduce / ftred_run_allreduce: which child the root
+   selects depends on the failed bit alone.  Extra outputs (each may be NULL, not
+   all three); for the allreduce they describe the reduce of the last attempt:
+     info_count  dev [S] length of the list carried by the message the root selected
+     info_ids    dev [S][max(f,1)] that list: ranks in the order of the scenario's
+                 failure list, padded with FTRED_NO_RANK
+     info_child  dev [S][f+1] what the root holds from child k+1 (the top of subtree
+                 k+1) at the end: bits 16..17 = 0 no message, 1 message without the
+                 failed bit, 2 message with it; bits 0..15 = its list as a set of
+                 slots of the scenario's failure list (bit q = fail_rank[s][q])
+   All three are zero / FTRED_NO_RANK for a scenario without a result. */
+int ftred_run_reduce_info(const ftred_plan_t *plan, uint32_t S, const uint32_t *root,
+                          const void *payload, uint64_t scen_stride_elems,
+                          const uint32_t *fail_rank, const uint32_t *fail_round,
+                          void *result, uint32_t *status, uint64_t *msgs,
+                          uint32_t *info_count, uint32_t *info_ids, uint32_t *info_child,
+                          void *workspace, uint64_t workspace_bytes, void *hip_stream);
+int ftred_run_allreduce_info(const ftred_plan_t *plan, uint32_t S,
+                             const void *payload, uint64_t scen_stride_elems,
+                             const uint32_t *fail_rank, const uint32_t *fail_round,
+                             void *result, uint32_t *has_bitmap, void *per_process_out,
+                             uint32_t *status, uint32_t *attempts, uint64_t *msgs,
+                             uint32_t *info_count, uint32_t *info_ids, uint32_t *info_child,
+                             void *workspace, uint64_t workspace_bytes, void *hip_stream);
+
 /* Check results against the semantics (sections "Reduce / Semantics", items 3
    and 4, and "Allreduce / Semantics", items 4 and 5; message-count theorems),
    independently of the protocol: per scenario the reduction over the never-failed

@@ -72,6 +72,10 @@ def lib():
         L.ftred_structure.argtypes = [_vp, _u32] + [_vp] * 8
         L.ftred_run_reduce.argtypes = [_vp, _u32, _vp, _vp, _u64, _vp, _vp, _vp, _vp, _vp, _vp, _u64, _vp]
         L.ftred_run_allreduce.argtypes = [_vp, _u32, _vp, _u64, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _u64, _vp]
+        L.ftred_run_reduce_info.argtypes = [_vp, _u32, _vp, _vp, _u64, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _u64,
+                                            _vp]
+        L.ftred_run_allreduce_info.argtypes = [_vp, _u32, _vp, _u64, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp,
+                                               _vp, _vp, _u64, _vp]
         L.ftred_validate.argtypes = [_vp, _int, _u32, _vp, _vp, _u64, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp,
                                      ctypes.POINTER(_u64), _vp, _u64, _vp]
         L.ftred_gen_failures.argtypes = [_vp, _u64, _u32, _u32, _u32, _u32, _u32, _vp, _vp, _vp, _vp]
@@ -195,6 +199,52 @@ def run_allreduce(plan, S, payload, fail_rank, fail_round, want_bitmap=True, wan
                                      _ptr(result), _ptr(bitmap), _ptr(out), _ptr(status), _ptr(attempts),
                                      _ptr(msgs), _ptr(ws), ws.numel(), _stream(stream)))
     return dict(result=result, has_bitmap=bitmap, per_process_out=out, status=status, attempts=attempts, msgs=msgs)
+
+
+def _info_buffers(plan, S, dev):
+    return (torch.empty(S, dtype=torch.uint32, device=dev),
+            torch.empty((S, plan.F), dtype=torch.uint32, device=dev),
+            torch.empty((S, plan.f + 1), dtype=torch.uint32, device=dev))
+
+
+def run_reduce_info(plan, S, payload, fail_rank, fail_round, root=None, workspace=None, stream=None):
+    """ftred_run_reduce_info.  As run_reduce, plus info_count[S], info_ids[S][F], info_child[S][f+1]."""
+    stride = _payload_stride(plan, payload, S)
+    _fail(plan, S, fail_rank, fail_round)
+    dev = payload.device
+    if root is not None:
+        assert root.is_cuda and root.dtype == torch.uint32 and tuple(root.shape) == (S,)
+    result = torch.empty((S, plan.elems), dtype=TORCH_DTYPE[plan.dtype], device=dev)
+    status = torch.empty(S, dtype=torch.uint32, device=dev)
+    msgs = torch.empty((S, 2), dtype=torch.uint64, device=dev)
+    count, ids, child = _info_buffers(plan, S, dev)
+    ws = workspace if workspace is not None else plan.workspace(S, dev)
+    _check(lib().ftred_run_reduce_info(plan.handle, S, _ptr(root), _ptr(payload), stride, _ptr(fail_rank),
+                                       _ptr(fail_round), _ptr(result), _ptr(status), _ptr(msgs), _ptr(count),
+                                       _ptr(ids), _ptr(child), _ptr(ws), ws.numel(), _stream(stream)))
+    return dict(result=result, status=status, msgs=msgs, info_count=count, info_ids=ids, info_child=child)
+
+
+def run_allreduce_info(plan, S, payload, fail_rank, fail_round, workspace=None, stream=None):
+    """ftred_run_allreduce_info.  As run_allreduce, plus info_count[S], info_ids[S][F], info_child[S][f+1]."""
+    stride = _payload_stride(plan, payload, S)
+    _fail(plan, S, fail_rank, fail_round)
+    dev = payload.device
+    dt = TORCH_DTYPE[plan.dtype]
+    result = torch.empty((S, plan.elems), dtype=dt, device=dev)
+    status = torch.empty(S, dtype=torch.uint32, device=dev)
+    attempts = torch.empty(S, dtype=torch.uint32, device=dev)
+    bitmap = torch.empty((S, (plan.P + 31) // 32), dtype=torch.uint32, device=dev)
+    out = torch.empty((S, plan.P, plan.elems), dtype=dt, device=dev)
+    msgs = torch.empty((S, 4), dtype=torch.uint64, device=dev)
+    count, ids, child = _info_buffers(plan, S, dev)
+    ws = workspace if workspace is not None else plan.workspace(S, dev)
+    _check(lib().ftred_run_allreduce_info(plan.handle, S, _ptr(payload), stride, _ptr(fail_rank), _ptr(fail_round),
+                                          _ptr(result), _ptr(bitmap), _ptr(out), _ptr(status), _ptr(attempts),
+                                          _ptr(msgs), _ptr(count), _ptr(ids), _ptr(child), _ptr(ws), ws.numel(),
+                                          _stream(stream)))
+    return dict(result=result, has_bitmap=bitmap, per_process_out=out, status=status, attempts=attempts, msgs=msgs,
+                info_count=count, info_ids=ids, info_child=child)
 
 
 def validate(plan, kind, S, payload, fail_rank, fail_round, result, status, root=None, has_bitmap=None,

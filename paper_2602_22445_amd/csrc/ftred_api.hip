@@ -144,8 +144,9 @@ extern "C" int ftred_plan(ftred_plan_t** out, uint32_t P, uint32_t f, uint32_t e
     // tiers of the tree phase, deepest first.  The deepest tier reads the payload
     // and wants many workgroups per CU (small tiles); the upper tiers are small.
     const uint32_t stage_rows = kStageBytes / g.RB;               // rows the prefetch registers hold
-    uint32_t cap0 = budget / (g.RB + 4u);
-    uint32_t cap1 = (56u * 1024u) / (g.RB + 4u);
+    const uint32_t per_row = g.RB + 4u + 2u * g.W;          // values, meta word, lists
+    uint32_t cap0 = budget / per_row;
+    uint32_t cap1 = (56u * 1024u) / per_row;
     if (cap0 > stage_rows) cap0 = stage_rows;
     if (cap1 > 2u * stage_rows + 1u) cap1 = 2u * stage_rows + 1u;
     if (cap0 < 1 || cap1 < 3) {
@@ -183,16 +184,22 @@ extern "C" int ftred_plan(ftred_plan_t** out, uint32_t P, uint32_t f, uint32_t e
         const uint32_t h = td.dhi - td.dlo;
         td.is_top = td.dlo == 0 ? 1u : 0u;
         td.lds_rows = ((2u << h) - 1u) + (td.child_in ? (2u << h) : 0u);
-        td.lds_bytes = uint32_t(sizeof(FailTab)) + align_up(td.lds_rows * 4u, 16) + td.lds_rows * g.RB;
+        td.lds_bytes = uint32_t(sizeof(FailTab)) + align_up(td.lds_rows * 4u, 16) + align_up(td.lds_rows * g.RB, 16) +
+                       align_up(td.lds_rows * g.W * 2u, 16);      // failure table, meta words, rows, lists
         if (td.lds_bytes > p->max_lds) p->max_lds = td.lds_bytes;
         td.kshift = td.dlo < kwalk ? td.dlo : kwalk;
         td.gshift = td.dlo - td.kshift;
-        if (t > 0) { td.in_off = p->tiers[t - 1].out_off; td.in_meta_off = p->tiers[t - 1].out_meta_off; }
+        if (t > 0) {
+            td.in_off = p->tiers[t - 1].out_off; td.in_meta_off = p->tiers[t - 1].out_meta_off;
+            td.in_mask_off = p->tiers[t - 1].out_mask_off;
+        }
         if (!td.is_top) {
             td.out_off = off;
             off += align_up((1u << td.dlo) * g.RB, 16);
             td.out_meta_off = off;
             off += align_up((1u << td.dlo) * 4u, 16);
+            td.out_mask_off = off;
+            off += align_up((1u << td.dlo) * g.W * 2u, 16);
         }
     }
     if (p->use_wave) {
@@ -392,19 +399,40 @@ static void fill_run_args(RunArgs& A, const ftred_plan_t* p, uint32_t S, const v
 // ---------------------------------------------------------------------------
 // reduce
 
-extern "C" int ftred_run_reduce(const ftred_plan_t* plan, uint32_t S, const uint32_t* root, const void* payload,
-                                uint64_t scen_stride_elems, const uint32_t* fail_rank, const uint32_t* fail_round,
-                                void* result, uint32_t* status, uint64_t* msgs, void* workspace,
-                                uint64_t workspace_bytes, void* hip_stream)
+// outputs of the richer failure-information schemes (all three may be nullptr)
+struct InfoOut {
+    uint32_t* count;
+    uint32_t* ids;
+    uint32_t* child;
+    bool any() const { return count || ids || child; }
+};
+
+// the outputs start empty: scenarios without a result keep that
+static hipError_t clear_info(const Geom& g, uint32_t S, const InfoOut& io, hipStream_t st)
 {
-    int rc = check_common("ftred_run_reduce", plan, S, payload, scen_stride_elems, fail_rank, fail_round, workspace,
-                          workspace_bytes);
+    const size_t F = g.f > 0 ? g.f : 1;
+    if (io.count) hipLaunchKernelGGL(fill_words_kernel, dim3((S + 255u) / 256u), dim3(256), 0, st, io.count, size_t(S), 0u);
+    if (io.ids)
+        hipLaunchKernelGGL(fill_words_kernel, dim3(uint32_t((S * F + 255u) / 256u)), dim3(256), 0, st, io.ids, S * F, kNoRank);
+    if (io.child)
+        hipLaunchKernelGGL(fill_words_kernel, dim3(uint32_t((size_t(S) * g.W + 255u) / 256u)), dim3(256), 0, st, io.child,
+                           size_t(S) * g.W, 0u);
+    return hipGetLastError();
+}
+
+static int run_reduce_impl(const char* who, const ftred_plan_t* plan, uint32_t S, const uint32_t* root,
+                           const void* payload, uint64_t scen_stride_elems, const uint32_t* fail_rank,
+                           const uint32_t* fail_round, void* result, uint32_t* status, uint64_t* msgs,
+                           const InfoOut& io, void* workspace, uint64_t workspace_bytes, void* hip_stream)
+{
+    int rc = check_common(who, plan, S, payload, scen_stride_elems, fail_rank, fail_round, workspace, workspace_bytes);
     if (rc != FTRED_OK) return rc;
-    if (!result || !status) return fail(FTRED_EINVAL, "ftred_run_reduce: result and status are required");
+    if (!result || !status) return fail(FTRED_EINVAL, "%s: result and status are required", who);
     if (reinterpret_cast<uintptr_t>(result) % plan->g.esz != 0)
-        return fail(FTRED_EINVAL, "ftred_run_reduce: result must be aligned to the element size");
+        return fail(FTRED_EINVAL, "%s: result must be aligned to the element size", who);
     hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
     const Geom& g = plan->g;
+    if (io.any()) HIP_TRY(clear_info(g, S, io, st));
 
     {
         TimedLaunch tl(FTRED_PH_CHECK, st);
@@ -424,25 +452,52 @@ extern "C" int ftred_run_reduce(const ftred_plan_t* plan, uint32_t S, const uint
     A.result = static_cast<unsigned char*>(result);
     A.msgs = reinterpret_cast<unsigned long long*>(msgs);
     A.nmsg = 2;
+    A.info = io.any() ? 1u : 0u;
+    A.info_count = io.count;
+    A.info_ids = io.ids;
+    A.info_child = io.child;
     return launch_tiers(plan, A, S, 0, st);
+}
+
+extern "C" int ftred_run_reduce(const ftred_plan_t* plan, uint32_t S, const uint32_t* root, const void* payload,
+                                uint64_t scen_stride_elems, const uint32_t* fail_rank, const uint32_t* fail_round,
+                                void* result, uint32_t* status, uint64_t* msgs, void* workspace,
+                                uint64_t workspace_bytes, void* hip_stream)
+{
+    return run_reduce_impl("ftred_run_reduce", plan, S, root, payload, scen_stride_elems, fail_rank, fail_round, result,
+                           status, msgs, InfoOut{nullptr, nullptr, nullptr}, workspace, workspace_bytes, hip_stream);
+}
+
+extern "C" int ftred_run_reduce_info(const ftred_plan_t* plan, uint32_t S, const uint32_t* root, const void* payload,
+                                     uint64_t scen_stride_elems, const uint32_t* fail_rank, const uint32_t* fail_round,
+                                     void* result, uint32_t* status, uint64_t* msgs, uint32_t* info_count,
+                                     uint32_t* info_ids, uint32_t* info_child, void* workspace,
+                                     uint64_t workspace_bytes, void* hip_stream)
+{
+    if (!info_count && !info_ids && !info_child)
+        return fail(FTRED_EINVAL, "ftred_run_reduce_info: at least one of info_count, info_ids, info_child is required");
+    return run_reduce_impl("ftred_run_reduce_info", plan, S, root, payload, scen_stride_elems, fail_rank, fail_round,
+                           result, status, msgs, InfoOut{info_count, info_ids, info_child}, workspace, workspace_bytes,
+                           hip_stream);
 }
 
 // ---------------------------------------------------------------------------
 // allreduce
 
-extern "C" int ftred_run_allreduce(const ftred_plan_t* plan, uint32_t S, const void* payload, uint64_t scen_stride_elems,
-                                   const uint32_t* fail_rank, const uint32_t* fail_round, void* result,
-                                   uint32_t* has_bitmap, void* per_process_out, uint32_t* status, uint32_t* attempts,
-                                   uint64_t* msgs, void* workspace, uint64_t workspace_bytes, void* hip_stream)
+static int run_allreduce_impl(const char* who, const ftred_plan_t* plan, uint32_t S, const void* payload,
+                              uint64_t scen_stride_elems, const uint32_t* fail_rank, const uint32_t* fail_round,
+                              void* result, uint32_t* has_bitmap, void* per_process_out, uint32_t* status,
+                              uint32_t* attempts, uint64_t* msgs, const InfoOut& io, void* workspace,
+                              uint64_t workspace_bytes, void* hip_stream)
 {
-    int rc = check_common("ftred_run_allreduce", plan, S, payload, scen_stride_elems, fail_rank, fail_round, workspace,
-                          workspace_bytes);
+    int rc = check_common(who, plan, S, payload, scen_stride_elems, fail_rank, fail_round, workspace, workspace_bytes);
     if (rc != FTRED_OK) return rc;
-    if (!result || !status || !attempts) return fail(FTRED_EINVAL, "ftred_run_allreduce: result, status and attempts are required");
+    if (!result || !status || !attempts) return fail(FTRED_EINVAL, "%s: result, status and attempts are required", who);
     if (reinterpret_cast<uintptr_t>(result) % plan->g.esz != 0 || reinterpret_cast<uintptr_t>(per_process_out) % plan->g.esz != 0)
-        return fail(FTRED_EINVAL, "ftred_run_allreduce: result and per_process_out must be aligned to the element size");
+        return fail(FTRED_EINVAL, "%s: result and per_process_out must be aligned to the element size", who);
     hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
     const Geom& g = plan->g;
+    if (io.any()) HIP_TRY(clear_info(g, S, io, st));
 
     unsigned char* wsb = static_cast<unsigned char*>(workspace);
     uint32_t* retry_list = reinterpret_cast<uint32_t*>(wsb + ws_list_off(plan, S));
@@ -464,6 +519,10 @@ extern "C" int ftred_run_allreduce(const ftred_plan_t* plan, uint32_t S, const v
     A.result = static_cast<unsigned char*>(result);
     A.msgs = reinterpret_cast<unsigned long long*>(msgs);
     A.nmsg = 4;
+    A.info = io.any() ? 1u : 0u;
+    A.info_count = io.count;
+    A.info_ids = io.ids;
+    A.info_child = io.child;
     const uint32_t slots = g.f > 0 ? kRetrySlots : 0u;
     A.retry_list = retry_list;
     A.retry_count = retry_count;
@@ -505,4 +564,28 @@ extern "C" int ftred_run_allreduce(const ftred_plan_t* plan, uint32_t S, const v
     }
     HIP_TRY(hipGetLastError());
     return FTRED_OK;
+}
+
+extern "C" int ftred_run_allreduce(const ftred_plan_t* plan, uint32_t S, const void* payload, uint64_t scen_stride_elems,
+                                   const uint32_t* fail_rank, const uint32_t* fail_round, void* result,
+                                   uint32_t* has_bitmap, void* per_process_out, uint32_t* status, uint32_t* attempts,
+                                   uint64_t* msgs, void* workspace, uint64_t workspace_bytes, void* hip_stream)
+{
+    return run_allreduce_impl("ftred_run_allreduce", plan, S, payload, scen_stride_elems, fail_rank, fail_round, result,
+                              has_bitmap, per_process_out, status, attempts, msgs, InfoOut{nullptr, nullptr, nullptr},
+                              workspace, workspace_bytes, hip_stream);
+}
+
+extern "C" int ftred_run_allreduce_info(const ftred_plan_t* plan, uint32_t S, const void* payload,
+                                        uint64_t scen_stride_elems, const uint32_t* fail_rank,
+                                        const uint32_t* fail_round, void* result, uint32_t* has_bitmap,
+                                        void* per_process_out, uint32_t* status, uint32_t* attempts, uint64_t* msgs,
+                                        uint32_t* info_count, uint32_t* info_ids, uint32_t* info_child, void* workspace,
+                                        uint64_t workspace_bytes, void* hip_stream)
+{
+    if (!info_count && !info_ids && !info_child)
+        return fail(FTRED_EINVAL, "ftred_run_allreduce_info: at least one of info_count, info_ids, info_child is required");
+    return run_allreduce_impl("ftred_run_allreduce_info", plan, S, payload, scen_stride_elems, fail_rank, fail_round,
+                              result, has_bitmap, per_process_out, status, attempts, msgs,
+                              InfoOut{info_count, info_ids, info_child}, workspace, workspace_bytes, hip_stream);
 }

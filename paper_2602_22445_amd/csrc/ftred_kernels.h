@@ -71,6 +71,7 @@ struct TierDesc {
     uint32_t is_top;            // 1: dlo == 0, ends with the root's choice
     uint32_t in_off, in_meta_off;    // scratch offsets (bytes inside one scenario's scratch)
     uint32_t out_off, out_meta_off;
+    uint32_t in_mask_off, out_mask_off;   // failure lists of the messages (16 bits per member), see process_lists
     uint32_t lds_rows;          // rows of LDS the tier stages
     uint32_t lds_bytes;         // dynamic LDS of the launch
     uint32_t kshift;            // a workgroup walks through 2^kshift consecutive cones
@@ -104,7 +105,10 @@ struct RunArgs {
     uint32_t* fix_list;          // pairs (scenario or S + retry entry, first cone): subtrees of the deepest
     uint32_t* fix_count;         //   tier left to the general kernel by the wavefront kernel
     uint32_t fix_kshift;         // cones per entry = 2^fix_kshift
-    uint32_t pad1;
+    uint32_t info;               // 1: carry the lists of failed processes with the tree messages
+    uint32_t* info_count;        // [S] or nullptr
+    uint32_t* info_ids;          // [S][max(f,1)] or nullptr
+    uint32_t* info_child;        // [S][W] or nullptr
     TierDesc tiers[kMaxTiers];
 };
 
@@ -275,6 +279,51 @@ __device__ __forceinline__ void process_item(const Geom& g, const FailTab& ft, T
     }
 }
 
+// The lists of failed processes the tree messages of one row carry (first scheme
+// of section "Failure information"; the second scheme sends their length): lmask
+// holds, per LDS row, W 16-bit words, a set of slots of the scenario's failure
+// list (only listed processes ever fail to send).  A member adds the group mates
+// whose up-correction message did not come, the children that sent nothing, and
+// its children's lists.  Concatenated lists are disjoint, so the length is the
+// number of bits.  Runs beside process_item on the same level: reads the children's
+// meta words and lists, writes the row's lists.
+__device__ __forceinline__ void process_lists(const Geom& g, const FailTab& ft, const uint32_t* meta, uint16_t* lmask,
+                                              uint32_t li, uint32_t j, bool kids_in_lds, bool check_fail)
+{
+    const uint32_t W = g.W;
+    const bool last = (j == g.M - 1);
+    const uint32_t gs = (last && g.a > 1) ? g.a : W;      // group size, root included
+    for (uint32_t i = 0; i < W; ++i) {
+        uint32_t mk = 0;
+        if (check_fail && i < gs) {
+            // member i misses the message of listed member w, due in round t = (i - w) mod gs, iff w sends in
+            // fewer rounds than t
+            for (uint32_t q = 0; q < ft.n; ++q) {
+                if (ft.row[q] != j || ft.idx[q] == i) continue;
+                const uint32_t w = ft.idx[q];
+                const uint32_t t = w < i ? i - w : i + gs - w;
+                if (t > ft.uc[q]) mk |= 1u << q;
+            }
+        }
+        if (kids_in_lds) {
+            for (uint32_t c = 0; c < 2; ++c) {
+                const uint32_t jc = 2u * j + 1u + c;
+                if (jc >= g.M) continue;
+                const uint32_t lc = 2u * li + 1u + c;
+                const uint32_t nkc = (jc == g.M - 1) ? g.nlast : W;
+                if (i >= nkc) continue;
+                if ((meta[lc] >> i) & 1u) {
+                    mk |= lmask[size_t(lc) * W + i];               // the child's list
+                } else {
+                    for (uint32_t q = 0; q < ft.n; ++q)            // the child itself
+                        if (ft.row[q] == jc && ft.idx[q] == i) mk |= 1u << q;
+                }
+            }
+        }
+        lmask[size_t(li) * W + i] = uint16_t(mk);
+    }
+}
+
 // Workgroup barrier that orders LDS traffic only: prefetch loads of the next cone
 // stay in flight across it (a full __syncthreads would wait for them).
 __device__ __forceinline__ void lds_barrier()
@@ -424,7 +473,7 @@ __device__ __forceinline__ bool cone_has_failure(const FailTab& ft, uint32_t r, 
 // tier above or the root's choice.  LDS-only barriers; ends with one.
 template <class T, int OP, int WP>
 __device__ __forceinline__ void cone_rounds(const RunArgs& A, const TierDesc& td, const FailTab& ft, T* rows,
-                                            uint32_t* lmeta, uint32_t s, uint32_t root, uint32_t cone,
+                                            uint32_t* lmeta, uint16_t* lmask, uint32_t s, uint32_t root, uint32_t cone,
                                             const unsigned char* pay, unsigned char* wsS, bool discard,
                                             uint32_t& uc_cnt, uint32_t& tree_cnt)
 {
@@ -449,6 +498,9 @@ __device__ __forceinline__ void cone_rounds(const RunArgs& A, const TierDesc& td
                 process_item<T, OP, WP>(g, ft, rows, lmeta, lfirst + lr, gfirst + lr, e, kids, check_fail,
                                         vroot_out, uc_cnt, tree_cnt);
             }
+            if (lmask != nullptr)
+                for (uint32_t lr = tid; lr < cnt; lr += kThreads)
+                    process_lists(g, ft, lmeta, lmask, lfirst + lr, gfirst + lr, kids, check_fail);
         }
         lds_barrier();
     }
@@ -462,6 +514,8 @@ __device__ __forceinline__ void cone_rounds(const RunArgs& A, const TierDesc& td
             for (uint32_t o = tid; o < g.W * g.E; o += kThreads) reinterpret_cast<T*>(dst)[o] = rows[o];
         }
         if (tid == 0) reinterpret_cast<uint32_t*>(wsS + td.out_meta_off)[cone] = lmeta[0];
+        if (lmask != nullptr && tid < g.W)
+            reinterpret_cast<uint16_t*>(wsS + td.out_mask_off)[size_t(cone) * g.W + tid] = lmask[tid];
     } else if (!discard) {
         // Algorithm "reduce at the root": lowest-numbered child whose message is
         // present and reports no failure; the root adds its own value iff that
@@ -489,6 +543,32 @@ __device__ __forceinline__ void cone_rounds(const RunArgs& A, const TierDesc& td
             res[e] = val;
         }
         if (tid == 0) A.status[s] = st;
+        if (A.info) {
+            // what the root received from each child, and the list of the message it selected, as
+            // slots of the failure list; the ranks themselves in slot order
+            const uint32_t F = g.f > 0 ? g.f : 1;
+            const uint32_t ks = st == kStOk ? uint32_t(__ffs(int(okm))) - 1u : 0u;
+            const uint32_t sel = st == kStOk ? uint32_t(lmask[ks]) : 0u;
+            if (A.info_child && tid < g.W) {
+                uint32_t w = 0;
+                if (st != kStRootFailed && tid < nk0) {
+                    const uint32_t present = (cm >> tid) & 1u, fbit = (cm >> (16u + tid)) & 1u;
+                    w = present ? ((fbit ? 2u : 1u) << 16) | uint32_t(lmask[tid]) : 0u;
+                }
+                A.info_child[size_t(s) * g.W + tid] = w;
+            }
+            if (A.info_count && tid == 0) A.info_count[s] = uint32_t(__popc(sel));
+            if (A.info_ids && tid < F) {
+                // the tid-th set bit of sel
+                uint32_t rank = kNoRank, seen = 0;
+                for (uint32_t q = 0; q < g.f; ++q)
+                    if ((sel >> q) & 1u) {
+                        if (seen == tid) rank = A.fail_rank[size_t(s) * F + q];
+                        ++seen;
+                    }
+                A.info_ids[size_t(s) * F + tid] = rank;
+            }
+        }
     }
     lds_barrier();
 }
@@ -496,7 +576,8 @@ __device__ __forceinline__ void cone_rounds(const RunArgs& A, const TierDesc& td
 // messages of the level below an upper tier's cone, from scratch into LDS
 template <class T>
 __device__ __forceinline__ void stage_children(const RunArgs& A, const TierDesc& td, unsigned char* lrows_b,
-                                               uint32_t* lmeta, const unsigned char* wsS, uint32_t cone)
+                                               uint32_t* lmeta, uint16_t* lmask, const unsigned char* wsS,
+                                               uint32_t cone)
 {
     const Geom& g = A.g;
     const uint32_t h = td.dhi - td.dlo;
@@ -510,6 +591,10 @@ __device__ __forceinline__ void stage_children(const RunArgs& A, const TierDesc&
     else copy_to_lds<T>(lrows_b + size_t(nx) * g.RB, src, cc * g.RB);
     const uint32_t* msrc = reinterpret_cast<const uint32_t*>(wsS + td.in_meta_off) + size_t(cone) * per;
     for (uint32_t i = threadIdx.x; i < cc; i += kThreads) lmeta[nx + i] = msrc[i];
+    if (lmask != nullptr) {
+        const uint16_t* ksrc = reinterpret_cast<const uint16_t*>(wsS + td.in_mask_off) + size_t(cone) * per * g.W;
+        for (uint32_t i = threadIdx.x; i < cc * g.W; i += kThreads) lmask[size_t(nx) * g.W + i] = ksrc[i];
+    }
 }
 
 // A workgroup's walk through its cones of one tier of one (scenario, attempt).
@@ -517,10 +602,12 @@ template <class T, int OP, int WP, class V>
 __device__ __forceinline__ void walk_cones(const RunArgs& A, const TierDesc& td, FailTab& ft, unsigned char* lrows,
                                            uint32_t* lmeta, uint32_t s, uint32_t root, uint32_t base,
                                            uint32_t c_lo, uint32_t c_hi, const unsigned char* pay,
-                                           unsigned char* wsS, bool discard)
+                                           unsigned char* wsS, bool discard, uint32_t lds_rows_max)
 {
     const Geom& g = A.g;
     const uint32_t h = td.dhi - td.dlo;
+    // the lists of the staged rows sit behind the rows (16 bits per member)
+    uint16_t* lmask = A.info ? reinterpret_cast<uint16_t*>(lrows + ((size_t(lds_rows_max) * g.RB + 15u) & ~size_t(15))) : nullptr;
     Stage<V> stg;
     stg.init(g, td.dlo, h);
     stg.issue(g, pay, c_lo, root);                 // in flight while the failure list is resolved
@@ -530,10 +617,10 @@ __device__ __forceinline__ void walk_cones(const RunArgs& A, const TierDesc& td,
         const uint32_t r = (1u << td.dlo) - 1u + cone;
         stg.commit(lrows);
         stage_patches<V>(g, lrows, pay, r, h, root);
-        if (td.child_in) stage_children<T>(A, td, lrows, lmeta, wsS, cone);
+        if (td.child_in) stage_children<T>(A, td, lrows, lmeta, lmask, wsS, cone);
         __syncthreads();
         if (cone + 1 < c_hi) stg.issue(g, pay, cone + 1, root);    // prefetch
-        cone_rounds<T, OP, WP>(A, td, ft, reinterpret_cast<T*>(lrows), lmeta, s, root, cone, pay, wsS, discard,
+        cone_rounds<T, OP, WP>(A, td, ft, reinterpret_cast<T*>(lrows), lmeta, lmask, s, root, cone, pay, wsS, discard,
                                uc_cnt, tree_cnt);
     }
     if (A.msgs) {
@@ -587,8 +674,8 @@ __global__ void __launch_bounds__(kThreads) tier_kernel(RunArgs A)
     uint32_t* lmeta = reinterpret_cast<uint32_t*>(smem + sizeof(FailTab));
     unsigned char* lrows = smem + sizeof(FailTab) + ((size_t(td.lds_rows) * 4u + 15u) & ~size_t(15));
     const unsigned char* pay = A.payload + size_t(s) * A.scen_stride_bytes;
-    if constexpr (VEC) walk_cones<T, OP, WP, vec16_t>(A, td, ft, lrows, lmeta, s, root, base, c_lo, c_hi, pay, wsS, discard);
-    else walk_cones<T, OP, WP, T>(A, td, ft, lrows, lmeta, s, root, base, c_lo, c_hi, pay, wsS, discard);
+    if constexpr (VEC) walk_cones<T, OP, WP, vec16_t>(A, td, ft, lrows, lmeta, s, root, base, c_lo, c_hi, pay, wsS, discard, td.lds_rows);
+    else walk_cones<T, OP, WP, T>(A, td, ft, lrows, lmeta, s, root, base, c_lo, c_hi, pay, wsS, discard, td.lds_rows);
 }
 
 // The deepest tier's cones that the wavefront kernel handed over (failures, the
@@ -631,8 +718,8 @@ __global__ void __launch_bounds__(kThreads) tier_list_kernel(RunArgs A)
         }
         const unsigned char* pay = A.payload + size_t(s) * A.scen_stride_bytes;
         __syncthreads();              // the previous entry is done with LDS
-        if constexpr (VEC) walk_cones<T, OP, WP, vec16_t>(A, td, ft, lrows, lmeta, s, root, base, c_lo, c_hi, pay, wsS, discard);
-        else walk_cones<T, OP, WP, T>(A, td, ft, lrows, lmeta, s, root, base, c_lo, c_hi, pay, wsS, discard);
+        if constexpr (VEC) walk_cones<T, OP, WP, vec16_t>(A, td, ft, lrows, lmeta, s, root, base, c_lo, c_hi, pay, wsS, discard, td.lds_rows);
+        else walk_cones<T, OP, WP, T>(A, td, ft, lrows, lmeta, s, root, base, c_lo, c_hi, pay, wsS, discard, td.lds_rows);
     }
 }
 
@@ -662,7 +749,7 @@ __global__ void __launch_bounds__(kThreads) retry_kernel(RunArgs A)
             uint32_t c_hi = 1u << td.dlo;
             if (top0 + c_hi > A.g.M) c_hi = A.g.M - top0;
             __syncthreads();          // scratch rows of the tier below are complete and visible
-            walk_cones<T, OP, WP, T>(A, td, ft, lrows, lmeta, s, root, base, 0, c_hi, pay, wsB, true);   // element-wise staging
+            walk_cones<T, OP, WP, T>(A, td, ft, lrows, lmeta, s, root, base, 0, c_hi, pay, wsB, true, max_rows);   // element-wise staging
         }
     }
 }

@@ -71,6 +71,12 @@ __global__ void zero_words_kernel(uint32_t* p, uint32_t n)
     if (i < n) p[i] = 0u;
 }
 
+__global__ void fill_words_kernel(uint32_t* p, size_t n, uint32_t value)
+{
+    const size_t i = size_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = value;
+}
+
 __global__ void prepass_kernel(Geom g, uint32_t kind /* 0 reduce, 1 allreduce */, uint32_t S, const uint32_t* root,
                                const uint32_t* fail_rank, const uint32_t* fail_round, uint32_t* status,
                                uint32_t* attempts, unsigned long long* msgs, uint32_t nmsg, unsigned char* result,

@@ -257,7 +257,14 @@ __global__ void __launch_bounds__(kWaveThreads) wave_tier_kernel(RunArgs A, Wave
             unsigned char* dst = wsS + td.out_off + size_t(cone) * g.RB + size_t(ecol) * g.esz;
 #pragma unroll
             for (int k = 0; k < WP; ++k) *reinterpret_cast<T*>(dst + size_t(k) * g.EB) = out[k];
-            if (ecol == 0) reinterpret_cast<uint32_t*>(wsS + td.out_meta_off)[cone] = (1u << g.W) - 1u;   // all sent, no failed bit
+            if (ecol == 0) {
+                reinterpret_cast<uint32_t*>(wsS + td.out_meta_off)[cone] = (1u << g.W) - 1u;   // all sent, no failed bit
+                if (A.info) {         // and nobody in the subtree missed a message: empty lists
+                    uint16_t* mk = reinterpret_cast<uint16_t*>(wsS + td.out_mask_off) + size_t(cone) * g.W;
+#pragma unroll
+                    for (int k = 0; k < WP; ++k) mk[k] = 0;
+                }
+            }
         }
     }
     // every process of the rows folded here sent all its messages
