@@ -35,7 +35,7 @@ class FtredError(RuntimeError):
 class Info(ctypes.Structure):
     _fields_ = [(n, ctypes.c_uint32) for n in
                 ("P", "f", "elems", "dtype", "op", "groups_full", "a", "D", "rounds_reduce", "rounds_attempt",
-                 "tiers", "reserved")] + \
+                 "tiers", "deep_kernel")] + \
                [(n, ctypes.c_uint64) for n in
                 ("msgs_uc_ff", "msgs_tree_ff", "msgs_bcast_tree_ff", "msgs_bcast_corr_ff")]
 

@@ -236,6 +236,7 @@ extern "C" int ftred_plan_info(const ftred_plan_t* plan, ftred_info_t* info)
     info->rounds_reduce = g.Rred;
     info->rounds_attempt = g.Ratt;
     info->tiers = plan->ntiers;
+    info->deep_kernel = plan->use_wave;
     info->msgs_uc_ff = msgs_uc_ff(g);
     info->msgs_tree_ff = g.P - 1;
     info->msgs_bcast_tree_ff = g.P - 1;
