@@ -310,7 +310,19 @@ __global__ void __launch_bounds__(kThreads) bcast_kernel(BcastArgs B)
         unsigned char* dst = B.out + (size_t(s) * g.P + c0) * g.EB;
         const unsigned char* res = B.result + size_t(s) * g.EB;
         const uint32_t bytes = (c1 - c0) * g.EB;
-        if (B.vec16) {
+        if (B.vec16 && (kThreads * 16u) % g.EB == 0u) {
+            // a thread's 16 bytes sit at the same place of a value in every pass: one load of the result
+            const uint32_t o0 = tid * 16u;
+            const uint32_t r0 = fdiv(o0, g.divEB);
+            const vec16_t mine = *reinterpret_cast<const vec16_t*>(res + (o0 - r0 * g.EB));
+            const vec16_t zero = {0u, 0u, 0u, 0u};
+            const uint32_t rstep = (kThreads * 16u) / g.EB;
+            uint32_t rr = r0;
+            for (uint32_t o = o0; o < bytes; o += kThreads * 16u, rr += rstep) {
+                const bool has = ((bits[rr >> 5] >> (rr & 31u)) & 1u) != 0u;
+                __builtin_nontemporal_store(has ? mine : zero, reinterpret_cast<vec16_t*>(dst + o));   // written once, read by others
+            }
+        } else if (B.vec16) {
             for (uint32_t o = tid * 16u; o < bytes; o += kThreads * 16u) {
                 const uint32_t rr = fdiv(o, g.divEB);
                 const uint32_t within = o - rr * g.EB;

@@ -233,7 +233,7 @@ template <class T, int OP>
 __global__ void __launch_bounds__(256) val_final_kernel(ValArgs A)
 {
     extern __shared__ __align__(16) unsigned char smem[];
-    __shared__ uint32_t s_inop[16];
+    __shared__ uint32_t s_inop[16], s_fr[16], s_fo[16];
     __shared__ uint32_t s_ninop, s_found, s_expect;
     const Geom& g = A.g;
     const uint32_t tid = threadIdx.x;
@@ -243,8 +243,15 @@ __global__ void __launch_bounds__(256) val_final_kernel(ValArgs A)
     double* scale = reinterpret_cast<double*>(smem + size_t(g.E) * 8u); // [E]
     const T* x = reinterpret_cast<const T*>(A.payload + size_t(s) * A.scen_stride_bytes);
     const T* res = reinterpret_cast<const T*>(A.result) + size_t(s) * g.E;
-    const uint32_t* fr = A.fail_rank + size_t(s) * F;
-    const uint32_t* fo = A.fail_round + size_t(s) * F;
+    const uint32_t nthr = blockDim.x;
+    // the failure list goes through LDS: one round trip to memory instead of one per entry
+    if (tid < 16) {
+        s_fr[tid] = tid < F ? A.fail_rank[size_t(s) * F + tid] : kNoRank;
+        s_fo[tid] = tid < F ? A.fail_round[size_t(s) * F + tid] : 0u;
+    }
+    __syncthreads();
+    const uint32_t* fr = s_fr;
+    const uint32_t* fo = s_fo;
 
     // ---- the scenario's failure set: expected status, processes failed during the operation
     if (tid == 0) {
@@ -304,7 +311,7 @@ __global__ void __launch_bounds__(256) val_final_kernel(ValArgs A)
         if (v) atomicOr(&A.verdict[s], v);
     }
     // ---- reduction over the never-failed processes: chunk partials in order
-    for (uint32_t e = tid; e < g.E; e += 256u) {
+    for (uint32_t e = tid; e < g.E; e += nthr) {
         T acc = T(0);
         double sa = 0.0;
         for (uint32_t c = 0; c < A.nchunks; ++c) {
@@ -321,7 +328,7 @@ __global__ void __launch_bounds__(256) val_final_kernel(ValArgs A)
         const uint32_t k = s_ninop;
         const uint32_t nsub = 1u << k;
         uint32_t found = 0;
-        for (uint32_t sub = tid; sub < nsub && !found; sub += 256u) {
+        for (uint32_t sub = tid; sub < nsub && !found; sub += nthr) {
             bool all = true;
             for (uint32_t e = 0; e < g.E && all; ++e) {
                 T cand = base[e];
@@ -367,7 +374,8 @@ hipError_t launch_validate(const ValArgs& A, hipStream_t st)
     const uint32_t lds = A.g.E * 16u;
     {
         TimedLaunch tl(FTRED_PH_VAL_FINAL, st);
-        hipLaunchKernelGGL((val_final_kernel<T, OP>), dim3(A.S), dim3(256), lds, st, A);
+        // one wavefront per scenario unless there are many value indices: the work is a few dependent loads
+        hipLaunchKernelGGL((val_final_kernel<T, OP>), dim3(A.S), dim3(A.g.E <= 64u ? 64 : 256), lds, st, A);
     }
     return hipGetLastError();
 }
