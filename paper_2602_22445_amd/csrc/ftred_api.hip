@@ -556,6 +556,9 @@ static int run_allreduce_impl(const char* who, const ftred_plan_t* plan, uint32_
     B.div_nchunks = make_fastdiv(B.nchunks);
     B.vec16 = (g.EB % 16 == 0 && reinterpret_cast<uintptr_t>(result) % 16 == 0 &&
                (!per_process_out || reinterpret_cast<uintptr_t>(per_process_out) % 16 == 0)) ? 1u : 0u;
+    // values of 4 or 8 bytes: 4 or 2 receive buffers per 16-byte store (a chunk starts at a multiple of 32 ranks)
+    B.small16 = ((g.EB == 4 || g.EB == 8) && per_process_out && reinterpret_cast<uintptr_t>(per_process_out) % 16 == 0 &&
+                 (uint64_t(g.P) * g.EB) % 16 == 0) ? 1u : 0u;
     if (uint64_t(S) * B.nchunks >= (uint64_t(1) << 31))
         return fail(FTRED_EUNSUPPORTED, "ftred_run_allreduce: S = %u scenarios need too many workgroups; split the batch", S);
     const uint32_t lds = bcast_lds_bytes(B);

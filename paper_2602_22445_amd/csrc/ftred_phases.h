@@ -137,6 +137,7 @@ struct BcastArgs {
     uint32_t chunk, nchunks;
     FastDiv div_nchunks;
     uint32_t vec16;
+    uint32_t small16;              // one value of 4 or 8 bytes per process: several receive buffers per store
 };
 
 struct BcastFail {
@@ -321,6 +322,25 @@ __global__ void __launch_bounds__(kThreads) bcast_kernel(BcastArgs B)
             for (uint32_t o = o0; o < bytes; o += kThreads * 16u, rr += rstep) {
                 const bool has = ((bits[rr >> 5] >> (rr & 31u)) & 1u) != 0u;
                 __builtin_nontemporal_store(has ? mine : zero, reinterpret_cast<vec16_t*>(dst + o));   // written once, read by others
+            }
+        } else if (B.small16) {
+            // 16 bytes = the receive buffers of 16 / EB consecutive processes
+            const uint32_t per = 16u / g.EB, wpr = g.EB / 4u;         // processes per store, words per value
+            const uint32_t r0w = reinterpret_cast<const uint32_t*>(res)[0];
+            const uint32_t r1w = wpr > 1u ? reinterpret_cast<const uint32_t*>(res)[1] : r0w;
+            const uint32_t nvec = bytes / 16u;                       // whole: P * EB is a multiple of 16, so is the chunk
+            for (uint32_t i = tid; i < nvec; i += kThreads) {
+                const uint32_t rr = i * per;
+                const uint32_t m = (bits[rr >> 5] >> (rr & 31u));    // per <= 4 and rr % per == 0: same word
+                vec16_t val;
+                if (wpr == 2u) {
+                    val.x = (m & 1u) ? r0w : 0u; val.y = (m & 1u) ? r1w : 0u;
+                    val.z = (m & 2u) ? r0w : 0u; val.w = (m & 2u) ? r1w : 0u;
+                } else {
+                    val.x = (m & 1u) ? r0w : 0u; val.y = (m & 2u) ? r0w : 0u;
+                    val.z = (m & 4u) ? r0w : 0u; val.w = (m & 8u) ? r0w : 0u;
+                }
+                __builtin_nontemporal_store(val, reinterpret_cast<vec16_t*>(dst + size_t(i) * 16u));
             }
         } else if (B.vec16) {
             for (uint32_t o = tid * 16u; o < bytes; o += kThreads * 16u) {

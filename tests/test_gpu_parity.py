@@ -149,6 +149,8 @@ ALLREDUCE_CASES = [
     (1500, 4, 8, 2, 0, 128, 500), (4099, 5, 3, 2, 0, 48, 500), (20000, 2, 4, 1, 0, 24, 500),
     (33333, 4, 8, 2, 0, 12, 500), (3000, 12, 2, 0, 0, 32, 500), (1 << 16, 8, 1, 0, 0, 6, 250),
     (3000, 1, 80, 1, 0, 24, 500), (2000, 2, 4, 1, 1, 64, 500), (700, 1, 3, 0, 1, 64, 500), (9000, 3, 5, 2, 0, 24, 500),
+    # one 4-byte value per process: four receive buffers per store; and a P that rules that path out
+    (1004, 2, 1, 1, 0, 64, 500), (1003, 2, 1, 1, 1, 64, 500),
 ]
 
 
