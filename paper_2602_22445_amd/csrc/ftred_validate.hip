@@ -234,7 +234,7 @@ __global__ void __launch_bounds__(256) val_final_kernel(ValArgs A)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     __shared__ uint32_t s_inop[16], s_fr[16], s_fo[16];
-    __shared__ uint32_t s_ninop, s_found, s_expect;
+    __shared__ uint32_t s_ninop, s_found, s_expect, s_verdict;
     const Geom& g = A.g;
     const uint32_t tid = threadIdx.x;
     const uint32_t s = blockIdx.x;
@@ -308,7 +308,7 @@ __global__ void __launch_bounds__(256) val_final_kernel(ValArgs A)
                 if (none && (m[2] != g.P - 1u || m[3] != A.uc_ff)) v |= FTRED_BAD_COUNT;
             }
         }
-        if (v) atomicOr(&A.verdict[s], v);
+        s_verdict = v;          // this pass's findings; only this workgroup touches the scenario's verdict now
     }
     // ---- reduction over the never-failed processes: chunk partials in order
     for (uint32_t e = tid; e < g.E; e += nthr) {
@@ -346,13 +346,14 @@ __global__ void __launch_bounds__(256) val_final_kernel(ValArgs A)
         }
         if (found) atomicOr(&s_found, 1u);
         __syncthreads();
-        if (tid == 0 && !s_found) atomicOr(&A.verdict[s], uint32_t(FTRED_BAD_VALUE));
+        if (tid == 0 && !s_found) s_verdict |= uint32_t(FTRED_BAD_VALUE);
     }
     __syncthreads();
     if (tid == 0) {
-        __threadfence();
-        // pass 1 of this scenario has finished (earlier kernel), so the verdict is final
-        if (atomicOr(&A.verdict[s], 0u) != 0u) atomicAdd(A.n_invalid, 1ull);
+        // pass 1 of this scenario has finished (earlier kernel): its bits are in memory, the verdict is final
+        const uint32_t all = A.verdict[s] | s_verdict;
+        if (s_verdict != 0u) A.verdict[s] = all;
+        if (all != 0u) atomicAdd(A.n_invalid, 1ull);
     }
 }
 
