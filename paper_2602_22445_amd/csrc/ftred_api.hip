@@ -132,7 +132,7 @@ extern "C" int ftred_plan(ftred_plan_t** out, uint32_t P, uint32_t f, uint32_t e
         budget = (flags & 0xFFu) * 1024u;
     }
     if (((flags >> 8) & 0xFu) != 0) kwalk = ((flags >> 8) & 0xFu) - 1u;
-    if ((flags >> 13) != 0) return fail(FTRED_EINVAL, "ftred_plan: unknown flag bits");
+    if ((flags >> 16) != 0) return fail(FTRED_EINVAL, "ftred_plan: unknown flag bits");
     ftred_plan_t* p = new (std::nothrow) ftred_plan_t;
     if (!p) return fail(FTRED_ENOMEM, "ftred_plan: out of host memory");
     memset(p, 0, sizeof(*p));
@@ -204,7 +204,9 @@ extern "C" int ftred_plan(ftred_plan_t** out, uint32_t P, uint32_t f, uint32_t e
     }
     if (p->use_wave) {
         p->wl = make_wave_layout(g, p->tiers[0].dlo);
-        p->wave_gshift = p->tiers[0].dlo - p->wl.slot_shift;      // one wavefront per workgroup
+        const uint32_t most = p->tiers[0].dlo - p->wl.slot_shift;
+        if ((flags >> 13) & 7u) p->wl.group_shift = ((flags >> 13) & 7u) - 1u < most ? ((flags >> 13) & 7u) - 1u : most;
+        p->wave_gshift = most - p->wl.group_shift;                // one wavefront per workgroup
     }
     p->ws_scen = align_up(off, 256);
     p->retry_blocks = 64;
@@ -336,7 +338,10 @@ static int launch_tiers(const ftred_plan_t* plan, RunArgs& A, uint32_t S, uint32
         A.tier = t;
         TimedLaunch tl(t == 0 ? FTRED_PH_TREE_DEEP : FTRED_PH_TREE_UPPER, st);
         if (t == 0 && plan->use_wave) {
-            // pure subtrees: one wavefront each; the others: listed, then the general kernel
+            // subtrees with listed processes, relabelled ranks, the short last group or a ragged bottom are listed
+            // and run by the general kernel; the register kernel runs all the others
+            hipLaunchKernelGGL(fixlist_kernel, dim3((S + extra + 255u) / 256u), dim3(256), 0, st, A);
+            HIP_TRY(hipGetLastError());
             HIP_TRY(dispatch_wave(plan, A, (S + extra) << plan->wave_gshift, st));
             uint64_t cap = (uint64_t(S) + extra) * (plan->g.f + 3u);
             HIP_TRY(dispatch_list(plan, A, uint32_t(cap < 4096u ? cap : 4096u), plan->tiers[0].lds_bytes, st));

@@ -7,6 +7,7 @@
 
 #include "ftred_geom.h"
 #include "ftred_kernels.h"
+#include "ftred_wave.h"
 
 namespace ftred {
 
@@ -112,6 +113,56 @@ __global__ void prepass_kernel(Geom g, uint32_t kind /* 0 reduce, 1 allreduce */
         for (uint32_t k = 0; k < nmsg; ++k) msgs[size_t(s) * nmsg + k] = 0ull;
     if (bad)
         for (uint32_t b = 0; b < g.EB; b += 4) *reinterpret_cast<uint32_t*>(result + size_t(s) * g.EB + b) = 0u;
+}
+
+// One thread per scenario (or retry entry): the subtrees of the deepest tier that
+// the general LDS-tile kernel has to run, each once, appended to the list (one
+// atomic per wavefront: the counter is a single hot word).
+__global__ void __launch_bounds__(256) fixlist_kernel(RunArgs A)
+{
+    const Geom& g = A.g;
+    const uint32_t dlo = A.tiers[0].dlo;
+    const uint32_t sv = blockIdx.x * blockDim.x + threadIdx.x;
+    const uint32_t F = g.f > 0 ? g.f : 1;
+    uint32_t cones[18], nc = 0;
+    bool live = sv < A.S + A.retry_slots;
+    uint32_t s = sv, root = 0;
+    if (live) {
+        if (sv < A.S) {
+            if (A.status[s] == kStBadFailureSet) live = false;
+            else if (A.attempts) root = A.attempts[s] - 1u;
+            else if (A.root) root = A.root[s];
+        } else {
+            const uint32_t kk = sv - A.S;
+            if (kk >= *A.retry_count) live = false;
+            else { s = A.retry_list[2u * kk]; root = A.retry_list[2u * kk + 1u]; }
+        }
+    }
+    if (live)
+        for_each_special_row(g, dlo, A.fail_rank + size_t(s) * F, root, [&](uint32_t jr) {
+            const uint32_t c = subtree_of_row(jr, dlo);
+            if (c == kNoRank) return;
+            bool dup = false;
+            for (uint32_t k = 0; k < nc; ++k) dup = dup || cones[k] == c;
+            if (!dup) cones[nc++] = c;
+        });
+    // exclusive prefix sum of nc over the wavefront, one atomic for all of it
+    const uint32_t lane = threadIdx.x & 63u;
+    uint32_t incl = nc;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const uint32_t up = __shfl_up(incl, d);
+        if (lane >= uint32_t(d)) incl += up;
+    }
+    const uint32_t total = __shfl(incl, 63);
+    uint32_t base = 0;
+    if (lane == 0 && total != 0) base = atomicAdd(A.fix_count, total);
+    base = __shfl(base, 0);
+    const uint32_t at = base + incl - nc;
+    for (uint32_t k = 0; k < nc; ++k) {
+        A.fix_list[2u * (at + k)] = sv;
+        A.fix_list[2u * (at + k) + 1u] = cones[k];
+    }
 }
 
 // ---------------------------------------------------------------------------

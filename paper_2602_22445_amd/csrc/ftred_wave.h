@@ -33,12 +33,14 @@ namespace ftred {
 
 constexpr int kWaveH = 4;            // height of the subtree one lane walks
 constexpr int kWaveThreads = 64;     // one wavefront per workgroup: lanes are independent
+constexpr uint32_t kWaveRows = (2u << kWaveH) - 1u;
 
 struct WaveLayout {                  // how the 64 lanes map to (subtree slot, value index)
     uint32_t ne;                     // value indices per pass
     uint32_t slot_shift;             // 2^slot_shift sibling subtrees per wavefront
     uint32_t nact;                   // active lanes = slots * ne
     uint32_t passes;                 // ceil(E / ne)
+    uint32_t group_shift;            // a wavefront walks through 2^group_shift groups of subtrees
 };
 
 // group widths the kernel is built for (straight-line code per width)
@@ -53,6 +55,10 @@ inline WaveLayout make_wave_layout(const Geom& g, uint32_t dlo)
     w.slot_shift = sh;
     w.nact = (1u << sh) * w.ne;
     w.passes = (g.E + w.ne - 1u) / w.ne;
+    // enough bytes per wavefront to outweigh its start: about 64 KiB of rows or more
+    w.group_shift = 0;
+    while (w.group_shift < dlo - sh &&
+           (uint64_t(kWaveRows) << (sh + w.group_shift)) * g.RB < 64u * 1024u) ++w.group_shift;
     return w;
 }
 
@@ -160,47 +166,70 @@ struct SubtreeWalk {
     }
 };
 
+// The subtree (of height kWaveH below a row of depth dlo) that holds row jr: its
+// number among the subtrees of that depth, or kNoRank if the row lies above or
+// below them.
+__device__ __forceinline__ uint32_t subtree_of_row(uint32_t jr, uint32_t dlo)
+{
+    if (jr == kNoRank) return kNoRank;
+    const uint32_t d = ilog2(jr + 1u);
+    if (d < dlo || d > dlo + uint32_t(kWaveH)) return kNoRank;
+    return ((jr + 1u) >> (d - dlo)) - (1u << dlo);
+}
+
+// Rows that take a subtree out of the register kernel, for one (scenario, root):
+// the rows of the listed processes, the row of the process that carries the root's
+// number, and the last row when the root is a member of its group or the bottom
+// level of its subtree is incomplete.  At most f + 2 rows; fn(row) is called for
+// each.  Used by the kernel that lists those subtrees and by the register kernel
+// that skips them: both must agree.
+template <class Fn>
+__device__ __forceinline__ void for_each_special_row(const Geom& g, uint32_t dlo, const uint32_t* fail_rank_s,
+                                                     uint32_t root, Fn fn)
+{
+    for (uint32_t q = 0; q < g.f; ++q) {
+        const uint32_t rank = fail_rank_s[q];
+        if (rank == kNoRank) continue;
+        const uint32_t vr = relabel(rank, root);
+        const uint32_t jr = vr == 0 ? (g.a > 1 ? g.M - 1u : kNoRank) : fdiv(vr - 1u, g.divW);
+        if (jr != kNoRank) fn(jr);
+    }
+    if (root != 0) fn(fdiv(root - 1u, g.divW));
+    // the last row: short group with the root in it, or a subtree whose deepest level stops early
+    const uint32_t c = subtree_of_row(g.M - 1u, dlo);
+    if (c != kNoRank) {
+        const uint32_t rs = (1u << dlo) - 1u + c;
+        const uint32_t first_leaf = ((rs + 1u) << kWaveH) - 1u, last_leaf = ((rs + 2u) << kWaveH) - 2u;
+        const bool ragged = first_leaf < g.M && last_leaf >= g.M;
+        if (g.a > 1 || ragged) fn(g.M - 1u);
+    }
+}
+
 template <class T, int OP, int WP>
 __global__ void __launch_bounds__(kWaveThreads) wave_tier_kernel(RunArgs A, WaveLayout wl)
 {
     const Geom& g = A.g;
     const TierDesc& td = A.tiers[0];
     const uint32_t lane = threadIdx.x;
-    const uint32_t wshift = td.dlo - wl.slot_shift;            // wavefronts per scenario = 2^wshift
+    // a wavefront walks through 2^group_shift consecutive groups of 2^slot_shift sibling subtrees of one scenario
+    const uint32_t wshift = td.dlo - wl.slot_shift - wl.group_shift;   // wavefronts per scenario = 2^wshift
     const uint32_t sv = blockIdx.x >> wshift;                  // scenario, or S + retry entry
     const uint32_t top0 = (1u << td.dlo) - 1u;
-    const uint32_t cone_w = (blockIdx.x & ((1u << wshift) - 1u)) << wl.slot_shift;
-    if (top0 + cone_w >= g.M) return;                          // no such rows
+    const uint32_t grp0 = (blockIdx.x & ((1u << wshift) - 1u)) << wl.group_shift;
+    if (top0 + (grp0 << wl.slot_shift) >= g.M) return;         // no such rows
 
     // lane -> (subtree slot, value index e)
     const uint32_t slot = lane / wl.ne;
     const uint32_t e = lane - slot * wl.ne;
     const bool active = lane < wl.nact;
-    const uint32_t cone = cone_w + (active ? slot : 0u);
-    const uint32_t rs = top0 + cone;                           // top row of the lane's subtree
-    const bool exists = active && rs < g.M;
 
-    // shape of the lane's subtree: complete with or without the bottom level, or ragged
-    const uint32_t first_leaf = ((rs + 1u) << kWaveH) - 1u;
-    const uint32_t last_leaf = ((rs + 2u) << kWaveH) - 2u;
-    const bool bottom = last_leaf < g.M;
-    auto in_tree = [&](uint32_t jr) -> bool {                  // is row jr inside the lane's subtree?
-        if (jr == kNoRank) return false;
-        const uint32_t d = ilog2(jr + 1u);
-        if (d < td.dlo || d > td.dlo + uint32_t(kWaveH)) return false;
-        return ((jr + 1u) >> (d - td.dlo)) - 1u == rs;
-    };
-    bool handover = !bottom && first_leaf < g.M;               // ragged bottom level
-    if (g.a > 1 && in_tree(g.M - 1u)) handover = true;         // the short last group (the root is a member)
-
-    uint32_t s = sv, root = 0, status = kStOk, frank = kNoRank;
+    uint32_t s = sv, root = 0, status = kStOk;
     unsigned char* wsS;
     const uint32_t F = g.f > 0 ? g.f : 1;
     if (sv < A.S) {
         status = A.status[s];
         if (A.attempts) root = A.attempts[s];                  // roots tried; the last one is alive
         else if (A.root) root = A.root[s];
-        if (lane < g.f) frank = A.fail_rank[size_t(s) * F + lane];
         if (A.attempts) root = root > 0 ? root - 1u : 0u;
         wsS = A.ws + size_t(s) * A.ws_stride;
     } else {
@@ -208,74 +237,70 @@ __global__ void __launch_bounds__(kWaveThreads) wave_tier_kernel(RunArgs A, Wave
         if (kk >= *A.retry_count) return;
         s = __builtin_amdgcn_readfirstlane(A.retry_list[2u * kk]);
         root = A.retry_list[2u * kk + 1u];
-        if (lane < g.f) frank = A.fail_rank[size_t(s) * F + lane];
         wsS = A.retry_ws + size_t(kk) * A.ws_stride;
     }
     status = __builtin_amdgcn_readfirstlane(status);
     root = __builtin_amdgcn_readfirstlane(root);
     if (status == kStBadFailureSet) return;
-    // rows of the listed processes, and of the process that carries the root's number
-    {
-        uint32_t frow = kNoRank;
-        if (frank != kNoRank) {
-            const uint32_t vr = relabel(frank, root);
-            frow = vr == 0 ? (g.a > 1 ? g.M - 1u : kNoRank) : fdiv(vr - 1u, g.divW);
-        }
-        for (uint32_t q = 0; q < g.f; ++q)
-            if (in_tree(uint32_t(__builtin_amdgcn_readlane(int(frow), int(q))))) handover = true;
-        if (root != 0 && in_tree(fdiv(root - 1u, g.divW))) handover = true;
-    }
-    if (exists && handover && e == 0) {
-        // not for this kernel: the general (LDS tile) kernel runs this subtree
-        const uint32_t n = atomicAdd(A.fix_count, 1u);
-        A.fix_list[2u * n] = sv;
-        A.fix_list[2u * n + 1u] = cone;
-    }
-    const bool mine = exists && !handover;
-    const bool any_bottom = __ballot(mine && bottom) != 0ull;  // else no lane here has the deepest level
-
     const unsigned char* pay = A.payload + size_t(s) * A.scen_stride_bytes;
     const unsigned char* bk[WP];
 #pragma unroll
     for (int k = 0; k < WP; ++k) bk[k] = pay + size_t(k) * g.EB;
-    for (uint32_t pass = 0; pass < wl.passes; ++pass) {
-        const uint32_t ecol = pass * wl.ne + e;
-        if (mine && ecol < g.E) {
-            T out[WP];
-            if (any_bottom) {
-                SubtreeWalk<T, OP, WP, kWaveH> w(g, bk, rs, ecol, bottom);
-                w.run();
+    unsigned long long rows_done = 0;        // rows folded here: every process of them sent all its messages
+
+    for (uint32_t gi = 0; gi < (1u << wl.group_shift); ++gi) {
+        const uint32_t cone_w = (grp0 + gi) << wl.slot_shift;
+        if (top0 + cone_w >= g.M) break;                       // no such rows
+        const uint32_t cone = cone_w + (active ? slot : 0u);
+        const uint32_t rs = top0 + cone;                       // top row of the lane's subtree
+        const bool exists = active && rs < g.M;
+
+        // shape of the lane's subtree: complete with or without the bottom level (a ragged one is listed)
+        const uint32_t last_leaf = ((rs + 2u) << kWaveH) - 2u;
+        const bool bottom = last_leaf < g.M;
+        // subtrees on the list of the general (LDS tile) kernel are not for this one
+        bool handover = false;
+        for_each_special_row(g, td.dlo, A.fail_rank + size_t(s) * F, root, [&](uint32_t jr) {
+            if (subtree_of_row(jr, td.dlo) == cone) handover = true;
+        });
+        const bool mine = exists && !handover;
+        const bool any_bottom = __ballot(mine && bottom) != 0ull;  // else no lane here has the deepest level
+
+        for (uint32_t pass = 0; pass < wl.passes; ++pass) {
+            const uint32_t ecol = pass * wl.ne + e;
+            if (mine && ecol < g.E) {
+                T out[WP];
+                if (any_bottom) {
+                    SubtreeWalk<T, OP, WP, kWaveH> w(g, bk, rs, ecol, bottom);
+                    w.run();
 #pragma unroll
-                for (int k = 0; k < WP; ++k) out[k] = w.cur[k];
-            } else {
-                SubtreeWalk<T, OP, WP, kWaveH - 1> w(g, bk, rs, ecol, true);
-                w.run();
+                    for (int k = 0; k < WP; ++k) out[k] = w.cur[k];
+                } else {
+                    SubtreeWalk<T, OP, WP, kWaveH - 1> w(g, bk, rs, ecol, true);
+                    w.run();
 #pragma unroll
-                for (int k = 0; k < WP; ++k) out[k] = w.cur[k];
-            }
-            // the top row of the subtree goes to the tier above
-            unsigned char* dst = wsS + td.out_off + size_t(cone) * g.RB + size_t(ecol) * g.esz;
+                    for (int k = 0; k < WP; ++k) out[k] = w.cur[k];
+                }
+                // the top row of the subtree goes to the tier above
+                unsigned char* dst = wsS + td.out_off + size_t(cone) * g.RB + size_t(ecol) * g.esz;
 #pragma unroll
-            for (int k = 0; k < WP; ++k) *reinterpret_cast<T*>(dst + size_t(k) * g.EB) = out[k];
-            if (ecol == 0) {
-                reinterpret_cast<uint32_t*>(wsS + td.out_meta_off)[cone] = (1u << g.W) - 1u;   // all sent, no failed bit
-                if (A.info) {         // and nobody in the subtree missed a message: empty lists
-                    uint16_t* mk = reinterpret_cast<uint16_t*>(wsS + td.out_mask_off) + size_t(cone) * g.W;
+                for (int k = 0; k < WP; ++k) *reinterpret_cast<T*>(dst + size_t(k) * g.EB) = out[k];
+                if (ecol == 0) {
+                    reinterpret_cast<uint32_t*>(wsS + td.out_meta_off)[cone] = (1u << g.W) - 1u;   // all sent, no failed bit
+                    if (A.info) {         // and nobody in the subtree missed a message: empty lists
+                        uint16_t* mk = reinterpret_cast<uint16_t*>(wsS + td.out_mask_off) + size_t(cone) * g.W;
 #pragma unroll
-                    for (int k = 0; k < WP; ++k) mk[k] = 0;
+                        for (int k = 0; k < WP; ++k) mk[k] = 0;
+                    }
                 }
             }
         }
+        rows_done += (unsigned long long)__popcll(__ballot(mine && e == 0 && bottom)) * ((2u << kWaveH) - 1u) +
+                     (unsigned long long)__popcll(__ballot(mine && e == 0 && !bottom)) * ((1u << kWaveH) - 1u);
     }
-    // every process of the rows folded here sent all its messages
-    if (A.msgs) {
-        const unsigned long long rows =
-            (unsigned long long)__popcll(__ballot(mine && e == 0 && bottom)) * ((2u << kWaveH) - 1u) +
-            (unsigned long long)__popcll(__ballot(mine && e == 0 && !bottom)) * ((1u << kWaveH) - 1u);
-        if (lane == 0 && rows != 0) {
-            atomicAdd(&A.msgs[size_t(s) * A.nmsg + 0], rows * g.W * (g.W - 1u));
-            atomicAdd(&A.msgs[size_t(s) * A.nmsg + 1], rows * g.W);
-        }
+    if (A.msgs && lane == 0 && rows_done != 0) {
+        atomicAdd(&A.msgs[size_t(s) * A.nmsg + 0], rows_done * g.W * (g.W - 1u));
+        atomicAdd(&A.msgs[size_t(s) * A.nmsg + 1], rows_done * g.W);
     }
 }
 

@@ -45,7 +45,7 @@ def test_plan_info_matches_the_closed_forms(ft, P, f, D, uc, groups, a):
 def test_plan_rejects_bad_arguments(ft):
     for args in [(2, 1, 1, ft.I64, ft.SUM), (8, 1, 0, ft.I64, ft.SUM), (8, 1, 1, 7, ft.SUM),
                  (8, 1, 1, ft.F64, ft.BOR), (8, 1, 1, ft.I64, 5), (100, 16, 1, ft.I64, ft.SUM),
-                 (8, 1, 1, ft.I64, ft.SUM, 3), (8, 1, 1, ft.I64, ft.SUM, 1 << 13)]:
+                 (8, 1, 1, ft.I64, ft.SUM, 3), (8, 1, 1, ft.I64, ft.SUM, 1 << 16)]:
         with pytest.raises(ft.FtredError) as ei:
             ft.Plan(*args)
         assert ei.value.code in (ft.EINVAL, ft.EUNSUPPORTED)
