@@ -22,6 +22,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 #include "ftred_geom.h"
 
 namespace ftred {
@@ -112,49 +114,91 @@ struct RunArgs {
     TierDesc tiers[kMaxTiers];
 };
 
+// One entry of the failure list, resolved by lane q < f of the first wavefront
+// (the other lanes hold "unused"), plus the two facts about the whole list.
+struct FailRegs {
+    uint32_t vr, fr, row, idx, uc, tree;
+    uint32_t listed, root_alive;
+};
+
+// Entry tid of the scenario's failure list as it stands in memory (unused for tid >= f).
+struct FailRaw {
+    uint32_t rank, round;
+};
+
+__device__ __forceinline__ FailRaw failtab_load(const Geom& g, const uint32_t* fail_rank, const uint32_t* fail_round,
+                                                uint32_t s)
+{
+    const uint32_t F = g.f > 0 ? g.f : 1;
+    FailRaw w;
+    w.rank = kNoRank; w.round = 0;
+    if (threadIdx.x < g.f) {
+        w.rank = fail_rank[size_t(s) * F + threadIdx.x];
+        w.round = fail_round[size_t(s) * F + threadIdx.x];
+    }
+    return w;
+}
+
+// called by the threads tid < 64 (one full wavefront, so that the ballots are defined)
+__device__ __forceinline__ FailRegs failtab_compute(const Geom& g, const FailRaw& w, uint32_t root, uint32_t base)
+{
+    const uint32_t tid = threadIdx.x;
+    FailRegs r;
+    r.vr = kNoRank; r.fr = 0; r.row = kNoRank; r.idx = 0; r.uc = 0; r.tree = 0;
+    if (tid < g.f) {
+        uint32_t rank = w.rank;
+        if (rank != kNoRank) {
+            r.fr = w.round;
+            r.vr = relabel(rank, root);
+            uint32_t gs;
+            if (r.vr == 0) {
+                r.row = g.a > 1 ? g.M - 1 : kNoRank;
+                r.idx = g.a - 1;
+                gs = g.a;
+            } else {
+                uint32_t j = fdiv(r.vr - 1, g.divW);
+                r.idx = r.vr - 1 - j * g.W;
+                r.row = j;
+                gs = group_size(g, j);
+                r.tree = alive_at(r.fr, base + tree_send_round(g, r.idx, j)) ? 1u : 0u;
+            }
+            // the send of up-correction round t happens iff base + t < fr
+            uint32_t done = r.fr > base + 1 ? r.fr - base - 1 : 0u;
+            r.uc = done < gs - 1 ? done : gs - 1;
+        }
+    }
+    unsigned long long m = __ballot(r.vr != kNoRank);
+    unsigned long long rd = __ballot(r.vr == 0 && !alive_at(r.fr, base + g.Rred));
+    r.listed = uint32_t(__popcll(m));
+    r.root_alive = rd == 0ull ? 1u : 0u;
+    return r;
+}
+
+// called by the same threads
+__device__ __forceinline__ void failtab_store(FailTab& ft, const Geom& g, const FailRegs& r)
+{
+    const uint32_t tid = threadIdx.x;
+    if (tid < 16) {
+        ft.vr[tid] = r.vr; ft.fr[tid] = r.fr; ft.row[tid] = r.row; ft.idx[tid] = r.idx; ft.uc[tid] = r.uc;
+        ft.tree[tid] = r.tree;
+    }
+    if (tid == 0) {
+        ft.n = g.f;
+        ft.cnt_uc = 0;
+        ft.cnt_tree = 0;
+        ft.listed = r.listed;
+        ft.root_alive = r.root_alive;
+    }
+}
+
 __device__ __forceinline__ void load_failtab(FailTab& ft, const Geom& g, const uint32_t* fail_rank,
                                              const uint32_t* fail_round, uint32_t s, uint32_t root,
                                              uint32_t base)
 {
-    const uint32_t F = g.f > 0 ? g.f : 1;
-    const uint32_t tid = threadIdx.x;
-    if (tid < 64) {      // one full wavefront, so that the ballots below are defined
-        uint32_t vr = kNoRank, fr = 0, row = kNoRank, idx = 0, uc = 0, tree = 0;
-        if (tid < g.f) {
-            uint32_t rank = fail_rank[size_t(s) * F + tid];
-            if (rank != kNoRank) {
-                fr = fail_round[size_t(s) * F + tid];
-                vr = relabel(rank, root);
-                uint32_t gs;
-                if (vr == 0) {
-                    row = g.a > 1 ? g.M - 1 : kNoRank;
-                    idx = g.a - 1;
-                    gs = g.a;
-                } else {
-                    uint32_t j = fdiv(vr - 1, g.divW);
-                    idx = vr - 1 - j * g.W;
-                    row = j;
-                    gs = group_size(g, j);
-                    tree = alive_at(fr, base + tree_send_round(g, idx, j)) ? 1u : 0u;
-                }
-                // the send of up-correction round t happens iff base + t < fr
-                uint32_t done = fr > base + 1 ? fr - base - 1 : 0u;
-                uc = done < gs - 1 ? done : gs - 1;
-            }
-        }
-        if (tid < 16) {
-            ft.vr[tid] = vr; ft.fr[tid] = fr; ft.row[tid] = row; ft.idx[tid] = idx; ft.uc[tid] = uc;
-            ft.tree[tid] = tree;
-        }
-        unsigned long long m = __ballot(vr != kNoRank);
-        unsigned long long rd = __ballot(vr == 0 && !alive_at(fr, base + g.Rred));
-        if (tid == 0) {
-            ft.n = g.f;
-            ft.cnt_uc = 0;
-            ft.cnt_tree = 0;
-            ft.listed = uint32_t(__popcll(m));
-            ft.root_alive = rd == 0ull ? 1u : 0u;
-        }
+    if (threadIdx.x < 64) {
+        const FailRaw w = failtab_load(g, fail_rank, fail_round, s);
+        const FailRegs r = failtab_compute(g, w, root, base);
+        failtab_store(ft, g, r);
     }
 }
 
@@ -459,6 +503,40 @@ __device__ __forceinline__ void stage_patches(const Geom& g, unsigned char* lrow
     }
 }
 
+// The same two patches with the loads apart from the LDS stores (one chunk per
+// thread: values of at most kThreads * sizeof(V) bytes).
+template <class V>
+struct PatchRegs {
+    V a, b;
+    uint32_t dst_a, dst_b;        // LDS byte offsets, kNoRank = none
+
+    __device__ __forceinline__ void issue(const Geom& g, const unsigned char* pay, uint32_t r, uint32_t h, uint32_t root)
+    {
+        const uint32_t o = threadIdx.x * uint32_t(sizeof(V));
+        dst_a = dst_b = kNoRank;
+        if (root != 0) {
+            const uint32_t jr = fdiv(root - 1u, g.divW);
+            const uint32_t li = local_row(jr, r, h);
+            if (li != kNoRank && o < g.EB) {
+                dst_a = li * g.RB + (root - 1u - jr * g.W) * g.EB + o;
+                a = *reinterpret_cast<const V*>(pay + o);
+            }
+        }
+        if (g.a > 1) {
+            const uint32_t li = local_row(g.M - 1u, r, h);
+            if (li != kNoRank && o < g.EB) {
+                dst_b = li * g.RB + (g.a - 1u) * g.EB + o;
+                b = *reinterpret_cast<const V*>(pay + size_t(root) * g.EB + o);
+            }
+        }
+    }
+    __device__ __forceinline__ void commit(unsigned char* lrows) const
+    {
+        if (dst_a != kNoRank) *reinterpret_cast<V*>(lrows + dst_a) = a;
+        if (dst_b != kNoRank) *reinterpret_cast<V*>(lrows + dst_b) = b;
+    }
+};
+
 // does the cone (top row r, height h) hold a row with a listed process?
 __device__ __forceinline__ bool cone_has_failure(const FailTab& ft, uint32_t r, uint32_t h)
 {
@@ -678,48 +756,100 @@ __global__ void __launch_bounds__(kThreads) tier_kernel(RunArgs A)
     else walk_cones<T, OP, WP, T>(A, td, ft, lrows, lmeta, s, root, base, c_lo, c_hi, pay, wsS, discard, td.lds_rows);
 }
 
-// The deepest tier's cones that the wavefront kernel handed over (failures, the
+// The deepest tier's subtrees that are not for the register kernel (failures, the
 // short last group, relabelled ranks, ragged bottom level): workgroups stride over
-// the list.
+// the list, one subtree at a time.  The entries are independent, so everything an
+// entry needs from memory (its descriptor, the failure list, the rows, the two
+// patched values) is requested while the entry before it is reduced out of LDS.
+struct ListEntry {
+    uint32_t sv, cone, s, root, base;
+    bool valid, discard;
+    unsigned char* wsS;
+    const unsigned char* pay;
+};
+
+// entry i of the list: four words (scenario or S + retry entry, subtree, scenario, root), one load
+__device__ __forceinline__ vec16_t list_load(const RunArgs& A, uint32_t i, uint32_t n)
+{
+    return reinterpret_cast<const vec16_t*>(A.fix_list)[i < n ? i : 0u];       // always a valid address
+}
+
+__device__ __forceinline__ ListEntry list_entry(const RunArgs& A, const vec16_t& w, bool valid)
+{
+    ListEntry en;
+    en.valid = valid;
+    en.sv = w.x; en.cone = w.y; en.s = w.z; en.root = w.w;
+    en.discard = en.sv >= A.S;
+    en.base = (en.discard || A.attempts) ? en.root * A.g.Ratt : 0u;
+    en.wsS = en.discard ? A.retry_ws + size_t(en.sv - A.S) * A.ws_stride : A.ws + size_t(en.s) * A.ws_stride;
+    en.pay = A.payload + size_t(en.s) * A.scen_stride_bytes;
+    return en;
+}
+
 template <class T, int OP, int WP, bool VEC>
 __global__ void __launch_bounds__(kThreads) tier_list_kernel(RunArgs A)
 {
+    using V = typename std::conditional<VEC, vec16_t, T>::type;
     extern __shared__ __align__(16) unsigned char smem[];
+    const Geom& g = A.g;
     const TierDesc& td = A.tiers[0];
     FailTab& ft = *reinterpret_cast<FailTab*>(smem);
     uint32_t* lmeta = reinterpret_cast<uint32_t*>(smem + sizeof(FailTab));
     unsigned char* lrows = smem + sizeof(FailTab) + ((size_t(td.lds_rows) * 4u + 15u) & ~size_t(15));
+    uint16_t* lmask = A.info ? reinterpret_cast<uint16_t*>(lrows + ((size_t(td.lds_rows) * g.RB + 15u) & ~size_t(15))) : nullptr;
     const uint32_t n = *A.fix_count;
+    const uint32_t h = td.dhi - td.dlo;
     const uint32_t top0 = (1u << td.dlo) - 1u;
-    for (uint32_t i = blockIdx.x; i < n; i += gridDim.x) {
-        const uint32_t sv = A.fix_list[2u * i];
-        uint32_t c_lo = A.fix_list[2u * i + 1u];
-        uint32_t c_hi = c_lo + (1u << A.fix_kshift);
-        if (top0 + c_hi > A.g.M) c_hi = A.g.M - top0;
-        uint32_t s = sv, root = 0, base = 0;
-        bool discard = false;
-        unsigned char* wsS;
-        if (sv >= A.S) {
-            const uint32_t k = sv - A.S;
-            s = A.retry_list[2u * k];
-            root = A.retry_list[2u * k + 1u];
-            base = root * A.g.Ratt;
-            discard = true;
-            wsS = A.retry_ws + size_t(k) * A.ws_stride;
-        } else {
-            if (A.status[s] == kStBadFailureSet) continue;
-            if (A.attempts) {
-                root = A.attempts[s] - 1u;
-                base = root * A.g.Ratt;
-            } else if (A.root) {
-                root = A.root[s];
-            }
-            wsS = A.ws + size_t(s) * A.ws_stride;
-        }
-        const unsigned char* pay = A.payload + size_t(s) * A.scen_stride_bytes;
+    const bool reg_patches = g.EB <= uint32_t(kThreads * sizeof(V));
+    const uint32_t tid = threadIdx.x;
+    const uint32_t stride = gridDim.x;
+    if (blockIdx.x >= n) return;
+
+    // Pipeline over the entries i, i + stride, ..: while entry i is reduced out of LDS, the rows, patches and
+    // failure list of entry i + stride and the descriptor of entry i + 2 stride are on their way.
+    Stage<V> stg;
+    stg.init(g, td.dlo, h);
+    PatchRegs<V> pr;
+    pr.dst_a = pr.dst_b = kNoRank;
+    ListEntry cur = list_entry(A, list_load(A, blockIdx.x, n), true);
+    vec16_t nxt_w = list_load(A, blockIdx.x + stride, n);
+    stg.issue(g, cur.pay, cur.cone, cur.root);
+    if (reg_patches) pr.issue(g, cur.pay, top0 + cur.cone, h, cur.root);
+    FailRaw raw = failtab_load(g, A.fail_rank, A.fail_round, cur.s);
+
+    for (uint32_t i = blockIdx.x; i < n; i += stride) {
         __syncthreads();              // the previous entry is done with LDS
-        if constexpr (VEC) walk_cones<T, OP, WP, vec16_t>(A, td, ft, lrows, lmeta, s, root, base, c_lo, c_hi, pay, wsS, discard, td.lds_rows);
-        else walk_cones<T, OP, WP, T>(A, td, ft, lrows, lmeta, s, root, base, c_lo, c_hi, pay, wsS, discard, td.lds_rows);
+        if (tid < 64) failtab_store(ft, g, failtab_compute(g, raw, cur.root, cur.base));
+        stg.commit(lrows);
+        if (reg_patches) pr.commit(lrows);
+        else stage_patches<V>(g, lrows, cur.pay, top0 + cur.cone, h, cur.root);
+        __syncthreads();
+        // Everything requested from here on is used after the rounds of this entry.  (Nothing is requested
+        // before the waits above: they wait for all outstanding requests, loads and stores alike.)
+        const vec16_t nxt2_w = list_load(A, i + 2u * stride, n);
+        const ListEntry nxt = list_entry(A, nxt_w, i + stride < n);
+        if (nxt.valid) {
+            stg.issue(g, nxt.pay, nxt.cone, nxt.root);
+            if (reg_patches) pr.issue(g, nxt.pay, top0 + nxt.cone, h, nxt.root);
+            raw = failtab_load(g, A.fail_rank, A.fail_round, nxt.s);
+        }
+        uint32_t uc_cnt = 0, tree_cnt = 0;
+        cone_rounds<T, OP, WP>(A, td, ft, reinterpret_cast<T*>(lrows), lmeta, lmask, cur.s, cur.root, cur.cone, cur.pay,
+                               cur.wsS, cur.discard, uc_cnt, tree_cnt);
+        if (A.msgs) {
+            // per wavefront: sum over the lanes, one atomic each
+#pragma unroll
+            for (int d = 32; d >= 1; d >>= 1) {
+                uc_cnt += __shfl_xor(uc_cnt, d);
+                tree_cnt += __shfl_xor(tree_cnt, d);
+            }
+            if ((tid & 63u) == 0) {
+                if (uc_cnt) atomicAdd(&A.msgs[size_t(cur.s) * A.nmsg + 0], (unsigned long long)uc_cnt);
+                if (tree_cnt) atomicAdd(&A.msgs[size_t(cur.s) * A.nmsg + 1], (unsigned long long)tree_cnt);
+            }
+        }
+        cur = nxt;
+        nxt_w = nxt2_w;
     }
 }
 

@@ -159,9 +159,9 @@ __global__ void __launch_bounds__(256) fixlist_kernel(RunArgs A)
     if (lane == 0 && total != 0) base = atomicAdd(A.fix_count, total);
     base = __shfl(base, 0);
     const uint32_t at = base + incl - nc;
-    for (uint32_t k = 0; k < nc; ++k) {
-        A.fix_list[2u * (at + k)] = sv;
-        A.fix_list[2u * (at + k) + 1u] = cones[k];
+    for (uint32_t k = 0; k < nc; ++k) {            // (scenario or S + retry entry, subtree, scenario, root)
+        const vec16_t en = {sv, cones[k], s, root};
+        reinterpret_cast<vec16_t*>(A.fix_list)[at + k] = en;
     }
 }
 

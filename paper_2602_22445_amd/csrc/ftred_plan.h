@@ -52,12 +52,12 @@ inline uint64_t ws_list_bytes(const ftred_plan_s* p, uint32_t S)
     // at most f failed attempts per scenario, two words each
     return (uint64_t(S) * p->g.f * 8u + 255u) / 256u * 256u;
 }
-// subtrees the wavefront kernel leaves to the general kernel: at most f + 3
-// wavefronts per scenario or retry entry, two words each
+// subtrees the register kernel leaves to the general kernel: at most f + 3 per
+// scenario or retry entry, four words each
 inline uint64_t ws_fix_off(const ftred_plan_s* p, uint32_t S) { return ws_list_off(p, S) + ws_list_bytes(p, S); }
 inline uint64_t ws_fix_bytes(const ftred_plan_s* p, uint32_t S)
 {
-    return ((uint64_t(S) + kRetrySlots) * (p->g.f + 3u) * 8u + 255u) / 256u * 256u;
+    return ((uint64_t(S) + kRetrySlots) * (p->g.f + 3u) * 16u + 255u) / 256u * 256u;
 }
 inline uint64_t ws_ctr_off(const ftred_plan_s* p, uint32_t S) { return ws_fix_off(p, S) + ws_fix_bytes(p, S); }
 inline uint64_t ws_total(const ftred_plan_s* p, uint32_t S) { return ws_ctr_off(p, S) + 256u; }
