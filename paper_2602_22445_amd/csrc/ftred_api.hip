@@ -399,7 +399,6 @@ static void fill_run_args(RunArgs& A, const ftred_plan_t* p, uint32_t S, const v
     for (uint32_t t = 0; t < p->ntiers; ++t) A.tiers[t] = p->tiers[t];
     A.fix_list = reinterpret_cast<uint32_t*>(A.ws + ws_fix_off(p, S));
     A.fix_count = reinterpret_cast<uint32_t*>(A.ws + ws_ctr_off(p, S) + 12u);
-    A.fix_kshift = 0u;                  // the lane-per-subtree kernel hands over single subtrees
 }
 
 // ---------------------------------------------------------------------------

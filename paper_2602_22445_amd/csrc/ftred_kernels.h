@@ -104,9 +104,9 @@ struct RunArgs {
     uint32_t retry_slots;        // entries run by the tier launches (the rest by the retry kernel)
     uint32_t pad0;
     unsigned char* retry_ws;     // scratch of the retry entries, ws_stride bytes each
-    uint32_t* fix_list;          // pairs (scenario or S + retry entry, first cone): subtrees of the deepest
-    uint32_t* fix_count;         //   tier left to the general kernel by the wavefront kernel
-    uint32_t fix_kshift;         // cones per entry = 2^fix_kshift
+    uint32_t* fix_list;          // four words per entry (scenario or S + retry entry, subtree, scenario, root):
+    uint32_t* fix_count;         //   subtrees of the deepest tier that the general kernel runs
+    uint32_t pad1;
     uint32_t info;               // 1: carry the lists of failed processes with the tree messages
     uint32_t* info_count;        // [S] or nullptr
     uint32_t* info_ids;          // [S][max(f,1)] or nullptr

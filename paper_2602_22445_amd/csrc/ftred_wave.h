@@ -16,9 +16,9 @@
 // This kernel runs the subtrees in which every row exists (with or without the
 // bottom level), nothing is listed as failed, and neither the relabelled ranks nor
 // the short last group occur.  The few others (at most f + 3 per scenario) are
-// appended to a list and run by the general LDS-tile kernel, which carries
-// per-member liveness, sent and failed bits (section "Failure information": the
-// single failed bit).
+// listed by a small kernel of their own and run by the general LDS-tile kernel,
+// which carries per-member liveness, sent and failed bits (section "Failure
+// information": the single failed bit); here they are skipped.
 //
 // The subtree's top row leaves through the scratch area in the format the upper
 // tiers read: W*E values and one word (bits 0..15 sent, 16..31 failed bit).
@@ -85,7 +85,11 @@ struct WaveDepth { static constexpr int value = WP <= 5 ? 4 : 2; };     // rows 
 // differ).  Leaves the W tree messages of row rs in cur.  W == WP.  The visits are
 // numbered at compile time (template recursion), so every array index is a constant
 // and the arrays live in registers.
-template <class T, int OP, int WP, int HH>
+// SWAP: the root is not process 0, so the process that carries the root's number
+// (virtual rank `root`, member kx of row jx) is process 0 (section "Reduce": the
+// root swaps numbers with process 0): its input x0 replaces what the row's place in
+// memory holds, which is the root's own input.
+template <class T, int OP, int WP, int HH, bool SWAP>
 struct SubtreeWalk {
     static constexpr int PD = WaveDepth<WP>::value;
     static constexpr int NR = (2 << HH) - 1;
@@ -93,6 +97,8 @@ struct SubtreeWalk {
     const unsigned char* const (&bk)[WP];
     uint32_t rs, ecol;
     bool bottom;
+    uint32_t jx, kx;               // SWAP only
+    T x0;
     T xq[PD][WP];                  // rows in flight
     T st[HH + 1][WP];              // finished lower-numbered children waiting for their sibling, by level
     T cur[WP];                     // the row finished last: a higher-numbered child, or the top
@@ -122,6 +128,12 @@ struct SubtreeWalk {
         // additions up to the loads and waits for each row as soon as it is requested
 #pragma unroll
         for (int k = 0; k < WP; ++k) asm volatile("" : "+v"(xq[N % PD][k]) : : "memory");
+        if constexpr (SWAP) {
+            const uint32_t j = ((rs + 1u) << l) - 1u + uint32_t(li - ((1 << l) - 1));
+            const bool here = j == jx;
+#pragma unroll
+            for (int k = 0; k < WP; ++k) xq[N % PD][k] = (here && kx == uint32_t(k)) ? x0 : xq[N % PD][k];
+        }
         // up-correction: in round t member i receives the input of member (i - t) mod W
         T v[WP];
 #pragma unroll
@@ -164,6 +176,16 @@ struct SubtreeWalk {
         prime<0>();
         visit<0>();
     }
+
+    // the same with the relabelled rank: root = the root's number (not 0), pay = the scenario's payload
+    __device__ __forceinline__ void run_swapped(uint32_t root, const unsigned char* pay)
+    {
+        jx = fdiv(root - 1u, g.divW);
+        kx = root - 1u - jx * g.W;
+        x0 = *reinterpret_cast<const T*>(pay + size_t(ecol) * g.esz);
+        prime<0>();
+        visit<0>();
+    }
 };
 
 // The subtree (of height kWaveH below a row of depth dlo) that holds row jr: its
@@ -178,10 +200,9 @@ __device__ __forceinline__ uint32_t subtree_of_row(uint32_t jr, uint32_t dlo)
 }
 
 // Rows that take a subtree out of the register kernel, for one (scenario, root):
-// the rows of the listed processes, the row of the process that carries the root's
-// number, and the last row when the root is a member of its group or the bottom
-// level of its subtree is incomplete.  At most f + 2 rows; fn(row) is called for
-// each.  Used by the kernel that lists those subtrees and by the register kernel
+// the rows of the listed processes, and the last row when the root is a member of
+// its group or the bottom level of its subtree is incomplete.  At most f + 1 rows;
+// fn(row) is called for each.  Used by the kernel that lists those subtrees and by the register kernel
 // that skips them: both must agree.
 template <class Fn>
 __device__ __forceinline__ void for_each_special_row(const Geom& g, uint32_t dlo, const uint32_t* fail_rank_s,
@@ -194,7 +215,6 @@ __device__ __forceinline__ void for_each_special_row(const Geom& g, uint32_t dlo
         const uint32_t jr = vr == 0 ? (g.a > 1 ? g.M - 1u : kNoRank) : fdiv(vr - 1u, g.divW);
         if (jr != kNoRank) fn(jr);
     }
-    if (root != 0) fn(fdiv(root - 1u, g.divW));
     // the last row: short group with the root in it, or a subtree whose deepest level stops early
     const uint32_t c = subtree_of_row(g.M - 1u, dlo);
     if (c != kNoRank) {
@@ -270,16 +290,30 @@ __global__ void __launch_bounds__(kWaveThreads) wave_tier_kernel(RunArgs A, Wave
             const uint32_t ecol = pass * wl.ne + e;
             if (mine && ecol < g.E) {
                 T out[WP];
-                if (any_bottom) {
-                    SubtreeWalk<T, OP, WP, kWaveH> w(g, bk, rs, ecol, bottom);
-                    w.run();
+                if (root == 0) {
+                    if (any_bottom) {
+                        SubtreeWalk<T, OP, WP, kWaveH, false> w(g, bk, rs, ecol, bottom);
+                        w.run();
 #pragma unroll
-                    for (int k = 0; k < WP; ++k) out[k] = w.cur[k];
+                        for (int k = 0; k < WP; ++k) out[k] = w.cur[k];
+                    } else {
+                        SubtreeWalk<T, OP, WP, kWaveH - 1, false> w(g, bk, rs, ecol, true);
+                        w.run();
+#pragma unroll
+                        for (int k = 0; k < WP; ++k) out[k] = w.cur[k];
+                    }
                 } else {
-                    SubtreeWalk<T, OP, WP, kWaveH - 1> w(g, bk, rs, ecol, true);
-                    w.run();
+                    if (any_bottom) {
+                        SubtreeWalk<T, OP, WP, kWaveH, true> w(g, bk, rs, ecol, bottom);
+                        w.run_swapped(root, pay);
 #pragma unroll
-                    for (int k = 0; k < WP; ++k) out[k] = w.cur[k];
+                        for (int k = 0; k < WP; ++k) out[k] = w.cur[k];
+                    } else {
+                        SubtreeWalk<T, OP, WP, kWaveH - 1, true> w(g, bk, rs, ecol, true);
+                        w.run_swapped(root, pay);
+#pragma unroll
+                        for (int k = 0; k < WP; ++k) out[k] = w.cur[k];
+                    }
                 }
                 // the top row of the subtree goes to the tier above
                 unsigned char* dst = wsS + td.out_off + size_t(cone) * g.RB + size_t(ecol) * g.esz;
