@@ -324,6 +324,13 @@ static hipError_t dispatch_list(const ftred_plan_t* p, const RunArgs& A, uint32_
     return launch_list_f64_sum(A, grid, lds, st);
 }
 
+static hipError_t dispatch_wave_list(const ftred_plan_t* p, const RunArgs& A, uint32_t grid, uint32_t lds, hipStream_t st)
+{
+    if (p->dtype == FTRED_I64) return p->op == FTRED_SUM ? launch_wave_list_i64_sum(A, p->wl, grid, lds, st) : launch_wave_list_i64_bor(A, p->wl, grid, lds, st);
+    if (p->dtype == FTRED_U32) return p->op == FTRED_SUM ? launch_wave_list_u32_sum(A, p->wl, grid, lds, st) : launch_wave_list_u32_bor(A, p->wl, grid, lds, st);
+    return launch_wave_list_f64_sum(A, p->wl, grid, lds, st);
+}
+
 static hipError_t dispatch_wave(const ftred_plan_t* p, const RunArgs& A, uint32_t grid, hipStream_t st)
 {
     if (p->dtype == FTRED_I64) return p->op == FTRED_SUM ? launch_wave_i64_sum(A, p->wl, grid, st) : launch_wave_i64_bor(A, p->wl, grid, st);
@@ -340,9 +347,17 @@ static int launch_tiers(const ftred_plan_t* plan, RunArgs& A, uint32_t S, uint32
         if (t == 0 && plan->use_wave) {
             // subtrees with listed processes, relabelled ranks, the short last group or a ragged bottom are listed
             // and run by the general kernel; the register kernel runs all the others
+            A.wave_general = A.info ? 0u : 1u;     // the lists of failed processes travel through the tile kernel only
+            // at most f + 3 listed subtrees per scenario or retry entry, 2^slot_shift of them per wavefront
+            const uint64_t wgs = ((uint64_t(S) + extra) * (plan->g.f + 3u) + (1u << plan->wl.slot_shift) - 1u) >> plan->wl.slot_shift;
+            A.wfix_cap = uint32_t(wgs << plan->wl.slot_shift);
             hipLaunchKernelGGL(fixlist_kernel, dim3((S + extra + 255u) / 256u), dim3(256), 0, st, A);
             HIP_TRY(hipGetLastError());
             HIP_TRY(dispatch_wave(plan, A, (S + extra) << plan->wave_gshift, st));
+            if (A.wave_general) {
+                const uint32_t lds = (1u << plan->wl.slot_shift) * kWaveRows * uint32_t(sizeof(RowInfo));
+                HIP_TRY(dispatch_wave_list(plan, A, uint32_t(wgs), lds, st));
+            }
             uint64_t cap = (uint64_t(S) + extra) * (plan->g.f + 3u);
             HIP_TRY(dispatch_list(plan, A, uint32_t(cap < 4096u ? cap : 4096u), plan->tiers[0].lds_bytes, st));
         } else
@@ -399,6 +414,8 @@ static void fill_run_args(RunArgs& A, const ftred_plan_t* p, uint32_t S, const v
     for (uint32_t t = 0; t < p->ntiers; ++t) A.tiers[t] = p->tiers[t];
     A.fix_list = reinterpret_cast<uint32_t*>(A.ws + ws_fix_off(p, S));
     A.fix_count = reinterpret_cast<uint32_t*>(A.ws + ws_ctr_off(p, S) + 12u);
+    A.wfix_list = reinterpret_cast<uint32_t*>(A.ws + ws_wfix_off(p, S));
+    A.wfix_count = reinterpret_cast<uint32_t*>(A.ws + ws_ctr_off(p, S) + 16u);
 }
 
 // ---------------------------------------------------------------------------
@@ -442,7 +459,7 @@ static int run_reduce_impl(const char* who, const ftred_plan_t* plan, uint32_t S
     {
         TimedLaunch tl(FTRED_PH_CHECK, st);
         hipLaunchKernelGGL(zero_words_kernel, dim3(1), dim3(64), 0, st,
-                           reinterpret_cast<uint32_t*>(static_cast<unsigned char*>(workspace) + ws_ctr_off(plan, S) + 8u), 2u);
+                           reinterpret_cast<uint32_t*>(static_cast<unsigned char*>(workspace) + ws_ctr_off(plan, S) + 8u), 4u);
         hipLaunchKernelGGL(prepass_kernel, dim3((S + 255u) / 256u), dim3(256), 0, st, g, 0u, S, root, fail_rank,
                            fail_round, status, static_cast<uint32_t*>(nullptr),
                            reinterpret_cast<unsigned long long*>(msgs), 2u, static_cast<unsigned char*>(result),
@@ -509,7 +526,7 @@ static int run_allreduce_impl(const char* who, const ftred_plan_t* plan, uint32_
     uint32_t* retry_count = reinterpret_cast<uint32_t*>(wsb + ws_ctr_off(plan, S) + 8u);
     {
         TimedLaunch tl(FTRED_PH_CHECK, st);
-        hipLaunchKernelGGL(zero_words_kernel, dim3(1), dim3(64), 0, st, retry_count, 2u);     // and the fix-list count
+        hipLaunchKernelGGL(zero_words_kernel, dim3(1), dim3(64), 0, st, retry_count, 4u);     // and the counts of the two lists of subtrees
         hipLaunchKernelGGL(prepass_kernel, dim3((S + 255u) / 256u), dim3(256), 0, st, g, 1u, S,
                            static_cast<const uint32_t*>(nullptr), fail_rank, fail_round, status, attempts,
                            reinterpret_cast<unsigned long long*>(msgs), 4u, static_cast<unsigned char*>(result),

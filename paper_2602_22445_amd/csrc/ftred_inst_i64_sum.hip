@@ -3,8 +3,10 @@
 // instantiations compile in parallel.
 #include "ftred_kernels.h"
 #include "ftred_wave.h"
+#include "ftred_wave_general.h"
 
 namespace ftred {
 FTRED_DEFINE_LAUNCHERS(i64_sum, unsigned long long, 0)
 FTRED_DEFINE_WAVE_LAUNCHER(i64_sum, unsigned long long, 0)
+FTRED_DEFINE_WAVE_LIST_LAUNCHER(i64_sum, unsigned long long, 0)
 }  // namespace ftred

@@ -3,8 +3,10 @@
 // instantiations compile in parallel.
 #include "ftred_kernels.h"
 #include "ftred_wave.h"
+#include "ftred_wave_general.h"
 
 namespace ftred {
 FTRED_DEFINE_LAUNCHERS(u32_bor, uint32_t, 1)
 FTRED_DEFINE_WAVE_LAUNCHER(u32_bor, uint32_t, 1)
+FTRED_DEFINE_WAVE_LIST_LAUNCHER(u32_bor, uint32_t, 1)
 }  // namespace ftred

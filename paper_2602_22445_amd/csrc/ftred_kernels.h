@@ -105,8 +105,11 @@ struct RunArgs {
     uint32_t pad0;
     unsigned char* retry_ws;     // scratch of the retry entries, ws_stride bytes each
     uint32_t* fix_list;          // four words per entry (scenario or S + retry entry, subtree, scenario, root):
-    uint32_t* fix_count;         //   subtrees of the deepest tier that the general kernel runs
-    uint32_t pad1;
+    uint32_t* fix_count;         //   subtrees of the deepest tier that the general (LDS tile) kernel runs
+    uint32_t* wfix_list;         // the same for the subtrees that the register kernel with failure handling runs:
+    uint32_t* wfix_count;        //   [0] entries without rows on the deepest level, filled from the front of the
+    uint32_t wfix_cap;           //   list, [1] entries with such rows, filled from its back (wfix_cap entries)
+    uint32_t wave_general;       // 1: the listed subtrees go to wfix_list
     uint32_t info;               // 1: carry the lists of failed processes with the tree messages
     uint32_t* info_count;        // [S] or nullptr
     uint32_t* info_ids;          // [S][max(f,1)] or nullptr

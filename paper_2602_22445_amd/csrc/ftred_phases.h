@@ -116,8 +116,10 @@ __global__ void prepass_kernel(Geom g, uint32_t kind /* 0 reduce, 1 allreduce */
 }
 
 // One thread per scenario (or retry entry): the subtrees of the deepest tier that
-// the general LDS-tile kernel has to run, each once, appended to the list (one
-// atomic per wavefront: the counter is a single hot word).
+// are not for the plain register kernel, each once, appended to one of two lists
+// (one atomic per wavefront and list: the counters are single hot words): to the
+// register kernel with failure handling if that is in use (A.wave_general), else
+// to the LDS-tile kernel.
 __global__ void __launch_bounds__(256) fixlist_kernel(RunArgs A)
 {
     const Geom& g = A.g;
@@ -146,22 +148,36 @@ __global__ void __launch_bounds__(256) fixlist_kernel(RunArgs A)
             for (uint32_t k = 0; k < nc; ++k) dup = dup || cones[k] == c;
             if (!dup) cones[nc++] = c;
         });
-    // exclusive prefix sum of nc over the wavefront, one atomic for all of it
-    const uint32_t lane = threadIdx.x & 63u;
-    uint32_t incl = nc;
-#pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-        const uint32_t up = __shfl_up(incl, d);
-        if (lane >= uint32_t(d)) incl += up;
+    // which list: 0 = LDS tiles, 1 = registers without rows on the deepest level, 2 = registers with such rows
+    // (kept apart so that a wavefront of the register kernel walks subtrees of one height)
+    const uint32_t top0 = (1u << dlo) - 1u;
+    uint32_t kind[18], cnt[3] = {0, 0, 0};
+    for (uint32_t k = 0; k < nc; ++k) {
+        const bool deep = (((top0 + cones[k] + 1u) << kWaveH) - 1u) < g.M;
+        kind[k] = A.wave_general ? (deep ? 2u : 1u) : 0u;
+        ++cnt[kind[k]];
     }
-    const uint32_t total = __shfl(incl, 63);
-    uint32_t base = 0;
-    if (lane == 0 && total != 0) base = atomicAdd(A.fix_count, total);
-    base = __shfl(base, 0);
-    const uint32_t at = base + incl - nc;
+    // exclusive prefix sums over the wavefront, one atomic per list
+    const uint32_t lane = threadIdx.x & 63u;
+    uint32_t at[3];
+    for (uint32_t c = 0; c < 3; ++c) {
+        uint32_t incl = cnt[c];
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const uint32_t up = __shfl_up(incl, d);
+            if (lane >= uint32_t(d)) incl += up;
+        }
+        const uint32_t total = __shfl(incl, 63);
+        uint32_t b = 0;
+        if (lane == 0 && total != 0) b = atomicAdd(c == 0 ? A.fix_count : A.wfix_count + (c - 1u), total);
+        at[c] = __shfl(b, 0) + incl - cnt[c];
+    }
     for (uint32_t k = 0; k < nc; ++k) {            // (scenario or S + retry entry, subtree, scenario, root)
         const vec16_t en = {sv, cones[k], s, root};
-        reinterpret_cast<vec16_t*>(A.fix_list)[at + k] = en;
+        const uint32_t c = kind[k];
+        if (c == 0) reinterpret_cast<vec16_t*>(A.fix_list)[at[0]++] = en;
+        else if (c == 1) reinterpret_cast<vec16_t*>(A.wfix_list)[at[1]++] = en;
+        else reinterpret_cast<vec16_t*>(A.wfix_list)[A.wfix_cap - 1u - at[2]++] = en;
     }
 }
 

@@ -6,6 +6,7 @@
 
 #include "ftred_kernels.h"
 #include "ftred_wave.h"
+#include "ftred_wave_general.h"
 
 struct ftred_plan_s {
     ftred::Geom g;
@@ -34,8 +35,8 @@ inline uint32_t val_chunks(const ftred_plan_s* p) { return (p->g.P + p->val_chun
 
 // workspace layout: [tree scratch of S scenarios][tree scratch of the retry
 // entries: kRetrySlots + retry_blocks][validation partials][retry list][fix list][256 bytes
-// of counters: +0 invalid scenarios (u64), +8 retry entries (u32), +12 fix-list
-// entries (u32)]
+// of counters: +0 invalid scenarios (u64), +8 retry entries (u32), +12, +16 and +20 entries
+// of the lists of subtrees (u32)]
 inline uint64_t ws_retry_off(const ftred_plan_s* p, uint32_t S) { return uint64_t(S) * p->ws_scen; }
 inline uint64_t ws_val_off(const ftred_plan_s* p, uint32_t S)
 {
@@ -57,9 +58,12 @@ inline uint64_t ws_list_bytes(const ftred_plan_s* p, uint32_t S)
 inline uint64_t ws_fix_off(const ftred_plan_s* p, uint32_t S) { return ws_list_off(p, S) + ws_list_bytes(p, S); }
 inline uint64_t ws_fix_bytes(const ftred_plan_s* p, uint32_t S)
 {
-    return ((uint64_t(S) + kRetrySlots) * (p->g.f + 3u) * 16u + 255u) / 256u * 256u;
+    // room for the capacity rounded up to whole wavefronts of the register kernel (at most 64 entries each)
+    return (((uint64_t(S) + kRetrySlots) * (p->g.f + 3u) + 64u) * 16u + 255u) / 256u * 256u;
 }
-inline uint64_t ws_ctr_off(const ftred_plan_s* p, uint32_t S) { return ws_fix_off(p, S) + ws_fix_bytes(p, S); }
+// two such lists: for the LDS-tile kernel and for the register kernel with failure handling
+inline uint64_t ws_wfix_off(const ftred_plan_s* p, uint32_t S) { return ws_fix_off(p, S) + ws_fix_bytes(p, S); }
+inline uint64_t ws_ctr_off(const ftred_plan_s* p, uint32_t S) { return ws_wfix_off(p, S) + ws_fix_bytes(p, S); }
 inline uint64_t ws_total(const ftred_plan_s* p, uint32_t S) { return ws_ctr_off(p, S) + 256u; }
 
 // event-pair timing of kernel launches (ftred_timing_begin / ftred_timing_end)
