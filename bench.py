@@ -38,7 +38,7 @@ def main():
     ap.add_argument("--cpu-sample", type=int, default=2048, help="scenarios timed on the CPU oracle")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU (scenarios are independent; nothing is sharded); "
+        print("bench.py: the library runs on ONE GPU (scenarios are independent; nothing is sharded); "
               "--gpus %d is not supported" % args.gpus, file=sys.stderr)
         sys.exit(2)
 
