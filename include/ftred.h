@@ -85,7 +85,8 @@ typedef struct ftred_info {
     uint32_t rounds_reduce;      /* f + D */
     uint32_t rounds_attempt;     /* 2 (f + D): reduce, broadcast down the tree, f correction rounds */
     uint32_t tiers;              /* kernel launches of one tree phase */
-    uint32_t deep_kernel;        /* deepest tier: 0 = LDS tiles, 1 = registers, one lane per subtree */
+    uint32_t deep_kernel;        /* deepest tier: 0 = LDS tiles, 1 = registers, one lane per subtree,
+                                    2 = registers, eight lanes per subtree (elems == 1) */
     uint64_t msgs_uc_ff;         /* failure-free up-correction messages (message-count theorem) */
     uint64_t msgs_tree_ff;       /* failure-free tree messages = P - 1 */
     uint64_t msgs_bcast_tree_ff; /* failure-free broadcast tree messages = P - 1 */

@@ -207,6 +207,13 @@ extern "C" int ftred_plan(ftred_plan_t** out, uint32_t P, uint32_t f, uint32_t e
         const uint32_t most = p->tiers[0].dlo - p->wl.slot_shift;
         if ((flags >> 13) & 7u) p->wl.group_shift = ((flags >> 13) & 7u) - 1u < most ? ((flags >> 13) & 7u) - 1u : most;
         p->wave_gshift = most - p->wl.group_shift;                // one wavefront per workgroup
+        p->use_unit = g.E == 1u ? 1u : 0u;
+        if (p->use_unit) {
+            p->ul = make_unit_layout(g, p->tiers[0].dlo);
+            const uint32_t mostu = p->tiers[0].dlo - p->ul.slot_shift;
+            if ((flags >> 13) & 7u) p->ul.group_shift = ((flags >> 13) & 7u) - 1u < mostu ? ((flags >> 13) & 7u) - 1u : mostu;
+            p->wave_gshift = mostu - p->ul.group_shift;
+        }
     }
     p->ws_scen = align_up(off, 256);
     p->retry_blocks = 64;
@@ -238,7 +245,7 @@ extern "C" int ftred_plan_info(const ftred_plan_t* plan, ftred_info_t* info)
     info->rounds_reduce = g.Rred;
     info->rounds_attempt = g.Ratt;
     info->tiers = plan->ntiers;
-    info->deep_kernel = plan->use_wave;
+    info->deep_kernel = plan->use_wave ? (plan->use_unit ? 2u : 1u) : 0u;
     info->msgs_uc_ff = msgs_uc_ff(g);
     info->msgs_tree_ff = g.P - 1;
     info->msgs_bcast_tree_ff = g.P - 1;
@@ -333,6 +340,11 @@ static hipError_t dispatch_wave_list(const ftred_plan_t* p, const RunArgs& A, ui
 
 static hipError_t dispatch_wave(const ftred_plan_t* p, const RunArgs& A, uint32_t grid, hipStream_t st)
 {
+    if (p->use_unit) {
+        if (p->dtype == FTRED_I64) return p->op == FTRED_SUM ? launch_unit_i64_sum(A, p->ul, grid, st) : launch_unit_i64_bor(A, p->ul, grid, st);
+        if (p->dtype == FTRED_U32) return p->op == FTRED_SUM ? launch_unit_u32_sum(A, p->ul, grid, st) : launch_unit_u32_bor(A, p->ul, grid, st);
+        return launch_unit_f64_sum(A, p->ul, grid, st);
+    }
     if (p->dtype == FTRED_I64) return p->op == FTRED_SUM ? launch_wave_i64_sum(A, p->wl, grid, st) : launch_wave_i64_bor(A, p->wl, grid, st);
     if (p->dtype == FTRED_U32) return p->op == FTRED_SUM ? launch_wave_u32_sum(A, p->wl, grid, st) : launch_wave_u32_bor(A, p->wl, grid, st);
     return launch_wave_f64_sum(A, p->wl, grid, st);

@@ -4,9 +4,11 @@
 #include "ftred_kernels.h"
 #include "ftred_wave.h"
 #include "ftred_wave_general.h"
+#include "ftred_wave_unit.h"
 
 namespace ftred {
 FTRED_DEFINE_LAUNCHERS(f64_sum, double, 0)
 FTRED_DEFINE_WAVE_LAUNCHER(f64_sum, double, 0)
 FTRED_DEFINE_WAVE_LIST_LAUNCHER(f64_sum, double, 0)
+FTRED_DEFINE_UNIT_LAUNCHER(f64_sum, double, 0)
 }  // namespace ftred

@@ -4,9 +4,11 @@
 #include "ftred_kernels.h"
 #include "ftred_wave.h"
 #include "ftred_wave_general.h"
+#include "ftred_wave_unit.h"
 
 namespace ftred {
 FTRED_DEFINE_LAUNCHERS(i64_bor, unsigned long long, 1)
 FTRED_DEFINE_WAVE_LAUNCHER(i64_bor, unsigned long long, 1)
 FTRED_DEFINE_WAVE_LIST_LAUNCHER(i64_bor, unsigned long long, 1)
+FTRED_DEFINE_UNIT_LAUNCHER(i64_bor, unsigned long long, 1)
 }  // namespace ftred

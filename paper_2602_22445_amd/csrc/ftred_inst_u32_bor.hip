@@ -4,9 +4,11 @@
 #include "ftred_kernels.h"
 #include "ftred_wave.h"
 #include "ftred_wave_general.h"
+#include "ftred_wave_unit.h"
 
 namespace ftred {
 FTRED_DEFINE_LAUNCHERS(u32_bor, uint32_t, 1)
 FTRED_DEFINE_WAVE_LAUNCHER(u32_bor, uint32_t, 1)
 FTRED_DEFINE_WAVE_LIST_LAUNCHER(u32_bor, uint32_t, 1)
+FTRED_DEFINE_UNIT_LAUNCHER(u32_bor, uint32_t, 1)
 }  // namespace ftred

@@ -151,6 +151,28 @@ __global__ void __launch_bounds__(256) fixlist_kernel(RunArgs A)
     // which list: 0 = LDS tiles, 1 = registers without rows on the deepest level, 2 = registers with such rows
     // (kept apart so that a wavefront of the register kernel walks subtrees of one height)
     const uint32_t top0 = (1u << dlo) - 1u;
+    // The register kernels fold all the other subtrees; every process in those sends each of its messages
+    // (W - 1 in the up-correction, one in the tree), and the count is a matter of shape: a subtree has all
+    // 2^(h+1) - 1 rows (h = kWaveH), or lacks the deepest level; the one in between is on the list.
+    if (live && A.msgs) {
+        const uint32_t nsub = 1u << dlo;
+        uint32_t n_full = ((g.M + 1u) >> kWaveH) - 1u - top0;            // subtrees whose last leaf exists
+        uint32_t n_some = (g.M >> kWaveH) - top0;                        // subtrees whose first leaf exists
+        n_full = n_full < nsub ? n_full : nsub;
+        n_some = n_some < nsub ? n_some : nsub;
+        uint32_t n_flat = nsub - n_some;                                 // subtrees without the deepest level
+        for (uint32_t k = 0; k < nc; ++k) {
+            const uint32_t rs = top0 + cones[k];
+            if ((((rs + 2u) << kWaveH) - 2u) < g.M) --n_full;
+            else if ((((rs + 1u) << kWaveH) - 1u) >= g.M) --n_flat;
+        }
+        const unsigned long long rows = (unsigned long long)n_full * ((2u << kWaveH) - 1u) +
+                                        (unsigned long long)n_flat * ((1u << kWaveH) - 1u);
+        if (rows != 0ull) {
+            atomicAdd(&A.msgs[size_t(s) * A.nmsg + 0], rows * g.W * (g.W - 1u));
+            atomicAdd(&A.msgs[size_t(s) * A.nmsg + 1], rows * g.W);
+        }
+    }
     uint32_t kind[18], cnt[3] = {0, 0, 0};
     for (uint32_t k = 0; k < nc; ++k) {
         const bool deep = (((top0 + cones[k] + 1u) << kWaveH) - 1u) < g.M;

@@ -7,6 +7,7 @@
 #include "ftred_kernels.h"
 #include "ftred_wave.h"
 #include "ftred_wave_general.h"
+#include "ftred_wave_unit.h"
 
 struct ftred_plan_s {
     ftred::Geom g;
@@ -19,6 +20,8 @@ struct ftred_plan_s {
     uint32_t retry_blocks;
     uint32_t use_wave;          // the deepest tier runs as one wavefront per subtree
     ftred::WaveLayout wl;
+    uint32_t use_unit;          // ... with eight lanes per subtree (one value per process)
+    ftred::UnitLayout ul;
     uint32_t wave_gshift;       // workgroups of the wavefront tier per scenario = 2^wave_gshift
     uint32_t bc_chunk;          // ranks per workgroup in the broadcast kernel
     uint32_t val_chunk;         // ranks per workgroup in the validation kernel

@@ -22,6 +22,9 @@
 //
 // The subtree's top row leaves through the scratch area in the format the upper
 // tiers read: W*E values and one word (bits 0..15 sent, 16..31 failed bit).
+// The messages of these subtrees (every process in them sends all of its own) are
+// counted by the kernel that lists the other subtrees: their number follows from
+// the shape of the tree and that list.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -225,6 +228,29 @@ __device__ __forceinline__ void for_each_special_row(const Geom& g, uint32_t dlo
     }
 }
 
+// The same rows, one per lane of a wavefront (f + 1 <= 64): lane e < f takes entry e of the
+// failure list (`rank` = that entry, read by the caller), lane f the last row.  Returns the
+// lane's row or kNoRank.
+__device__ __forceinline__ uint32_t special_row_of_lane(const Geom& g, uint32_t dlo, uint32_t rank, uint32_t root,
+                                                        uint32_t lane)
+{
+    if (lane < g.f) {
+        if (rank == kNoRank) return kNoRank;
+        const uint32_t vr = relabel(rank, root);
+        return vr == 0 ? (g.a > 1 ? g.M - 1u : kNoRank) : fdiv(vr - 1u, g.divW);
+    }
+    if (lane == g.f) {
+        const uint32_t c = subtree_of_row(g.M - 1u, dlo);
+        if (c != kNoRank) {
+            const uint32_t rs = (1u << dlo) - 1u + c;
+            const uint32_t first_leaf = ((rs + 1u) << kWaveH) - 1u, last_leaf = ((rs + 2u) << kWaveH) - 2u;
+            const bool ragged = first_leaf < g.M && last_leaf >= g.M;
+            if (g.a > 1 || ragged) return g.M - 1u;
+        }
+    }
+    return kNoRank;
+}
+
 template <class T, int OP, int WP>
 __global__ void __launch_bounds__(kWaveThreads) wave_tier_kernel(RunArgs A, WaveLayout wl)
 {
@@ -266,7 +292,6 @@ __global__ void __launch_bounds__(kWaveThreads) wave_tier_kernel(RunArgs A, Wave
     const unsigned char* bk[WP];
 #pragma unroll
     for (int k = 0; k < WP; ++k) bk[k] = pay + size_t(k) * g.EB;
-    unsigned long long rows_done = 0;        // rows folded here: every process of them sent all its messages
 
     for (uint32_t gi = 0; gi < (1u << wl.group_shift); ++gi) {
         const uint32_t cone_w = (grp0 + gi) << wl.slot_shift;
@@ -329,12 +354,6 @@ __global__ void __launch_bounds__(kWaveThreads) wave_tier_kernel(RunArgs A, Wave
                 }
             }
         }
-        rows_done += (unsigned long long)__popcll(__ballot(mine && e == 0 && bottom)) * ((2u << kWaveH) - 1u) +
-                     (unsigned long long)__popcll(__ballot(mine && e == 0 && !bottom)) * ((1u << kWaveH) - 1u);
-    }
-    if (A.msgs && lane == 0 && rows_done != 0) {
-        atomicAdd(&A.msgs[size_t(s) * A.nmsg + 0], rows_done * g.W * (g.W - 1u));
-        atomicAdd(&A.msgs[size_t(s) * A.nmsg + 1], rows_done * g.W);
     }
 }
 

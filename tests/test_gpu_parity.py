@@ -119,6 +119,10 @@ REDUCE_CASES = [
     (3000, 12, 2, 0, 0, 32, 500), (1 << 16, 8, 1, 0, 0, 6, 500),
     # the register kernel of the deepest tier: two passes over the value indices, bitwise or, every group width
     (3000, 1, 80, 1, 0, 24, 500), (2000, 2, 4, 1, 1, 64, 500), (700, 1, 3, 0, 1, 64, 500), (9000, 3, 5, 2, 0, 24, 500),
+    (5000, 8, 3, 0, 0, 24, 500),
+    # one value per process: eight lanes per subtree, every group width; fewer than eight subtrees in the tier
+    (700, 1, 1, 2, 0, 64, 500), (1000, 2, 1, 1, 1, 64, 500), (2500, 3, 1, 0, 1, 48, 500), (5003, 4, 1, 2, 0, 48, 500),
+    (81, 1, 1, 0, 0, 64, 500), (200, 1, 1, 1, 0, 64, 500),
 ]
 
 
@@ -151,17 +155,24 @@ ALLREDUCE_CASES = [
     (3000, 1, 80, 1, 0, 24, 500), (2000, 2, 4, 1, 1, 64, 500), (700, 1, 3, 0, 1, 64, 500), (9000, 3, 5, 2, 0, 24, 500),
     # one 4-byte value per process: four receive buffers per store; and a P that rules that path out
     (1004, 2, 1, 1, 0, 64, 500), (1003, 2, 1, 1, 1, 64, 500),
+    (5000, 8, 3, 0, 0, 24, 500),
+    # one value per process: eight lanes per subtree, every group width; fewer than eight subtrees in the tier
+    (700, 1, 1, 2, 0, 64, 500), (2500, 3, 1, 0, 1, 48, 500), (5003, 4, 1, 2, 0, 48, 500),
+    (81, 1, 1, 0, 0, 64, 500), (200, 1, 1, 1, 0, 64, 500),
 ]
 
 
 def test_the_sweeps_reach_both_kernels_of_the_deepest_tier(ft):
-    """Plans of the sweep cases: the register kernel for deep trees with f + 1 in {2,3,4,5,9}, LDS tiles otherwise;
-    one case walks the value indices in two passes (more than 64 of them)."""
+    """Plans of the sweep cases: the register kernels for deep trees with f + 1 in {2,3,4,5,9} (eight lanes per
+    subtree when a process holds one value, one lane otherwise), LDS tiles otherwise; one case walks the value
+    indices in two passes (more than 64 of them)."""
     kinds = {(P, f, E, dt): ft.Plan(P, f, E, dt, op).info.deep_kernel for P, f, E, dt, op, _, _ in ALLREDUCE_CASES}
     assert kinds[(3000, 1, 80, 1)] == 1 and kinds[(2000, 2, 4, 1)] == 1 and kinds[(9000, 3, 5, 2)] == 1
-    assert kinds[(1000, 8, 1, 0)] == 1 and kinds[(33333, 4, 8, 2)] == 1 and kinds[(1 << 16, 8, 1, 0)] == 1
+    assert kinds[(1000, 8, 1, 0)] == 2 and kinds[(33333, 4, 8, 2)] == 1 and kinds[(1 << 16, 8, 1, 0)] == 2
+    assert kinds[(81, 1, 1, 0)] == 2 and kinds[(200, 1, 1, 1)] == 2 and kinds[(5000, 8, 3, 0)] == 1
     assert kinds[(4099, 5, 3, 2)] == 0 and kinds[(3000, 12, 2, 0)] == 0 and kinds[(64, 2, 8, 1)] == 0
     assert {f + 1 for (P, f, E, dt), k in kinds.items() if k == 1} >= {2, 3, 4, 5, 9}
+    assert {f + 1 for (P, f, E, dt), k in kinds.items() if k == 2} >= {2, 3, 4, 5, 9}
 
 
 @pytest.mark.parametrize("P,f,E,dtype,op,S,permille", ALLREDUCE_CASES)
