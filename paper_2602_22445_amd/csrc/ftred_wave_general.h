@@ -106,6 +106,8 @@ struct GeneralWalk {
         constexpr uint32_t mask = (1u << WP) - 1u;
 #pragma unroll
         for (int k = 0; k < WP; ++k) asm volatile("" : "+v"(xq[N % PD][k]) : : "memory");
+        // what depends on the row is worked out at its visit, not for all rows ahead of the walk (registers)
+        asm volatile("" : "+v"(rs));
         const uint32_t j = ((rs + 1u) << l) - 1u + uint32_t(li - ((1 << l) - 1));
         const bool here = j == jx;
 #pragma unroll
@@ -315,8 +317,11 @@ __device__ __forceinline__ void wave_list_entries(const RunArgs& A, const WaveLa
 // kernel, an entry per slot.  Workgroups from the front of the grid take the front
 // part of the list, workgroups from its back the back part (so a wavefront walks
 // subtrees of one height).  Dynamic LDS: 2^slot_shift * kWaveRows RowInfo.
+// The walk is a chain of loads that wait for each other: for the narrower groups the registers are held
+// to what lets two wavefronts share a SIMD.
 template <class T, int OP, int WP>
-__global__ void __launch_bounds__(kWaveThreads) wave_list_kernel(RunArgs A, WaveLayout wl)
+__global__ void __launch_bounds__(kWaveThreads) __attribute__((amdgpu_waves_per_eu(WP <= 5 ? 2 : 1)))
+wave_list_kernel(RunArgs A, WaveLayout wl)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     RowInfo* rinfo = reinterpret_cast<RowInfo*>(smem);

@@ -55,15 +55,6 @@ inline UnitLayout make_unit_layout(const Geom& g, uint32_t dlo)
     return u;
 }
 
-// In a group whose members are all alive, every member ends the up-correction with
-// the reduction of all W inputs, each in the order of its own rounds.  For the
-// integer operators (wrapping sum, bitwise or), which are associative and commutative
-// exactly, these W results are one number, and so are the W tree messages of a row
-// below which nobody failed: the kernel then carries one value per row, not W.  In
-// floating point the W orders round differently and every member is carried.
-template <class T>
-struct SameInGroup { static constexpr bool value = !std::is_floating_point<T>::value; };
-
 template <class T, int OP, int WP>
 struct UnitRow {
     static constexpr int NV = SameInGroup<T>::value ? 1 : WP;      // values carried per row
