@@ -56,6 +56,8 @@ CASES = [
     (100, 6, 5, 2, 128, 600), (257, 7, 2, 0, 128, 600), (1000, 8, 1, 0, 96, 500), (1024, 3, 16, 0, 128, 400),
     (1500, 4, 8, 2, 128, 500), (4099, 5, 3, 2, 48, 500), (20000, 2, 4, 1, 24, 500), (33333, 4, 8, 2, 12, 500),
     (3000, 12, 2, 0, 32, 500),
+    # one value per process (eight lanes per subtree in the deepest tier)
+    (5003, 4, 1, 2, 48, 500), (2500, 3, 1, 0, 48, 500),
 ]
 
 
