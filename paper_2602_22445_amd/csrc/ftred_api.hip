@@ -189,6 +189,15 @@ extern "C" int ftred_plan(ftred_plan_t** out, uint32_t P, uint32_t f, uint32_t e
         if (td.lds_bytes > p->max_lds) p->max_lds = td.lds_bytes;
         td.kshift = td.dlo < kwalk ? td.dlo : kwalk;
         td.gshift = td.dlo - td.kshift;
+        // A small cone is a matter of latency and of instructions every wavefront repeats: no more wavefronts
+        // than its widest level has work for, but enough threads for the prefetch registers to hold its rows.
+        td.threads = uint32_t(kThreads);
+        if (t > 0) {
+            const uint32_t own_bytes = ((2u << h) - 1u) * g.RB, widest = (1u << h) * g.E;
+            uint32_t thr = 64;
+            while (thr < uint32_t(kThreads) && (thr * kStagePerThread < own_bytes || thr < widest)) thr *= 2u;
+            td.threads = thr;
+        }
         if (t > 0) {
             td.in_off = p->tiers[t - 1].out_off; td.in_meta_off = p->tiers[t - 1].out_meta_off;
             td.in_mask_off = p->tiers[t - 1].out_mask_off;

@@ -32,6 +32,7 @@ constexpr int kThreads = 256;
 constexpr int kMaxTiers = 8;
 constexpr int kCopyBatch = 8;           // loads in flight per thread in plain copies
 constexpr uint32_t kStageBytes = 24576; // most input bytes one cone stages (prefetch registers: 96 B per thread)
+constexpr uint32_t kStagePerThread = kStageBytes / kThreads;
 constexpr uint32_t kRetrySlots = 64;    // failed attempts that run inside the tier launches
 
 // 16 bytes as a native vector (stays in registers where a struct type may not)
@@ -78,6 +79,7 @@ struct TierDesc {
     uint32_t lds_bytes;         // dynamic LDS of the launch
     uint32_t kshift;            // a workgroup walks through 2^kshift consecutive cones
     uint32_t gshift;            // workgroups per scenario = 2^gshift = 2^(dlo - kshift)
+    uint32_t threads;           // workgroup size of tier_kernel: 64, 128 or kThreads
 };
 
 struct RunArgs {
@@ -384,16 +386,17 @@ template <class V>
 __device__ __forceinline__ void copy_to_lds(unsigned char* dst, const unsigned char* src, uint32_t bytes)
 {
     const uint32_t n = bytes / uint32_t(sizeof(V));
-    for (uint32_t c0 = threadIdx.x; c0 < n; c0 += kThreads * kCopyBatch) {
+    const uint32_t nthr = blockDim.x;
+    for (uint32_t c0 = threadIdx.x; c0 < n; c0 += nthr * kCopyBatch) {
         V r[kCopyBatch];
 #pragma unroll
         for (int u = 0; u < kCopyBatch; ++u) {
-            uint32_t ci = c0 + uint32_t(u) * kThreads;
+            uint32_t ci = c0 + uint32_t(u) * nthr;
             r[u] = reinterpret_cast<const V*>(src)[ci < n ? ci : 0u];    // always a valid address
         }
 #pragma unroll
         for (int u = 0; u < kCopyBatch; ++u) {
-            uint32_t ci = c0 + uint32_t(u) * kThreads;
+            uint32_t ci = c0 + uint32_t(u) * nthr;
             if (ci < n) reinterpret_cast<V*>(dst)[ci] = r[u];
         }
     }
@@ -426,7 +429,7 @@ struct Stage {
         const uint32_t top0 = (1u << dlo) - 1u;
 #pragma unroll
         for (int u = 0; u < NB; ++u) {
-            const uint32_t ci = threadIdx.x + uint32_t(u) * kThreads;
+            const uint32_t ci = threadIdx.x + uint32_t(u) * blockDim.x;
             uint32_t b = 0xFFFFFFFFu, st = 0u;         // never passes the clip
             if (ci < n) {
                 const uint32_t off = ci * CH;
@@ -465,7 +468,7 @@ struct Stage {
         const unsigned long long okm = (unsigned long long)okm_lo | ((unsigned long long)okm_hi << 32);
 #pragma unroll
         for (int u = 0; u < NB; ++u) {
-            const uint32_t ci = threadIdx.x + uint32_t(u) * kThreads;
+            const uint32_t ci = threadIdx.x + uint32_t(u) * blockDim.x;
             if ((okm >> u) & 1ull) *reinterpret_cast<V*>(lrows + size_t(ci) * CH) = reg[u];
         }
     }
@@ -491,7 +494,7 @@ __device__ __forceinline__ void stage_patches(const Geom& g, unsigned char* lrow
         const uint32_t li = local_row(jr, r, h);
         if (li != kNoRank) {
             unsigned char* dst = lrows + size_t(li) * g.RB + (root - 1u - jr * g.W) * g.EB;
-            for (uint32_t o = tid * CH; o < g.EB; o += kThreads * CH)
+            for (uint32_t o = tid * CH; o < g.EB; o += blockDim.x * CH)
                 *reinterpret_cast<V*>(dst + o) = *reinterpret_cast<const V*>(pay + o);
         }
     }
@@ -500,7 +503,7 @@ __device__ __forceinline__ void stage_patches(const Geom& g, unsigned char* lrow
         if (li != kNoRank) {
             unsigned char* dst = lrows + size_t(li) * g.RB + (g.a - 1u) * g.EB;
             const unsigned char* src = pay + size_t(root) * g.EB;
-            for (uint32_t o = tid * CH; o < g.EB; o += kThreads * CH)
+            for (uint32_t o = tid * CH; o < g.EB; o += blockDim.x * CH)
                 *reinterpret_cast<V*>(dst + o) = *reinterpret_cast<const V*>(src + o);
         }
     }
@@ -559,7 +562,7 @@ __device__ __forceinline__ void cone_rounds(const RunArgs& A, const TierDesc& td
                                             uint32_t& uc_cnt, uint32_t& tree_cnt)
 {
     const Geom& g = A.g;
-    const uint32_t tid = threadIdx.x;
+    const uint32_t tid = threadIdx.x, nthr = blockDim.x;
     const uint32_t h = td.dhi - td.dlo;
     const uint32_t r = (1u << td.dlo) - 1u + cone;
     const bool check_fail = cone_has_failure(ft, r, h);
@@ -573,14 +576,14 @@ __device__ __forceinline__ void cone_rounds(const RunArgs& A, const TierDesc& td
             if (cnt > (1u << l)) cnt = 1u << l;
             const uint32_t nitems = cnt * g.E;
             const bool kids = (uint32_t(l) < h) || td.child_in;
-            for (uint32_t it = tid; it < nitems; it += kThreads) {
+            for (uint32_t it = tid; it < nitems; it += nthr) {
                 const uint32_t lr = fdiv(it, g.divE);
                 const uint32_t e = it - lr * g.E;
                 process_item<T, OP, WP>(g, ft, rows, lmeta, lfirst + lr, gfirst + lr, e, kids, check_fail,
                                         vroot_out, uc_cnt, tree_cnt);
             }
             if (lmask != nullptr)
-                for (uint32_t lr = tid; lr < cnt; lr += kThreads)
+                for (uint32_t lr = tid; lr < cnt; lr += nthr)
                     process_lists(g, ft, lmeta, lmask, lfirst + lr, gfirst + lr, kids, check_fail);
         }
         lds_barrier();
@@ -589,10 +592,10 @@ __device__ __forceinline__ void cone_rounds(const RunArgs& A, const TierDesc& td
     if (!td.is_top) {
         unsigned char* dst = wsS + td.out_off + size_t(cone) * g.RB;
         if (A.vec16) {
-            for (uint32_t o = tid * 16u; o < g.RB; o += kThreads * 16u)
+            for (uint32_t o = tid * 16u; o < g.RB; o += nthr * 16u)
                 *reinterpret_cast<vec16_t*>(dst + o) = *reinterpret_cast<const vec16_t*>(reinterpret_cast<unsigned char*>(rows) + o);
         } else {
-            for (uint32_t o = tid; o < g.W * g.E; o += kThreads) reinterpret_cast<T*>(dst)[o] = rows[o];
+            for (uint32_t o = tid; o < g.W * g.E; o += nthr) reinterpret_cast<T*>(dst)[o] = rows[o];
         }
         if (tid == 0) reinterpret_cast<uint32_t*>(wsS + td.out_meta_off)[cone] = lmeta[0];
         if (lmask != nullptr && tid < g.W)
@@ -608,7 +611,7 @@ __device__ __forceinline__ void cone_rounds(const RunArgs& A, const TierDesc& td
         if (!ft.root_alive) st = kStRootFailed;
         else if (okm == 0) st = kStNoCleanSubtree;
         T* res = reinterpret_cast<T*>(A.result) + size_t(s) * g.E;
-        for (uint32_t e = tid; e < g.E; e += kThreads) {
+        for (uint32_t e = tid; e < g.E; e += nthr) {
             T val = T(0);
             if (st == kStOk) {
                 const uint32_t ks = uint32_t(__ffs(int(okm))) - 1u;
@@ -671,10 +674,10 @@ __device__ __forceinline__ void stage_children(const RunArgs& A, const TierDesc&
     if (A.vec16) copy_to_lds<vec16_t>(lrows_b + size_t(nx) * g.RB, src, cc * g.RB);
     else copy_to_lds<T>(lrows_b + size_t(nx) * g.RB, src, cc * g.RB);
     const uint32_t* msrc = reinterpret_cast<const uint32_t*>(wsS + td.in_meta_off) + size_t(cone) * per;
-    for (uint32_t i = threadIdx.x; i < cc; i += kThreads) lmeta[nx + i] = msrc[i];
+    for (uint32_t i = threadIdx.x; i < cc; i += blockDim.x) lmeta[nx + i] = msrc[i];
     if (lmask != nullptr) {
         const uint16_t* ksrc = reinterpret_cast<const uint16_t*>(wsS + td.in_mask_off) + size_t(cone) * per * g.W;
-        for (uint32_t i = threadIdx.x; i < cc * g.W; i += kThreads) lmask[size_t(nx) * g.W + i] = ksrc[i];
+        for (uint32_t i = threadIdx.x; i < cc * g.W; i += blockDim.x) lmask[size_t(nx) * g.W + i] = ksrc[i];
     }
 }
 
@@ -903,8 +906,9 @@ FTRED_DECLARE_LAUNCHERS(f64_sum)
     template <int WP>                                                                              \
     static hipError_t tier_wp_##NAME(const RunArgs& A, uint32_t grid, uint32_t lds, hipStream_t st) \
     {                                                                                              \
-        if (A.vec16) hipLaunchKernelGGL((tier_kernel<T, OP, WP, true>), dim3(grid), dim3(kThreads), lds, st, A); \
-        else hipLaunchKernelGGL((tier_kernel<T, OP, WP, false>), dim3(grid), dim3(kThreads), lds, st, A);        \
+        const uint32_t thr = A.tiers[A.tier].threads;                                              \
+        if (A.vec16) hipLaunchKernelGGL((tier_kernel<T, OP, WP, true>), dim3(grid), dim3(thr), lds, st, A); \
+        else hipLaunchKernelGGL((tier_kernel<T, OP, WP, false>), dim3(grid), dim3(thr), lds, st, A); \
         return hipGetLastError();                                                                  \
     }                                                                                              \
     template <int WP>                                                                              \
