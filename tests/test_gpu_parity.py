@@ -264,6 +264,24 @@ def test_shared_payload_unaligned_pointer_and_tree_kernel_variants(ft, oracle, w
     assert np.array_equal(g["per_process_out"].cpu().numpy(), o["out"])
 
 
+@pytest.mark.parametrize("P,f,E,dtype", [(9000, 8, 1, 0), (9000, 4, 1, 2), (9000, 3, 5, 2), (20000, 2, 4, 1)])
+@pytest.mark.parametrize("flags", [0x2000, 0x4000, 0x6000, 0xE000])
+def test_groups_of_subtrees_per_wavefront(ft, oracle, w, P, f, E, dtype, flags):
+    """Plan flags bits 13..15: a wavefront of the register kernels walks through 1, 2, 4 or (clamped) all groups
+    of sibling subtrees of a scenario; one value per process (eight lanes per subtree, top rows staged in LDS)
+    and wider payloads (one lane per subtree); reduce with a root per scenario."""
+    S, seed = 24, 4000 + P + f + E
+    Rred, _ = _rounds(oracle, P, f)
+    fr, fo = w.random_failure_sets(seed, S, P, f, inop_permille=500, rounds_per_attempt=Rred + 1)
+    fr[:4] = w.NO_RANK                                  # some scenarios without failures
+    root = w.random_roots(seed, S, P)
+    root[:2] = 0
+    x = _payload(w, seed, S, P, E, dtype)
+    plan = ft.Plan(P, f, E, dtype, 0, flags)
+    assert plan.info.deep_kernel == (2 if E == 1 else 1)
+    compare_reduce(ft, oracle, plan, x, fr, fo, root=root)
+
+
 @pytest.mark.parametrize("P,f,E,dtype,op,S,permille", [c for c in ALLREDUCE_CASES if c[0] >= 64])
 def test_allreduce_sweep_lds_tile_kernel(ft, oracle, w, P, f, E, dtype, op, S, permille):
     """The same sweep with the LDS-tile kernel as the deepest tier (flag 0x1000)."""
