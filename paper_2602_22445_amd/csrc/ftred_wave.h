@@ -29,8 +29,6 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
-#include <type_traits>
-
 #include "ftred_geom.h"
 #include "ftred_kernels.h"
 
@@ -80,17 +78,8 @@ constexpr int cx_postorder(int n, int H, int top = 0)
     return top;
 }
 
-// In a group whose members are all alive, every member ends the up-correction with
-// the reduction of all W inputs, each in the order of its own rounds.  For the
-// integer operators (wrapping sum, bitwise or), which are associative and commutative
-// exactly, these W results are one number, and so are the W tree messages of a row
-// below which nobody failed: the register kernels then carry one value per row, not
-// W.  In floating point the W orders round differently and every member is carried.
-template <class T>
-struct SameInGroup { static constexpr bool value = !std::is_floating_point<T>::value; };
-
 // rows requested ahead of the fold: what the registers allow
-template <class T, int WP>
+template <int WP>
 struct WaveDepth { static constexpr int value = WP <= 5 ? 4 : 2; };
 
 // One lane's walk through its subtree of height HH below row rs.  bk[k] = the
@@ -106,9 +95,8 @@ struct WaveDepth { static constexpr int value = WP <= 5 ? 4 : 2; };
 // memory holds, which is the root's own input.
 template <class T, int OP, int WP, int HH, bool SWAP>
 struct SubtreeWalk {
-    static constexpr int PD = WaveDepth<T, WP>::value;
+    static constexpr int PD = WaveDepth<WP>::value;
     static constexpr int NR = (2 << HH) - 1;
-    static constexpr int NV = SameInGroup<T>::value ? 1 : WP;      // values carried per row
     const Geom& g;
     const unsigned char* const (&bk)[WP];
     uint32_t rs, ecol;
@@ -116,8 +104,8 @@ struct SubtreeWalk {
     uint32_t jx, kx;               // SWAP only
     T x0;
     T xq[PD][WP];                  // rows in flight
-    T st[HH + 1][NV];              // finished lower-numbered children waiting for their sibling, by level
-    T cur[NV];                     // the row finished last: a higher-numbered child, or the top
+    T st[HH + 1][WP];              // finished lower-numbered children waiting for their sibling, by level
+    T cur[WP];                     // the row finished last: a higher-numbered child, or the top
 
     __device__ __forceinline__ SubtreeWalk(const Geom& g_, const unsigned char* const (&bk_)[WP], uint32_t rs_,
                                            uint32_t ecol_, bool bottom_)
@@ -151,9 +139,9 @@ struct SubtreeWalk {
             for (int k = 0; k < WP; ++k) xq[N % PD][k] = (here && kx == uint32_t(k)) ? x0 : xq[N % PD][k];
         }
         // up-correction: in round t member i receives the input of member (i - t) mod W
-        T v[NV];
+        T v[WP];
 #pragma unroll
-        for (int i = 0; i < NV; ++i) {
+        for (int i = 0; i < WP; ++i) {
             T acc = xq[N % PD][i];
 #pragma unroll
             for (int t = 1; t < WP; ++t) acc = comb<T, OP>(acc, xq[N % PD][(i - t + WP) % WP]);
@@ -163,20 +151,17 @@ struct SubtreeWalk {
         // tree phase: the lower-numbered child's message first
         if constexpr (l < HH) {
 #pragma unroll
-            for (int k = 0; k < NV; ++k) {
+            for (int k = 0; k < WP; ++k) {
                 const T sum = comb<T, OP>(comb<T, OP>(v[k], st[l + 1][k]), cur[k]);
                 v[k] = (l < HH - 1 || bottom) ? sum : v[k];
             }
         }
-        // the row is folded here and not later: with one value per row the compiler otherwise keeps the loaded
-        // rows in registers and adds them up many visits on
-        if constexpr (NV == 1) asm volatile("" : "+v"(v[0]));
         if constexpr (li != 0 && (li & 1)) {
 #pragma unroll
-            for (int k = 0; k < NV; ++k) st[l][k] = v[k];
+            for (int k = 0; k < WP; ++k) st[l][k] = v[k];
         } else {
 #pragma unroll
-            for (int k = 0; k < NV; ++k) cur[k] = v[k];
+            for (int k = 0; k < WP; ++k) cur[k] = v[k];
         }
         if constexpr (N + 1 < NR) visit<N + 1>();
     }
@@ -336,24 +321,24 @@ __global__ void __launch_bounds__(kWaveThreads) wave_tier_kernel(RunArgs A, Wave
                         SubtreeWalk<T, OP, WP, kWaveH, false> w(g, bk, rs, ecol, bottom);
                         w.run();
 #pragma unroll
-                        for (int k = 0; k < WP; ++k) out[k] = w.cur[SameInGroup<T>::value ? 0 : k];
+                        for (int k = 0; k < WP; ++k) out[k] = w.cur[k];
                     } else {
                         SubtreeWalk<T, OP, WP, kWaveH - 1, false> w(g, bk, rs, ecol, true);
                         w.run();
 #pragma unroll
-                        for (int k = 0; k < WP; ++k) out[k] = w.cur[SameInGroup<T>::value ? 0 : k];
+                        for (int k = 0; k < WP; ++k) out[k] = w.cur[k];
                     }
                 } else {
                     if (any_bottom) {
                         SubtreeWalk<T, OP, WP, kWaveH, true> w(g, bk, rs, ecol, bottom);
                         w.run_swapped(root, pay);
 #pragma unroll
-                        for (int k = 0; k < WP; ++k) out[k] = w.cur[SameInGroup<T>::value ? 0 : k];
+                        for (int k = 0; k < WP; ++k) out[k] = w.cur[k];
                     } else {
                         SubtreeWalk<T, OP, WP, kWaveH - 1, true> w(g, bk, rs, ecol, true);
                         w.run_swapped(root, pay);
 #pragma unroll
-                        for (int k = 0; k < WP; ++k) out[k] = w.cur[SameInGroup<T>::value ? 0 : k];
+                        for (int k = 0; k < WP; ++k) out[k] = w.cur[k];
                     }
                 }
                 // the top row of the subtree goes to the tier above

@@ -28,8 +28,6 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
-#include <type_traits>
-
 #include "ftred_geom.h"
 #include "ftred_kernels.h"
 #include "ftred_wave.h"
@@ -57,7 +55,6 @@ inline UnitLayout make_unit_layout(const Geom& g, uint32_t dlo)
 
 template <class T, int OP, int WP>
 struct UnitRow {
-    static constexpr int NV = SameInGroup<T>::value ? 1 : WP;      // values carried per row
     // the W inputs of row j as they lie in memory
     static __device__ __forceinline__ void load(const T* x, uint32_t j, T (&r)[WP])
     {
@@ -73,10 +70,10 @@ struct UnitRow {
         for (int k = 0; k < WP; ++k) r[k] = (here && kx == uint32_t(k)) ? x0 : r[k];
     }
     // up-correction: in round t member i receives the input of member (i - t) mod W
-    static __device__ __forceinline__ void correct(const T (&r)[WP], T (&v)[NV])
+    static __device__ __forceinline__ void correct(const T (&r)[WP], T (&v)[WP])
     {
 #pragma unroll
-        for (int i = 0; i < NV; ++i) {
+        for (int i = 0; i < WP; ++i) {
             T acc = r[i];
 #pragma unroll
             for (int t = 1; t < WP; ++t) acc = comb<T, OP>(acc, r[(i - t + WP) % WP]);
@@ -121,7 +118,6 @@ __global__ void __launch_bounds__(kWaveThreads) unit_tier_kernel(RunArgs A, Unit
     const uint32_t nfull = g.a > 1u ? g.M - 1u : g.M;          // rows whose W inputs all lie in memory
     const uint32_t ngroups = 1u << ul.group_shift;
     using Row = UnitRow<T, OP, WP>;
-    constexpr int NV = Row::NV;
 
     // the lane's rows in the subtree below row rs
     auto row4 = [&](uint32_t rs) { return ((rs + 1u) << 4) - 1u + 2u * q; };
@@ -175,8 +171,8 @@ __global__ void __launch_bounds__(kWaveThreads) unit_tier_kernel(RunArgs A, Unit
     // the top rows wait in LDS for one run of stores at the end: a store between the requests would make every
     // wait for rows a wait for that store as well
     extern __shared__ __align__(16) unsigned char unit_lds[];
-    T* tops = reinterpret_cast<T*>(unit_lds);                                  // [groups][slots][NV]
-    uint32_t* folded = reinterpret_cast<uint32_t*>(tops + (size_t(NV) << (ul.group_shift + ul.slot_shift)));
+    T* tops = reinterpret_cast<T*>(unit_lds);                                  // [groups][slots][W]
+    uint32_t* folded = reinterpret_cast<uint32_t*>(tops + (size_t(WP) << (ul.group_shift + ul.slot_shift)));
 
     for (uint32_t gi = 0; gi < ngroups; ++gi) {
         UnitRows<T, WP> C = R;
@@ -201,21 +197,21 @@ __global__ void __launch_bounds__(kWaveThreads) unit_tier_kernel(RunArgs A, Unit
         Row::patch(row3(rs), jx, kx, x0, C.rc);
         Row::patch(q < 7u ? rowu(rs) : kNoRank - 1u, jx, kx, x0, C.ru);
 
-        T va[NV], vb[NV], m[NV], vu[NV];
+        T va[WP], vb[WP], m[WP], vu[WP];
         Row::correct(C.ra, va);
         Row::correct(C.rb, vb);
         Row::correct(C.rc, m);
         Row::correct(C.ru, vu);
         // level 3: the two rows of level 4 are this lane's own
 #pragma unroll
-        for (int k = 0; k < NV; ++k) m[k] = bottom ? comb<T, OP>(comb<T, OP>(m[k], va[k]), vb[k]) : m[k];
+        for (int k = 0; k < WP; ++k) m[k] = bottom ? comb<T, OP>(comb<T, OP>(m[k], va[k]), vb[k]) : m[k];
         // levels 2, 1, 0: the children rows' messages come from lanes src and src + 1; all lanes take part in the
         // permutation, the lanes of the level keep the result
 #pragma unroll
         for (int lev = 2; lev >= 0; --lev) {
             const bool at = ulev == uint32_t(lev) && q < 7u;
 #pragma unroll
-            for (int k = 0; k < NV; ++k) {
+            for (int k = 0; k < WP; ++k) {
                 const T lo = __shfl(m[k], int(src));
                 const T hi = __shfl(m[k], int(src + 1u));
                 m[k] = at ? comb<T, OP>(comb<T, OP>(vu[k], lo), hi) : m[k];
@@ -225,7 +221,7 @@ __global__ void __launch_bounds__(kWaveThreads) unit_tier_kernel(RunArgs A, Unit
         if (active && q == 6u) {
             const uint32_t at = (gi << ul.slot_shift) + slot;
 #pragma unroll
-            for (int k = 0; k < NV; ++k) tops[at * uint32_t(NV) + k] = m[k];
+            for (int k = 0; k < WP; ++k) tops[at * uint32_t(WP) + k] = m[k];
             folded[at] = mine ? 1u : 0u;
         }
     }
@@ -233,10 +229,8 @@ __global__ void __launch_bounds__(kWaveThreads) unit_tier_kernel(RunArgs A, Unit
     // the top rows go to the tier above: the subtrees of this wavefront are neighbours, so are their rows there
     const uint32_t cone0 = grp0 << ul.slot_shift, ncones = ngroups << ul.slot_shift;
     T* dst = reinterpret_cast<T*>(wsS + td.out_off) + size_t(cone0) * uint32_t(WP);
-    for (uint32_t i = lane; i < ncones * uint32_t(WP); i += kWaveThreads) {
-        const uint32_t c = i / uint32_t(WP), k = i - c * uint32_t(WP);
-        if (folded[c]) dst[i] = tops[c * uint32_t(NV) + (NV == 1 ? 0u : k)];
-    }
+    for (uint32_t i = lane; i < ncones * uint32_t(WP); i += kWaveThreads)
+        if (folded[i / uint32_t(WP)]) dst[i] = tops[i];
     for (uint32_t c = lane; c < ncones; c += kWaveThreads)
         if (folded[c]) reinterpret_cast<uint32_t*>(wsS + td.out_meta_off)[cone0 + c] = (1u << g.W) - 1u;   // all sent, no failed bit
     if (A.info) {                     // and nobody in these subtrees missed a message: empty lists
@@ -251,7 +245,7 @@ template <class T>
 inline uint32_t unit_lds_bytes(const UnitLayout& ul, uint32_t W)
 {
     const uint32_t cones = 1u << (ul.group_shift + ul.slot_shift);
-    return cones * (SameInGroup<T>::value ? 1u : W) * uint32_t(sizeof(T)) + cones * 4u;
+    return cones * W * uint32_t(sizeof(T)) + cones * 4u;
 }
 
 #define FTRED_DECLARE_UNIT_LAUNCHER(NAME) \
