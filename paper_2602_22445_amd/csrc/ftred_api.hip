@@ -410,9 +410,12 @@ static int check_common(const char* who, const ftred_plan_t* plan, uint32_t S, c
     if (workspace_bytes < ftred_workspace_bytes(plan, S))
         return fail(FTRED_EINVAL, "%s: workspace of %llu bytes, %llu needed", who, (unsigned long long)workspace_bytes,
                     (unsigned long long)ftred_workspace_bytes(plan, S));
-    for (uint32_t t = 0; t < plan->ntiers; ++t)
-        if (((uint64_t(S) + kRetrySlots) << plan->tiers[t].gshift) >= (uint64_t(1) << 31))
+    for (uint32_t t = 0; t < plan->ntiers; ++t) {
+        const uint32_t sh = (t == 0 && plan->use_wave && plan->wave_gshift > plan->tiers[t].gshift) ? plan->wave_gshift
+                                                                                                    : plan->tiers[t].gshift;
+        if (((uint64_t(S) + kRetrySlots) << sh) >= (uint64_t(1) << 31))
             return fail(FTRED_EUNSUPPORTED, "%s: S = %u scenarios need too many workgroups; split the batch", who, S);
+    }
     return FTRED_OK;
 }
 

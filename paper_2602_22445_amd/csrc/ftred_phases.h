@@ -230,7 +230,8 @@ struct BcastArgs {
 };
 
 struct BcastFail {
-    uint32_t listed, cnt_tree, cnt_corr, pad;
+    uint32_t listed, cnt_tree, cnt_corr;
+    uint32_t touched;          // a listed process stands in a row of this chunk, or above one and did not forward
     uint32_t row[16], idx[16];
     uint32_t recv_alive[16];   // alive in the round in which the value reaches it down the tree
     uint32_t blocked[16];      // dead in the round in which it would forward the value
@@ -258,10 +259,22 @@ __global__ void __launch_bounds__(kThreads) bcast_kernel(BcastArgs B)
     const bool run = B.status[s] == kStOk;
 
     uint32_t root = 0, t0 = 0;
+    // the rows (up-correction groups) with a tree member among the chunk's ranks: virtual ranks vlo .. c1-1
+    const uint32_t vlo = c0 > 1u ? c0 : 1u;
+    uint32_t j0 = 0, nrows = 0;
+    if (vlo < c1) {
+        j0 = fdiv(vlo - 1u, g.divW);
+        nrows = fdiv(c1 - 2u, g.divW) - j0 + 1u;
+    }
+    uint32_t jx = kNoRank;                    // the row of the process numbered `root`, which stands at position 0
     for (uint32_t w = tid; w < nw + 1u; w += kThreads) bits[w] = 0u;
     if (run) {
         root = B.attempts[s] - 1u;
         t0 = root * g.Ratt + g.Rred;          // broadcast round tau is global round t0 + tau
+        if (root != 0 && c0 == 0) {
+            jx = fdiv(root - 1u, g.divW);
+            if (jx >= j0 && jx < j0 + nrows) jx = kNoRank;
+        }
         if (tid < 64) {
             const uint32_t F = g.f > 0 ? g.f : 1;
             uint32_t row = kNoRank, idx = 0, ra = 0, bl = 0, corr = 0;
@@ -289,11 +302,26 @@ __global__ void __launch_bounds__(kThreads) bcast_kernel(BcastArgs B)
                 bf.row[tid] = row; bf.idx[tid] = idx; bf.recv_alive[tid] = ra; bf.blocked[tid] = bl;
                 bf.corr[tid] = corr;
             }
+            // does this entry touch a row of the chunk?  Its own row, or (if it did not forward the value) a row
+            // below its own: the rows below row r on the k-th level down are (r+1) 2^k - 1 .. (r+2) 2^k - 2
+            bool hit = false;
+            if (used) {
+                const uint32_t j1 = j0 + nrows;            // one past the last row
+                hit = (nrows != 0 && row >= j0 && row < j1) || row == jx;
+                if (bl)
+                    for (uint32_t k = 1; !hit; ++k) {
+                        const uint32_t lo = ((row + 1u) << k) - 1u, hi = ((row + 2u) << k) - 2u;
+                        if (lo >= g.M) break;
+                        hit = (nrows != 0 && lo < j1 && hi >= j0) || (jx != kNoRank && lo <= jx && jx <= hi);
+                    }
+            }
             unsigned long long m = __ballot(used);
+            unsigned long long mh = __ballot(hit);
             if (tid == 0) {
                 bf.listed = uint32_t(__popcll(m));
                 bf.cnt_tree = 0;
                 bf.cnt_corr = 0;
+                bf.touched = mh != 0ull ? 1u : 0u;
             }
         }
     }
@@ -301,18 +329,7 @@ __global__ void __launch_bounds__(kThreads) bcast_kernel(BcastArgs B)
 
     if (run) {
         // ---- who holds the value: one thread per up-correction group
-        const uint32_t vlo = c0 > 1u ? c0 : 1u;        // virtual ranks vlo .. c1-1
-        uint32_t j0 = 0, nrows = 0;
-        if (vlo < c1) {
-            j0 = fdiv(vlo - 1u, g.divW);
-            nrows = fdiv(c1 - 2u, g.divW) - j0 + 1u;
-        }
-        // the process numbered `root` stands at physical position 0 (the swap)
-        uint32_t jx = kNoRank;
-        if (root != 0 && c0 == 0) {
-            jx = fdiv(root - 1u, g.divW);
-            if (jx >= j0 && jx < j0 + nrows) jx = kNoRank;
-        }
+        const bool touched = bf.touched != 0u;         // else every process of these rows receives and forwards
         const uint32_t ntask = nrows + (jx != kNoRank ? 1u : 0u);
         uint32_t my_tree = 0, my_corr = 0;
         for (uint32_t t = tid; t < ntask; t += kThreads) {
@@ -327,7 +344,7 @@ __global__ void __launch_bounds__(kThreads) bcast_kernel(BcastArgs B)
             if (gs > nk) H |= 1u << (gs - 1u);     // the root, member a-1 of the last group, holds it
             uint32_t blockedm = 0;
             bool rowfail = false;
-            if (bf.listed != 0) {
+            if (touched) {
                 for (uint32_t q = 0; q < g.f; ++q) {
                     const uint32_t rq = bf.row[q];
                     if (rq == kNoRank) continue;
@@ -348,16 +365,20 @@ __global__ void __launch_bounds__(kThreads) bcast_kernel(BcastArgs B)
                 const uint32_t m1 = jc + 1u < g.M - 1u ? 0xFFFFu : (jc + 1u == g.M - 1u ? (1u << g.nlast) - 1u : 0u);
                 my_tree += uint32_t(__popc(snd & m0)) + uint32_t(__popc(snd & m1));
             }
-            // correction rounds
-            for (uint32_t tt = 1; tt <= g.f && tt + 1u <= gs; ++tt) {
-                uint32_t am = full;
-                if (rowfail)
-                    for (uint32_t q = 0; q < g.f; ++q)
-                        if (bf.row[q] == j && bf.corr[q] < tt) am &= ~(1u << bf.idx[q]);
-                const uint32_t snd = H & am;
-                if (owner) my_corr += uint32_t(__popc(snd));
-                const uint32_t rot = ((snd << tt) | (snd >> (gs - tt))) & full;
-                H |= rot & am;
+            // correction rounds; where everybody holds the value and lives, each of them sends in every round
+            if (!rowfail && H == full) {
+                if (owner) my_corr += gs * (g.f < gs - 1u ? g.f : gs - 1u);
+            } else {
+                for (uint32_t tt = 1; tt <= g.f && tt + 1u <= gs; ++tt) {
+                    uint32_t am = full;
+                    if (rowfail)
+                        for (uint32_t q = 0; q < g.f; ++q)
+                            if (bf.row[q] == j && bf.corr[q] < tt) am &= ~(1u << bf.idx[q]);
+                    const uint32_t snd = H & am;
+                    if (owner) my_corr += uint32_t(__popc(snd));
+                    const uint32_t rot = ((snd << tt) | (snd >> (gs - tt))) & full;
+                    H |= rot & am;
+                }
             }
             // record the holders among the row's tree members, by physical rank
             uint32_t Hm = H & tmask;
