@@ -289,6 +289,10 @@ __global__ void __launch_bounds__(kWaveThreads) wave_tier_kernel(RunArgs A, Wave
     status = __builtin_amdgcn_readfirstlane(status);
     root = __builtin_amdgcn_readfirstlane(root);
     if (status == kStBadFailureSet) return;
+    // the subtrees that go to the list kernels, one per lane (at most f + 1 of them): worked out once and side by
+    // side; a loop over the failure list in every lane, in front of every group, delayed the first rows of the walk
+    const uint32_t listed = lane < g.f ? A.fail_rank[size_t(s) * F + lane] : kNoRank;
+    const uint32_t special = subtree_of_row(special_row_of_lane(g, td.dlo, listed, root, lane), td.dlo);
     const unsigned char* pay = A.payload + size_t(s) * A.scen_stride_bytes;
     const unsigned char* bk[WP];
 #pragma unroll
@@ -306,9 +310,12 @@ __global__ void __launch_bounds__(kWaveThreads) wave_tier_kernel(RunArgs A, Wave
         const bool bottom = last_leaf < g.M;
         // subtrees on the list of the general (LDS tile) kernel are not for this one
         bool handover = false;
-        for_each_special_row(g, td.dlo, A.fail_rank + size_t(s) * F, root, [&](uint32_t jr) {
-            if (subtree_of_row(jr, td.dlo) == cone) handover = true;
-        });
+        unsigned long long hits = __ballot(special - cone_w < (1u << wl.slot_shift));    // rarely any
+        while (hits != 0ull) {
+            const int en = __ffsll(hits) - 1;
+            hits &= hits - 1ull;
+            if (uint32_t(__builtin_amdgcn_readlane(int(special), en)) == cone) handover = true;
+        }
         const bool mine = exists && !handover;
         const bool any_bottom = __ballot(mine && bottom) != 0ull;  // else no lane here has the deepest level
 
