@@ -99,10 +99,11 @@ typedef struct ftred_info {
    < 2^31 bytes, no BOR on FTRED_F64.  flags: 0 for the defaults; tuning knobs of
    the tree kernels otherwise: bits 0..7 = LDS budget in KiB of the deepest tier's
    tiles (4..24), bits 8..11 = 1 + log2 of the tiles one workgroup walks through,
-   bit 12 = LDS-tile kernel also for the deepest tier (the default there is the
-   register kernel, one lane per subtree, when the tree is deep enough and f + 1 is
-   one of 2, 3, 4, 5, 9), bits 13..15 = 1 + log2 of the groups of subtrees one
-   wavefront of that kernel walks through.
+   bit 12 = LDS-tile kernel also for the deepest tier (the default there is a
+   register kernel when the tree is deep enough and f + 1 is one of 2, 3, 4, 5, 9:
+   one lane per subtree, or eight lanes per subtree when elems == 1),
+   bits 13..15 = 1 + log2 of the groups of subtrees one wavefront of the register
+   kernel walks through.
    Host call; no device work. */
 int ftred_plan(ftred_plan_t **out, uint32_t P, uint32_t f, uint32_t elems, int dtype, int op, uint32_t flags);
 int ftred_plan_info(const ftred_plan_t *plan, ftred_info_t *info /* host, written */);
