@@ -234,6 +234,11 @@ extern "C" int ftred_plan(ftred_plan_t** out, uint32_t P, uint32_t f, uint32_t e
         if (c > 8192u) c = 8192u;
         p->bc_chunk = c;
         p->val_chunk = c;
+        // the validation of a reduce reads the inputs only: twice the ranks for the same bytes per workgroup
+        uint32_t v = (64u * 1024u) / g.EB / 32u * 32u;
+        if (v < 32u) v = 32u;
+        if (v > 8192u) v = 8192u;
+        p->val_chunk_reduce = v;
     }
     *out = p;
     return FTRED_OK;

@@ -24,7 +24,8 @@ struct ftred_plan_s {
     ftred::UnitLayout ul;
     uint32_t wave_gshift;       // workgroups of the wavefront tier per scenario = 2^wave_gshift
     uint32_t bc_chunk;          // ranks per workgroup in the broadcast kernel
-    uint32_t val_chunk;         // ranks per workgroup in the validation kernel
+    uint32_t val_chunk;         // ranks per workgroup in the validation kernel (allreduce: inputs and receive buffers)
+    uint32_t val_chunk_reduce;  // the same for a reduce (inputs only); >= val_chunk, so the scratch for val_chunk suffices
 };
 
 namespace ftred {

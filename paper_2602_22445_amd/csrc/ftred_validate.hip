@@ -424,12 +424,12 @@ extern "C" int ftred_validate(const ftred_plan_t* plan, int kind, uint32_t S, co
     A.verdict = verdict;
     unsigned char* ws = static_cast<unsigned char*>(workspace);
     const uint64_t voff = ws_val_off(plan, S);
-    const uint64_t half = uint64_t(S) * val_chunks(plan) * g.E * 8u;
+    A.chunk = kind == 1 ? plan->val_chunk : plan->val_chunk_reduce;
+    A.nchunks = (g.P + A.chunk - 1u) / A.chunk;              // <= val_chunks(plan), which sizes the scratch
+    const uint64_t half = uint64_t(S) * A.nchunks * g.E * 8u;
     A.partial = ws + voff;
     A.scale = reinterpret_cast<double*>(ws + voff + half);
     A.n_invalid = reinterpret_cast<unsigned long long*>(ws + ws_ctr_off(plan, S));
-    A.chunk = plan->val_chunk;
-    A.nchunks = val_chunks(plan);
     A.div_nchunks = make_fastdiv(A.nchunks);
     A.uc_ff = msgs_uc_ff(g);
     if (uint64_t(S) * A.nchunks >= (uint64_t(1) << 31))
