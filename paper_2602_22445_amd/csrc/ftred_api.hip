@@ -218,7 +218,7 @@ extern "C" int ftred_plan(ftred_plan_t** out, uint32_t P, uint32_t f, uint32_t e
         p->wave_gshift = most - p->wl.group_shift;                // one wavefront per workgroup
         p->use_unit = g.E == 1u ? 1u : 0u;
         if (p->use_unit) {
-            p->ul = make_unit_layout(g, p->tiers[0].dlo);
+            p->ul = make_unit_layout(p->tiers[0].dlo);
             const uint32_t mostu = p->tiers[0].dlo - p->ul.slot_shift;
             if ((flags >> 13) & 7u) p->ul.group_shift = ((flags >> 13) & 7u) - 1u < mostu ? ((flags >> 13) & 7u) - 1u : mostu;
             p->wave_gshift = mostu - p->ul.group_shift;

@@ -34,17 +34,17 @@
 
 namespace ftred {
 
-constexpr uint32_t kUnitLanes = 8;   // lanes per subtree
-constexpr uint32_t kUnitShift = 3;   // log2 of the subtrees per wavefront when the tier has that many
+constexpr uint32_t kUnitShift = 3;   // eight lanes per subtree, so eight subtrees per wavefront (fewer if the tier has fewer)
 
 struct UnitLayout {
     uint32_t slot_shift;             // 2^slot_shift sibling subtrees per wavefront pass (<= 3)
     uint32_t group_shift;            // a wavefront walks through 2^group_shift such groups
 };
 
-inline UnitLayout make_unit_layout(const Geom& g, uint32_t dlo)
+static_assert(kWaveH == 4, "the lane mapping below is written out for subtrees of height 4");
+
+inline UnitLayout make_unit_layout(uint32_t dlo)
 {
-    (void)g;
     UnitLayout u;
     u.slot_shift = dlo < kUnitShift ? dlo : kUnitShift;
     // one group per wavefront measured fastest (the rows of neighbouring wavefronts are neighbours in memory);
