@@ -58,10 +58,9 @@ inline WaveLayout make_wave_layout(const Geom& g, uint32_t dlo)
     w.slot_shift = sh;
     w.nact = (1u << sh) * w.ne;
     w.passes = (g.E + w.ne - 1u) / w.ne;
-    // enough bytes per wavefront to outweigh its start: about 64 KiB of rows or more
+    // one group per wavefront measured fastest (P = 1024, f = 3, 16 values: 1.81 ms against 1.85 ms with two) or as
+    // fast as any other number (P = 16384, f = 4, 8 values); the plan's flags can ask for more
     w.group_shift = 0;
-    while (w.group_shift < dlo - sh &&
-           (uint64_t(kWaveRows) << (sh + w.group_shift)) * g.RB < 64u * 1024u) ++w.group_shift;
     return w;
 }
 
@@ -262,8 +261,10 @@ __global__ void __launch_bounds__(kWaveThreads) wave_tier_kernel(RunArgs A, Wave
     const uint32_t wshift = td.dlo - wl.slot_shift - wl.group_shift;   // wavefronts per scenario = 2^wshift
     const uint32_t sv = blockIdx.x >> wshift;                  // scenario, or S + retry entry
     const uint32_t top0 = (1u << td.dlo) - 1u;
-    const uint32_t grp0 = (blockIdx.x & ((1u << wshift) - 1u)) << wl.group_shift;
-    if (top0 + (grp0 << wl.slot_shift) >= g.M) return;         // no such rows
+    // the groups of a wavefront lie 2^wshift groups apart: wavefronts that run side by side read rows that lie side
+    // by side whichever of its groups each of them has reached
+    const uint32_t wid = blockIdx.x & ((1u << wshift) - 1u);
+    if (top0 + (wid << wl.slot_shift) >= g.M) return;          // no such rows
 
     // lane -> (subtree slot, value index e)
     const uint32_t slot = lane / wl.ne;
@@ -299,7 +300,7 @@ __global__ void __launch_bounds__(kWaveThreads) wave_tier_kernel(RunArgs A, Wave
     for (int k = 0; k < WP; ++k) bk[k] = pay + size_t(k) * g.EB;
 
     for (uint32_t gi = 0; gi < (1u << wl.group_shift); ++gi) {
-        const uint32_t cone_w = (grp0 + gi) << wl.slot_shift;
+        const uint32_t cone_w = (wid + (gi << wshift)) << wl.slot_shift;
         if (top0 + cone_w >= g.M) break;                       // no such rows
         const uint32_t cone = cone_w + (active ? slot : 0u);
         const uint32_t rs = top0 + cone;                       // top row of the lane's subtree
