@@ -131,7 +131,8 @@ extern "C" int ftred_plan(ftred_plan_t** out, uint32_t P, uint32_t f, uint32_t e
             return fail(FTRED_EINVAL, "ftred_plan: flags bits 0..7 = LDS budget of the deepest tier in KiB, 4..24");
         budget = (flags & 0xFFu) * 1024u;
     }
-    if (((flags >> 8) & 0xFu) != 0) kwalk = ((flags >> 8) & 0xFu) - 1u;
+    const bool kwalk_given = ((flags >> 8) & 0xFu) != 0;
+    if (kwalk_given) kwalk = ((flags >> 8) & 0xFu) - 1u;
     if ((flags >> 16) != 0) return fail(FTRED_EINVAL, "ftred_plan: unknown flag bits");
     ftred_plan_t* p = new (std::nothrow) ftred_plan_t;
     if (!p) return fail(FTRED_ENOMEM, "ftred_plan: out of host memory");
@@ -164,19 +165,24 @@ extern "C" int ftred_plan(ftred_plan_t** out, uint32_t P, uint32_t f, uint32_t e
         if (p->use_wave) h0 = uint32_t(kWaveH);
         TierDesc& t = p->tiers[nt++];
         t.dlo = g.L - h0; t.dhi = g.L; t.child_in = 0;
+        // the levels above, split evenly over as few tiers as the tile allows: small cones are many workgroups
+        // of few threads, which is what these latency-bound launches want
         int d = int(t.dlo) - 1;
+        const uint32_t levels = t.dlo, upper = (levels + hcap1) / (hcap1 + 1u);      // tiers above the deepest one
+        const uint32_t per = upper ? (levels + upper - 1u) / upper : 0u;             // levels of each but the top one
         while (d >= 0) {
             if (nt == kMaxTiers) {
                 delete p;
                 return fail(FTRED_EUNSUPPORTED, "ftred_plan: the tree needs more than %d tiers at this LDS budget", kMaxTiers);
             }
-            uint32_t h = hcap1 < uint32_t(d) ? hcap1 : uint32_t(d);
+            uint32_t h = per - 1u < uint32_t(d) ? per - 1u : uint32_t(d);
             TierDesc& u = p->tiers[nt++];
             u.dlo = uint32_t(d) - h; u.dhi = uint32_t(d); u.child_in = 1;
             d = int(u.dlo) - 1;
         }
     }
     p->ntiers = nt;
+    p->kwalk_given = kwalk_given ? 1u : 0u;
     uint32_t off = align_up(g.EB, 16);      // [0, EB): the root's value after up-correction
     p->vroot_off = 0;
     for (uint32_t t = 0; t < nt; ++t) {
@@ -386,8 +392,19 @@ static int launch_tiers(const ftred_plan_t* plan, RunArgs& A, uint32_t S, uint32
             }
             uint64_t cap = (uint64_t(S) + extra) * (plan->g.f + 3u);
             HIP_TRY(dispatch_list(plan, A, uint32_t(cap < 4096u ? cap : 4096u), plan->tiers[0].lds_bytes, st));
-        } else
-            HIP_TRY(dispatch_tier(plan, A, (S + extra) << plan->tiers[t].gshift, plan->tiers[t].lds_bytes, st));
+        } else {
+            // Tiers above the deepest one: how many cones a workgroup walks through follows the batch, unless the
+            // plan's flags fix it.  About 2^14 workgroups measured best (enough to fill the chip several times,
+            // few enough for the failure table and the first loads of a workgroup to be shared by several cones).
+            TierDesc& td = A.tiers[t];
+            if (t > 0 && !plan->kwalk_given) {
+                uint32_t k = 0;
+                while (k < 3u && k < td.dlo && ((uint64_t(S) + extra) << (td.dlo - k - 1u)) >= 12288u) ++k;
+                td.kshift = k;
+                td.gshift = td.dlo - k;
+            }
+            HIP_TRY(dispatch_tier(plan, A, (S + extra) << td.gshift, plan->tiers[t].lds_bytes, st));
+        }
     }
     return FTRED_OK;
 }
@@ -416,8 +433,9 @@ static int check_common(const char* who, const ftred_plan_t* plan, uint32_t S, c
         return fail(FTRED_EINVAL, "%s: workspace of %llu bytes, %llu needed", who, (unsigned long long)workspace_bytes,
                     (unsigned long long)ftred_workspace_bytes(plan, S));
     for (uint32_t t = 0; t < plan->ntiers; ++t) {
-        const uint32_t sh = (t == 0 && plan->use_wave && plan->wave_gshift > plan->tiers[t].gshift) ? plan->wave_gshift
-                                                                                                    : plan->tiers[t].gshift;
+        uint32_t sh = plan->tiers[t].gshift;
+        if (t == 0 && plan->use_wave && plan->wave_gshift > sh) sh = plan->wave_gshift;
+        if (t > 0) sh = plan->tiers[t].dlo;                       // at most one workgroup per cone
         if (((uint64_t(S) + kRetrySlots) << sh) >= (uint64_t(1) << 31))
             return fail(FTRED_EUNSUPPORTED, "%s: S = %u scenarios need too many workgroups; split the batch", who, S);
     }

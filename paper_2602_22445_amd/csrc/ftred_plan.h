@@ -20,6 +20,7 @@ struct ftred_plan_s {
     uint32_t retry_blocks;
     uint32_t use_wave;          // the deepest tier runs as one wavefront per subtree
     ftred::WaveLayout wl;
+    uint32_t kwalk_given;       // the flags fix the cones a workgroup walks through
     uint32_t use_unit;          // ... with eight lanes per subtree (one value per process)
     ftred::UnitLayout ul;
     uint32_t wave_gshift;       // workgroups of the wavefront tier per scenario = 2^wave_gshift
