@@ -42,6 +42,22 @@ def test_plan_info_matches_the_closed_forms(ft, P, f, D, uc, groups, a):
     assert p.workspace_bytes(4) > 0
 
 
+@pytest.mark.parametrize("P,f,E,dtype,tiers,kernel", [
+    (8, 1, 4, 0, 1, 0),                     # the whole tree in one LDS tile
+    (64, 2, 8, 1, 1, 0),
+    (1024, 3, 16, 0, 2, 1),                 # deepest tier in registers (one lane per subtree) + the top tier
+    (16384, 4, 8, 2, 3, 1),                 # depths 7..11 in registers, 3..6 and 0..2 in LDS tiles
+    (1 << 20, 8, 1, 0, 3, 2),               # one value per process: eight lanes per subtree
+    (3000, 12, 2, 0, 2, 0),                 # a group width the register kernels are not built for
+])
+def test_plan_tiers_and_deepest_kernel(ft, P, f, E, dtype, tiers, kernel):
+    """Launches of one tree phase and the kernel of the deepest tier for the shapes of the workloads: the levels
+    above the deepest tier are split over as few LDS-tile tiers as fit."""
+    i = ft.Plan(P, f, E, dtype, ft.SUM).info
+    assert (i.tiers, i.deep_kernel) == (tiers, kernel)
+    assert ft.Plan(P, f, E, dtype, ft.SUM, 0x1000).info.deep_kernel == 0
+
+
 def test_plan_rejects_bad_arguments(ft):
     for args in [(2, 1, 1, ft.I64, ft.SUM), (8, 1, 0, ft.I64, ft.SUM), (8, 1, 1, 7, ft.SUM),
                  (8, 1, 1, ft.F64, ft.BOR), (8, 1, 1, ft.I64, 5), (100, 16, 1, ft.I64, ft.SUM),
