@@ -160,3 +160,21 @@ def test_allreduce_p2e20_f8_1024_scenarios(ft, oracle, w):
     assert np.array_equal(g["msgs"].cpu().numpy()[idx], o["msgs"])
     assert np.array_equal(unpack_bitmap(g["has_bitmap"].cpu().numpy()[idx], P), o["has"])
     assert np.array_equal(g["per_process_out"][sel].cpu().numpy(), o["out"])
+
+
+def test_allreduce_p2e20_f1_u32_deep_binary_groups(ft, oracle, w):
+    """A tree of 19 levels with groups of two (P = 2^20, f = 1, one uint32 per process): the narrowest rows
+    (8 bytes) through the eight-lanes-per-subtree kernel and two LDS-tile tiers of seven levels each; every
+    scenario against the oracle."""
+    from _cmp import compare_allreduce
+    P, f, E, S, seed = 1 << 20, 1, 1, 6, 55
+    plan = ft.Plan(P, f, E, ft.U32, ft.SUM)
+    assert plan.info.deep_kernel == 2 and plan.info.tiers == 3
+    Ratt = plan.info.rounds_attempt
+    fr, fo = w.random_failure_sets(seed, S, P, f, inop_permille=500, rounds_per_attempt=Ratt, protected=f + 1)
+    fr[0], fo[0] = w.NO_RANK, 0
+    fr[1, 0], fo[1, 0] = 0, 0                        # a second attempt
+    fr[2, 0], fo[2, 0] = P - 1, 0
+    fr[3, 0], fo[3, 0] = 2, 0                        # the top of a subtree of the second root
+    x = w.payload_int(seed, S, P, E, "u32", 32)
+    compare_allreduce(ft, oracle, plan, x, fr, fo)
