@@ -377,10 +377,11 @@ static int launch_tiers(const ftred_plan_t* plan, RunArgs& A, uint32_t S, uint32
         A.tier = t;
         TimedLaunch tl(t == 0 ? FTRED_PH_TREE_DEEP : FTRED_PH_TREE_UPPER, st);
         if (t == 0 && plan->use_wave) {
-            // subtrees with listed processes, relabelled ranks, the short last group or a ragged bottom are listed
-            // and run by the general kernel; the register kernel runs all the others
+            // subtrees with listed processes, the short last group or a ragged bottom are listed and run by the
+            // list kernels; the plain register kernel runs all the others
             A.wave_general = A.info ? 0u : 1u;     // the lists of failed processes travel through the tile kernel only
-            // at most f + 3 listed subtrees per scenario or retry entry, 2^slot_shift of them per wavefront
+            // room for f + 3 listed subtrees per scenario or retry entry (at most f + 1 occur), 2^slot_shift of
+            // them per wavefront
             const uint64_t wgs = ((uint64_t(S) + extra) * (plan->g.f + 3u) + (1u << plan->wl.slot_shift) - 1u) >> plan->wl.slot_shift;
             A.wfix_cap = uint32_t(wgs << plan->wl.slot_shift);
             hipLaunchKernelGGL(fixlist_kernel, dim3((S + extra + 255u) / 256u), dim3(256), 0, st, A);

@@ -762,8 +762,8 @@ __global__ void __launch_bounds__(kThreads) tier_kernel(RunArgs A)
     else walk_cones<T, OP, WP, T>(A, td, ft, lrows, lmeta, s, root, base, c_lo, c_hi, pay, wsS, discard, td.lds_rows);
 }
 
-// The deepest tier's subtrees that are not for the register kernel (failures, the
-// short last group, relabelled ranks, ragged bottom level): workgroups stride over
+// The deepest tier's subtrees that are not for the plain register kernel (failures,
+// the short last group, ragged bottom level): workgroups stride over
 // the list, one subtree at a time.  The entries are independent, so everything an
 // entry needs from memory (its descriptor, the failure list, the rows, the two
 // patched values) is requested while the entry before it is reduced out of LDS.

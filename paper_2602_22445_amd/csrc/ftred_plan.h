@@ -58,8 +58,8 @@ inline uint64_t ws_list_bytes(const ftred_plan_s* p, uint32_t S)
     // at most f failed attempts per scenario, two words each
     return (uint64_t(S) * p->g.f * 8u + 255u) / 256u * 256u;
 }
-// subtrees the register kernel leaves to the general kernel: at most f + 3 per
-// scenario or retry entry, four words each
+// subtrees the plain register kernel leaves to the list kernels: at most f + 1 per
+// scenario or retry entry (room for f + 3), four words each
 inline uint64_t ws_fix_off(const ftred_plan_s* p, uint32_t S) { return ws_list_off(p, S) + ws_list_bytes(p, S); }
 inline uint64_t ws_fix_bytes(const ftred_plan_s* p, uint32_t S)
 {

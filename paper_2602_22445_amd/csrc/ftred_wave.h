@@ -14,11 +14,14 @@
 // ahead of the fold.
 //
 // This kernel runs the subtrees in which every row exists (with or without the
-// bottom level), nothing is listed as failed, and neither the relabelled ranks nor
-// the short last group occur.  The few others (at most f + 3 per scenario) are
-// listed by a small kernel of their own and run by the general LDS-tile kernel,
-// which carries per-member liveness, sent and failed bits (section "Failure
-// information": the single failed bit); here they are skipped.
+// bottom level), nobody is listed as failed and the short last group does not
+// occur; a root other than process 0 is handled here (the relabelled rank's input
+// is swapped in).  The few others (at most f + 1 per scenario) are listed by a
+// small kernel of their own and run by the list kernels (ftred_wave_general.h, or
+// the LDS-tile kernel when the lists of failed processes are asked for), which
+// carry per-member liveness, sent and failed bits (section "Failure information":
+// the single failed bit); here they are skipped.  A wavefront walks through one or
+// more groups of sibling subtrees; its groups lie a stride of wavefronts apart.
 //
 // The subtree's top row leaves through the scratch area in the format the upper
 // tiers read: W*E values and one word (bits 0..15 sent, 16..31 failed bit).
