@@ -387,12 +387,13 @@ static int launch_tiers(const ftred_plan_t* plan, RunArgs& A, uint32_t S, uint32
             hipLaunchKernelGGL(fixlist_kernel, dim3((S + extra + 255u) / 256u), dim3(256), 0, st, A);
             HIP_TRY(hipGetLastError());
             HIP_TRY(dispatch_wave(plan, A, (S + extra) << plan->wave_gshift, st));
-            if (A.wave_general) {
+            if (A.wave_general) {           // every listed subtree is on the register kernel's list
                 const uint32_t lds = (1u << plan->wl.slot_shift) * kWaveRows * uint32_t(sizeof(RowInfo));
                 HIP_TRY(dispatch_wave_list(plan, A, uint32_t(wgs), lds, st));
+            } else {                        // every listed subtree is on the LDS-tile kernel's list
+                uint64_t cap = (uint64_t(S) + extra) * (plan->g.f + 3u);
+                HIP_TRY(dispatch_list(plan, A, uint32_t(cap < 4096u ? cap : 4096u), plan->tiers[0].lds_bytes, st));
             }
-            uint64_t cap = (uint64_t(S) + extra) * (plan->g.f + 3u);
-            HIP_TRY(dispatch_list(plan, A, uint32_t(cap < 4096u ? cap : 4096u), plan->tiers[0].lds_bytes, st));
         } else {
             // Tiers above the deepest one: how many cones a workgroup walks through follows the batch, unless the
             // plan's flags fix it.  About 2^14 workgroups measured best (enough to fill the chip several times,
