@@ -293,6 +293,41 @@ def test_allreduce_sweep_lds_tile_kernel(ft, oracle, w, P, f, E, dtype, op, S, p
     compare_allreduce(ft, oracle, plan, x, fr, fo)
 
 
+def test_two_streams_with_their_own_workspaces_do_not_disturb_each_other(ft, oracle, w):
+    """Two plans run side by side on two streams (default priority), each with its own workspace and output
+    buffers, several calls each: the library keeps no device state of its own between or across calls."""
+    shapes = [(3000, 3, 5, 2, 0), (2500, 8, 1, 0, 0)]
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    S = 48
+    jobs = []
+    for (P, f, E, dtype, op), st in zip(shapes, streams):
+        seed = 8800 + P
+        _, Ratt = _rounds(oracle, P, f)
+        fr, fo = w.random_failure_sets(seed, S, P, f, inop_permille=500, rounds_per_attempt=Ratt, protected=f + 1)
+        fr[1, 0], fo[1, 0] = 0, 0
+        x = _payload(w, seed, S, P, E, dtype)
+        plan = ft.Plan(P, f, E, dtype, op)
+        jobs.append(dict(plan=plan, x=x, fr=fr, fo=fo, st=st, xd=to_dev(x), frd=to_dev(fr), fod=to_dev(fo),
+                         ws=plan.workspace(S), bufs=None))
+    torch.cuda.synchronize()
+    for _ in range(3):
+        for j in jobs:
+            with torch.cuda.stream(j["st"]):
+                j["bufs"] = ft.run_allreduce(j["plan"], S, j["xd"], j["frd"], j["fod"], workspace=j["ws"],
+                                             buffers=j["bufs"], stream=j["st"])
+    torch.cuda.synchronize()
+    for j in jobs:
+        plan, g = j["plan"], j["bufs"]
+        o = oracle.allreduce_batch(plan.P, plan.f, j["x"], plan.dtype, plan.op, S, fail_rank=j["fr"],
+                                   fail_round=j["fo"], want_has=True, want_out=True)
+        assert np.array_equal(g["status"].cpu().numpy(), o["status"])
+        assert np.array_equal(g["attempts"].cpu().numpy(), o["attempts"])
+        assert np.array_equal(g["result"].cpu().numpy(), o["result"])
+        assert np.array_equal(g["msgs"].cpu().numpy(), o["msgs"])
+        assert np.array_equal(unpack_bitmap(g["has_bitmap"].cpu().numpy(), plan.P), o["has"])
+        assert np.array_equal(g["per_process_out"].cpu().numpy(), o["out"])
+
+
 def test_runs_are_deterministic(ft, oracle, w):
     P, f, E, S = 4099, 4, 8, 64
     _, Ratt = _rounds(oracle, P, f)
