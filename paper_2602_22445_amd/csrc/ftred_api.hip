@@ -222,6 +222,7 @@ extern "C" int ftred_plan(ftred_plan_t** out, uint32_t P, uint32_t f, uint32_t e
         const uint32_t most = p->tiers[0].dlo - p->wl.slot_shift;
         if ((flags >> 13) & 7u) p->wl.group_shift = ((flags >> 13) & 7u) - 1u < most ? ((flags >> 13) & 7u) - 1u : most;
         p->wave_gshift = most - p->wl.group_shift;                // one wavefront per workgroup
+        p->wl.stage = (p->wl.group_shift > 0 && wave_can_stage(g, p->wl)) ? 1u : 0u;
         p->use_unit = g.E == 1u ? 1u : 0u;
         if (p->use_unit) {
             p->ul = make_unit_layout(p->tiers[0].dlo);

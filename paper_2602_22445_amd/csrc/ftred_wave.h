@@ -47,7 +47,21 @@ struct WaveLayout {                  // how the 64 lanes map to (subtree slot, v
     uint32_t nact;                   // active lanes = slots * ne
     uint32_t passes;                 // ceil(E / ne)
     uint32_t group_shift;            // a wavefront walks through 2^group_shift groups of subtrees
+    uint32_t stage;                  // 1: the top rows of all its groups wait in LDS for one run of stores at the end
 };
+
+// LDS of one wavefront when the top rows are staged: the rows, then one word per subtree
+inline uint32_t wave_lds_bytes(const Geom& g, const WaveLayout& w)
+{
+    const uint32_t cones = 1u << (w.group_shift + w.slot_shift);
+    return w.stage ? cones * g.RB + cones * 4u : 0u;
+}
+
+// staging needs all value indices in one pass and a modest tile
+inline bool wave_can_stage(const Geom& g, const WaveLayout& w)
+{
+    return w.passes == 1u && g.RB % 8u == 0u && (uint64_t(g.RB + 4u) << (w.group_shift + w.slot_shift)) <= 12u * 1024u;
+}
 
 // group widths the kernel is built for (straight-line code per width)
 inline bool wave_width_ok(uint32_t W) { return W == 2 || W == 3 || W == 4 || W == 5 || W == 9; }
@@ -61,9 +75,16 @@ inline WaveLayout make_wave_layout(const Geom& g, uint32_t dlo)
     w.slot_shift = sh;
     w.nact = (1u << sh) * w.ne;
     w.passes = (g.E + w.ne - 1u) / w.ne;
-    // one group per wavefront measured fastest (P = 1024, f = 3, 16 values: 1.81 ms against 1.85 ms with two) or as
-    // fast as any other number (P = 16384, f = 4, 8 values); the plan's flags can ask for more
+    // Four groups per wavefront with the top rows staged in LDS where a scenario still has four wavefronts or more
+    // then (P = 16384, f = 4, 8 values: 0.88 ms against 0.91 ms with one group); else one group (P = 1024, f = 3,
+    // 16 values: 1.80 ms against 1.83 ms with two or four).  The plan's flags can ask for another number.
     w.group_shift = 0;
+    w.stage = 0;
+    if (dlo >= sh + 4u) {
+        w.group_shift = 2;
+        if (wave_can_stage(g, w)) w.stage = 1;
+        else w.group_shift = 0;
+    }
     return w;
 }
 
@@ -268,6 +289,15 @@ __global__ void __launch_bounds__(kWaveThreads) wave_tier_kernel(RunArgs A, Wave
     // by side whichever of its groups each of them has reached
     const uint32_t wid = blockIdx.x & ((1u << wshift) - 1u);
     if (top0 + (wid << wl.slot_shift) >= g.M) return;          // no such rows
+    // staged top rows: [group][slot][member][value index], then one word per (group, slot): folded here
+    extern __shared__ __align__(16) unsigned char wave_lds[];
+    const uint32_t ncones = 1u << (wl.group_shift + wl.slot_shift);
+    T* tile = reinterpret_cast<T*>(wave_lds);
+    uint32_t* folded = reinterpret_cast<uint32_t*>(wave_lds + size_t(ncones) * g.RB);
+    if (wl.stage) {
+        for (uint32_t c = threadIdx.x; c < ncones; c += kWaveThreads) folded[c] = 0u;
+        __syncthreads();
+    }
 
     // lane -> (subtree slot, value index e)
     const uint32_t slot = lane / wl.ne;
@@ -352,6 +382,14 @@ __global__ void __launch_bounds__(kWaveThreads) wave_tier_kernel(RunArgs A, Wave
                         for (int k = 0; k < WP; ++k) out[k] = w.cur[k];
                     }
                 }
+                if (wl.stage) {
+                    // the top row waits in LDS: a run of stores per group would hold up the rows requested after it
+                    const uint32_t at = (gi << wl.slot_shift) + slot;
+#pragma unroll
+                    for (int k = 0; k < WP; ++k) tile[(size_t(at) * WP + k) * g.E + ecol] = out[k];
+                    if (ecol == 0) folded[at] = 1u;
+                    continue;
+                }
                 // the top row of the subtree goes to the tier above
                 unsigned char* dst = wsS + td.out_off + size_t(cone) * g.RB + size_t(ecol) * g.esz;
 #pragma unroll
@@ -364,6 +402,25 @@ __global__ void __launch_bounds__(kWaveThreads) wave_tier_kernel(RunArgs A, Wave
                         for (int k = 0; k < WP; ++k) mk[k] = 0;
                     }
                 }
+            }
+        }
+    }
+    if (wl.stage) {
+        __syncthreads();
+        const uint32_t RE = g.W * g.E, smask = (1u << wl.slot_shift) - 1u;
+        auto cone_of = [&](uint32_t c) { return ((wid + ((c >> wl.slot_shift) << wshift)) << wl.slot_shift) + (c & smask); };
+        T* dst = reinterpret_cast<T*>(wsS + td.out_off);
+        for (uint32_t i = lane; i < ncones * RE; i += kWaveThreads) {
+            const uint32_t c = fdiv(i * g.esz, g.divRB);
+            if (folded[c]) dst[size_t(cone_of(c)) * RE + (i - c * RE)] = tile[i];
+        }
+        for (uint32_t c = lane; c < ncones; c += kWaveThreads)
+            if (folded[c]) reinterpret_cast<uint32_t*>(wsS + td.out_meta_off)[cone_of(c)] = (1u << g.W) - 1u;
+        if (A.info) {
+            uint16_t* mk = reinterpret_cast<uint16_t*>(wsS + td.out_mask_off);
+            for (uint32_t i = lane; i < ncones * g.W; i += kWaveThreads) {
+                const uint32_t c = fdiv(i, g.divW);
+                if (folded[c]) mk[size_t(cone_of(c)) * g.W + (i - c * g.W)] = 0;
             }
         }
     }
@@ -382,7 +439,8 @@ FTRED_DECLARE_WAVE_LAUNCHER(f64_sum)
     template <int WP>                                                                               \
     static hipError_t wave_wp_##NAME(const RunArgs& A, const WaveLayout& wl, uint32_t grid, hipStream_t st) \
     {                                                                                               \
-        hipLaunchKernelGGL((wave_tier_kernel<T, OP, WP>), dim3(grid), dim3(kWaveThreads), 0, st, A, wl); \
+        hipLaunchKernelGGL((wave_tier_kernel<T, OP, WP>), dim3(grid), dim3(kWaveThreads),           \
+                           wave_lds_bytes(A.g, wl), st, A, wl);                                     \
         return hipGetLastError();                                                                   \
     }                                                                                               \
     hipError_t launch_wave_##NAME(const RunArgs& A, const WaveLayout& wl, uint32_t grid, hipStream_t st) \
