@@ -110,6 +110,12 @@ int ftred_plan_info(const ftred_plan_t *plan, ftred_info_t *info /* host, writte
 void ftred_plan_destroy(ftred_plan_t *plan);
 const char *ftred_last_error(void);      /* never NULL; valid until the thread's next failing call */
 
+/* The hash of the sources this library was built from (hex sha256 over the HIP
+   sources and headers, computed by the build); never NULL, "unknown" for a build
+   that did not pass one.  Lets a binding refuse a library that is older than the
+   sources beside it. */
+const char *ftred_source_hash(void);
+
 /* Bytes of device workspace a run or validation of S scenarios needs. */
 uint64_t ftred_workspace_bytes(const ftred_plan_t *plan, uint32_t S);
 
@@ -248,8 +254,10 @@ int ftred_gen_payload_int(const ftred_plan_t *plan, uint64_t seed, uint32_t S, u
    are not timed).  ftred_timing_end waits for the recorded events, adds up the
    elapsed milliseconds and the number of launches per phase (arrays of
    FTRED_PH_COUNT entries, host, either may be NULL), frees the events and switches
-   timing off.  Process-wide, not thread-safe; callers that time several streams
-   get the sum over them. */
+   timing off.  For benchmarks only: the state is process-wide and not
+   thread-safe, so while timing is on (and during the two calls themselves) no
+   other thread may call into the library; callers that time several streams get
+   the sum over them. */
 enum {
     FTRED_PH_CHECK = 0,        /* scenario check */
     FTRED_PH_RETRY = 1,        /* attempts with a failed root */

@@ -61,6 +61,16 @@ def lib():
         if not os.path.exists(LIB_PATH):
             raise RuntimeError("libftred.so is not built (%s); run `python -m paper_2602_22445_amd.build`" % LIB_PATH)
         L = ctypes.CDLL(LIB_PATH)
+        # a library built from other sources than those beside it would test or time code that is not there
+        from . import build
+        try:
+            L.ftred_source_hash.restype = ctypes.c_char_p
+            have = L.ftred_source_hash().decode()
+        except AttributeError:
+            have = None
+        if have != build.source_hash():
+            raise RuntimeError("libftred.so is stale: it was not built from the sources in %s; run "
+                               "`python -m paper_2602_22445_amd.build`" % os.path.join(HERE, "csrc"))
         L.ftred_plan.argtypes = [ctypes.POINTER(_vp), _u32, _u32, _u32, _int, _int, _u32]
         L.ftred_plan_info.argtypes = [_vp, ctypes.POINTER(Info)]
         L.ftred_plan_destroy.argtypes = [_vp]

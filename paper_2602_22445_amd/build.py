@@ -8,6 +8,7 @@ paper_2602_22445_amd/libftred.so.  hipcc cross-compiles without a GPU.
 from __future__ import annotations
 
 import glob
+import hashlib
 import os
 import subprocess
 import sys
@@ -31,11 +32,32 @@ def _deps():
     return glob.glob(os.path.join(CSRC, "*.h")) + glob.glob(os.path.join(HERE, "..", "include", "*.h"))
 
 
-def needs_build() -> bool:
+def source_hash() -> str:
+    """sha256 over the HIP sources and the headers (csrc/ and include/), in name order.
+    The build compiles it into the library (ftred_source_hash), so that a library
+    that was built from other sources than those on disk can be told apart."""
+    h = hashlib.sha256()
+    for p in sorted(_sources() + _deps(), key=os.path.basename):
+        h.update(os.path.basename(p).encode())
+        h.update(open(p, "rb").read())
+    return h.hexdigest()
+
+
+def built_hash():
+    """The source hash the library on disk was built from, or None."""
     if not os.path.exists(LIB):
-        return True
-    t = os.path.getmtime(LIB)
-    return any(os.path.getmtime(p) > t for p in _sources() + _deps())
+        return None
+    import ctypes
+    try:
+        L = ctypes.CDLL(LIB)
+        L.ftred_source_hash.restype = ctypes.c_char_p
+        return L.ftred_source_hash().decode()
+    except (OSError, AttributeError):
+        return None
+
+
+def needs_build() -> bool:
+    return built_hash() != source_hash()
 
 
 def build(force: bool = True, jobs: int = 8, verbose: bool = False) -> str:
@@ -43,10 +65,11 @@ def build(force: bool = True, jobs: int = 8, verbose: bool = False) -> str:
     if not force and not needs_build():
         return LIB
     os.makedirs(OBJ, exist_ok=True)
+    sha = source_hash()
 
     def compile_one(src):
         obj = os.path.join(OBJ, os.path.basename(src)[:-4] + ".o")
-        cmd = [HIPCC] + FLAGS + ["-c", src, "-o", obj]
+        cmd = [HIPCC] + FLAGS + ["-DFTRED_SOURCE_HASH=\"%s\"" % sha, "-c", src, "-o", obj]
         r = subprocess.run(cmd, capture_output=True, text=True)
         if r.returncode != 0:
             raise RuntimeError("hipcc failed for %s:\n%s\n%s" % (src, r.stdout, r.stderr))

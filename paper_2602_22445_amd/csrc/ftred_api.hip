@@ -33,6 +33,11 @@ int ftred::set_error(int code, const char* fmt, ...)
 
 extern "C" const char* ftred_last_error(void) { return g_err; }
 
+#ifndef FTRED_SOURCE_HASH
+#define FTRED_SOURCE_HASH "unknown"
+#endif
+extern "C" const char* ftred_source_hash(void) { return FTRED_SOURCE_HASH; }
+
 // ---------------------------------------------------------------------------
 // timing of kernel launches with event pairs
 
