@@ -182,6 +182,26 @@ int ftred_run_allreduce(const ftred_plan_t *plan, uint32_t S,
                         uint32_t *status, uint32_t *attempts, uint64_t *msgs,
                         void *workspace, uint64_t workspace_bytes, void *hip_stream);
 
+/* ftred_run_allreduce for callers that cannot allocate device memory (code under
+   HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): the
+   same operation, arguments and results, but the workspace is a fixed array of
+   FTRED_NOALLOC_WORKSPACE_BYTES in device memory that belongs to the library
+   (every GPU the library runs on holds its own copy until the process ends).
+   The call allocates and frees nothing; it enqueues kernels on the caller's
+   stream like ftred_run_allreduce.  Returns FTRED_EUNSUPPORTED, with nothing
+   enqueued, when ftred_workspace_bytes(plan, S) exceeds the array: use fewer
+   scenarios per call.  All calls on one GPU share that GPU's array, which keeps
+   what the last call left (the run clears what it needs to find zero): calls
+   whose kernels may overlap on one GPU, on different streams or from different
+   threads, race on it and must be ordered by the caller. */
+#define FTRED_NOALLOC_WORKSPACE_BYTES (32u * 1024u * 1024u)
+int ftred_run_allreduce_noalloc(const ftred_plan_t *plan, uint32_t S,
+                                const void *payload, uint64_t scen_stride_elems,
+                                const uint32_t *fail_rank, const uint32_t *fail_round,
+                                void *result, uint32_t *has_bitmap, void *per_process_out,
+                                uint32_t *status, uint32_t *attempts, uint64_t *msgs,
+                                void *hip_stream);
+
 /* The same operations with the two richer failure descriptions of section
    "Failure information" carried by the tree messages beside the failed bit: the
    list of the processes a sender and its descendants could not receive a value

@@ -82,6 +82,7 @@ def lib():
         L.ftred_structure.argtypes = [_vp, _u32] + [_vp] * 8
         L.ftred_run_reduce.argtypes = [_vp, _u32, _vp, _vp, _u64, _vp, _vp, _vp, _vp, _vp, _vp, _u64, _vp]
         L.ftred_run_allreduce.argtypes = [_vp, _u32, _vp, _u64, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _u64, _vp]
+        L.ftred_run_allreduce_noalloc.argtypes = [_vp, _u32, _vp, _u64, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]
         L.ftred_run_reduce_info.argtypes = [_vp, _u32, _vp, _vp, _u64, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _u64,
                                             _vp]
         L.ftred_run_allreduce_info.argtypes = [_vp, _u32, _vp, _u64, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp,
@@ -209,6 +210,22 @@ def run_allreduce(plan, S, payload, fail_rank, fail_round, want_bitmap=True, wan
                                      _ptr(result), _ptr(bitmap), _ptr(out), _ptr(status), _ptr(attempts),
                                      _ptr(msgs), _ptr(ws), ws.numel(), _stream(stream)))
     return dict(result=result, has_bitmap=bitmap, per_process_out=out, status=status, attempts=attempts, msgs=msgs)
+
+
+NOALLOC_WORKSPACE_BYTES = 32 * 1024 * 1024
+
+
+def run_allreduce_noalloc(plan, S, payload, fail_rank, fail_round, buffers, stream=None):
+    """ftred_run_allreduce_noalloc: the workspace is the library's own fixed array.  `buffers`: the output
+    tensors (result, has_bitmap, per_process_out, status, attempts, msgs; the optional ones may be None),
+    allocated by the caller beforehand.  Returns `buffers`."""
+    stride = _payload_stride(plan, payload, S)
+    _fail(plan, S, fail_rank, fail_round)
+    _check(lib().ftred_run_allreduce_noalloc(plan.handle, S, _ptr(payload), stride, _ptr(fail_rank), _ptr(fail_round),
+                                             _ptr(buffers["result"]), _ptr(buffers["has_bitmap"]),
+                                             _ptr(buffers["per_process_out"]), _ptr(buffers["status"]),
+                                             _ptr(buffers["attempts"]), _ptr(buffers["msgs"]), _stream(stream)))
+    return buffers
 
 
 def _info_buffers(plan, S, dev):

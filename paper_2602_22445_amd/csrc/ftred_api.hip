@@ -6,6 +6,7 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <mutex>
 #include <new>
 
 #include "../../include/ftred.h"
@@ -668,4 +669,57 @@ extern "C" int ftred_run_allreduce_info(const ftred_plan_t* plan, uint32_t S, co
     return run_allreduce_impl("ftred_run_allreduce_info", plan, S, payload, scen_stride_elems, fail_rank, fail_round,
                               result, has_bitmap, per_process_out, status, attempts, msgs,
                               InfoOut{info_count, info_ids, info_child}, workspace, workspace_bytes, hip_stream);
+}
+
+// ---------------------------------------------------------------------------
+// allreduce for callers that cannot allocate: the workspace is a fixed array in
+// device memory that belongs to the library
+
+static __device__ __align__(256) unsigned char scratch[FTRED_NOALLOC_WORKSPACE_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+unsigned char* g_scratch_ptr[kMaxDevices];     // the array's address on each device, once known
+}  // namespace
+
+// The address of `scratch` on the current device.  Every device holds its own copy of the array at its
+// own address; the name itself is only a host-side handle, never a pointer a kernel could use.
+static int scratch_of_current_device(unsigned char** out)
+{
+    int dev = -1;
+    HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return fail(FTRED_EUNSUPPORTED, "ftred_run_allreduce_noalloc: device %d not supported", dev);
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) return fail(FTRED_EDEVICE, "ftred_run_allreduce_noalloc: the workspace array has no device address");
+        g_scratch_ptr[dev] = static_cast<unsigned char*>(p);
+    }
+    *out = g_scratch_ptr[dev];
+    return FTRED_OK;
+}
+
+extern "C" int ftred_run_allreduce_noalloc(const ftred_plan_t* plan, uint32_t S, const void* payload,
+                                           uint64_t scen_stride_elems, const uint32_t* fail_rank,
+                                           const uint32_t* fail_round, void* result, uint32_t* has_bitmap,
+                                           void* per_process_out, uint32_t* status, uint32_t* attempts, uint64_t* msgs,
+                                           void* hip_stream)
+{
+    if (!plan) return fail(FTRED_EINVAL, "ftred_run_allreduce_noalloc: plan is NULL");
+    const uint64_t need = ftred_workspace_bytes(plan, S);
+    if (need > uint64_t(FTRED_NOALLOC_WORKSPACE_BYTES))
+        return fail(FTRED_EUNSUPPORTED,
+                    "ftred_run_allreduce_noalloc: S = %u scenarios of this plan need %llu bytes of workspace, the "
+                    "library's fixed array holds %llu; use fewer scenarios per call or ftred_run_allreduce",
+                    S, (unsigned long long)need, (unsigned long long)FTRED_NOALLOC_WORKSPACE_BYTES);
+    unsigned char* ws = nullptr;
+    const int rc = scratch_of_current_device(&ws);
+    if (rc != FTRED_OK) return rc;
+    // Nothing in the workspace has to survive from call to call, and what must start at zero (the counters of the
+    // retry entries and of the lists of subtrees) is cleared by the run itself, by a kernel on the caller's stream.
+    return run_allreduce_impl("ftred_run_allreduce_noalloc", plan, S, payload, scen_stride_elems, fail_rank, fail_round,
+                              result, has_bitmap, per_process_out, status, attempts, msgs,
+                              InfoOut{nullptr, nullptr, nullptr}, ws, uint64_t(FTRED_NOALLOC_WORKSPACE_BYTES), hip_stream);
 }
