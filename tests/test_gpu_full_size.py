@@ -1,16 +1,17 @@
 """The three large workloads at their full sizes, in the launch configuration the
 benchmark times (default plan flags, the whole batch in one call): the HIP library
-runs every scenario; the CPU oracle runs a sample of them, and every compared
-output of the sample must agree as in the small parity tests.  Properties that
-hold at any size are checked over the whole batch: the library's own validation
-pass finds no invalid scenario, statuses are OK, attempts are 1 + the number of
-leading root candidates listed as failed.
+runs every scenario, and so does the CPU oracle, slice by slice so that host
+memory stays bounded; EVERY scenario's status, result, message counters, attempts,
+holder bitmap and receive buffers must agree as in the small parity tests.  As a
+second check the library's own validation pass must find no invalid scenario.
 
-Inputs: the failure sets of the whole batch and the payload of the sampled
-scenarios come from the seeded host generators; the payload of the whole batch
-comes from the host generator (floating point) or from the library's device
-generator, which implements the same counter-based generator and is compared
-with the host's on the sample."""
+Inputs: failure sets and roots of the whole batch come from the seeded host
+generators.  The integer payloads the GPU works on are written by the library's
+device generator; each slice is generated again on the host for the oracle
+(scen0 = first scenario of the slice) and the two must be identical.  The
+floating-point payload is generated on the host and uploaded."""
+from concurrent.futures import ThreadPoolExecutor
+
 import numpy as np
 import pytest
 import torch
@@ -34,11 +35,6 @@ def w():
     return workloads
 
 
-def _sample(S, n, extra=()):
-    idx = sorted(set(np.linspace(0, S - 1, n).astype(np.int64).tolist()) | {int(e) for e in extra})
-    return np.array(idx, dtype=np.int64)
-
-
 def _expected_attempts(fr, fo, f):
     """1 + number of leading root candidates 0, 1, .. listed as failed before the operation."""
     S = fr.shape[0]
@@ -49,9 +45,22 @@ def _expected_attempts(fr, fo, f):
     return att
 
 
+def _host_payload_int(w, seed, s0, n, P, E, dtype, bits, threads=16):
+    """payload_int for scenarios s0 .. s0+n-1, a few scenarios per task."""
+    out = np.empty((n, P, E), dtype=np.int64 if dtype == "i64" else np.uint32)
+    step = max(1, min(64, n // threads))
+
+    def one(a):
+        out[a:a + step] = w.payload_int(seed, min(step, n - a), P, E, dtype, bits, scen0=s0 + a)
+
+    with ThreadPoolExecutor(max_workers=threads) as ex:
+        list(ex.map(one, range(0, n, step)))
+    return out
+
+
 def test_reduce_p1024_f3_65536_scenarios(ft, oracle, w):
     """Reduce, P = 1024, f = 3, 16 x int64 in [-2^40, 2^40), a root per scenario, failure sets of
-    size 0..3 before the operation."""
+    size 0..3 before the operation: all 65536 scenarios against the oracle."""
     P, f, E, S, seed = 1024, 3, 16, 65536, 3
     plan = ft.Plan(P, f, E, ft.I64, ft.SUM)
     fr, fo = w.random_failure_sets(seed, S, P, f, inop_permille=0, rounds_per_attempt=plan.info.rounds_reduce + 1)
@@ -62,25 +71,40 @@ def test_reduce_p1024_f3_65536_scenarios(ft, oracle, w):
     v = ft.validate(plan, 0, S, xd, frd, fod, g["result"], g["status"], root=rd, msgs=g["msgs"])
     torch.cuda.synchronize()
     assert v["n_invalid"] == 0
+    st, res, msgs = g["status"].cpu().numpy(), g["result"].cpu().numpy(), g["msgs"].cpu().numpy()
 
-    idx = _sample(S, 768)
-    x = np.concatenate([w.payload_int(seed, 1, P, E, "i64", 41, scen0=int(s)) for s in idx])
-    sel = torch.from_numpy(idx).cuda()
-    assert np.array_equal(xd[sel].cpu().numpy(), x), "device generator differs from the host generator"
-    o = oracle.reduce_batch(P, f, x, 0, 0, len(idx), root=root[idx], fail_rank=fr[idx], fail_round=fo[idx])
-    st = g["status"].cpu().numpy()[idx]
-    assert np.array_equal(st, o["status"])
-    assert np.array_equal(g["result"][sel].cpu().numpy(), o["result"])
-    assert np.array_equal(g["msgs"].cpu().numpy()[idx], o["msgs"])
+    step, done = 8192, 0
+    for s0 in range(0, S, step):
+        x = _host_payload_int(w, seed, s0, step, P, E, "i64", 41)
+        assert np.array_equal(xd[s0:s0 + step].cpu().numpy(), x), "device generator differs from the host generator"
+        o = oracle.reduce_batch(P, f, x, 0, 0, step, root=root[s0:s0 + step], fail_rank=fr[s0:s0 + step],
+                                fail_round=fo[s0:s0 + step])
+        assert np.array_equal(st[s0:s0 + step], o["status"]), s0
+        assert np.array_equal(res[s0:s0 + step], o["result"]), s0
+        assert np.array_equal(msgs[s0:s0 + step], o["msgs"]), s0
+        done += step
+    assert done == S
     # the root is listed in some scenarios of a batch this large
-    st_all = g["status"].cpu().numpy()
     root_listed = (fr == root[:, None]).any(axis=1)
-    assert root_listed.any() and np.array_equal(st_all != 0, root_listed)
+    assert root_listed.any() and np.array_equal(st != 0, root_listed)
+
+
+def _compare_allreduce_slice(oracle, plan, g, x, fr, fo, s0, n, att):
+    """Scenarios s0 .. s0+n-1 of the batch result g against the oracle on payload x[n][P][E]."""
+    P, f = plan.P, plan.f
+    o = oracle.allreduce_batch(P, f, x, plan.dtype, plan.op, n, fail_rank=fr[s0:s0 + n], fail_round=fo[s0:s0 + n],
+                               want_has=True, want_out=True)
+    assert np.array_equal(g["status"][s0:s0 + n].cpu().numpy(), o["status"]), s0
+    assert np.array_equal(att[s0:s0 + n], o["attempts"]), s0
+    assert_values(g["result"][s0:s0 + n].cpu().numpy(), o["result"], plan.dtype, x, "result of slice %d" % s0)
+    assert np.array_equal(g["msgs"][s0:s0 + n].cpu().numpy(), o["msgs"]), s0
+    assert np.array_equal(unpack_bitmap(g["has_bitmap"][s0:s0 + n].cpu().numpy(), P), o["has"]), s0
+    assert np.array_equal(g["per_process_out"][s0:s0 + n].cpu().numpy(), o["out"]), s0
 
 
 def test_allreduce_p16384_f4_4096_scenarios_f64(ft, oracle, w):
     """Allreduce, P = 16384, f = 4, 8 x fp64 N(0,1), k ~ U(0..4) failures, half of them during the
-    operation at a uniform round."""
+    operation at a uniform round: all 4096 scenarios against the oracle."""
     P, f, E, S, seed = 16384, 4, 8, 4096, 4
     plan = ft.Plan(P, f, E, ft.F64, ft.SUM)
     Ratt = plan.info.rounds_attempt
@@ -94,15 +118,9 @@ def test_allreduce_p16384_f4_4096_scenarios_f64(ft, oracle, w):
     xd = torch.empty((S, P, E), dtype=torch.float64, device="cuda")
     step = 256
     host = np.empty((step, P, E), dtype=np.float64)
-    idx = _sample(S, 40, extra=(100, 200, 300))
-    keep = {}
     for s0 in range(0, S, step):
         w.payload_normal(seed, step, P, E, scen0=s0, threads=16, out=host)
         xd[s0:s0 + step].copy_(torch.from_numpy(host))
-        for s in idx:
-            if s0 <= s < s0 + step:
-                keep[int(s)] = host[s - s0].copy()
-    x = np.stack([keep[int(s)] for s in idx])
     frd, fod = to_dev(fr), to_dev(fo)
     g = ft.run_allreduce(plan, S, xd, frd, fod)
     v = ft.validate(plan, 1, S, xd, frd, fod, g["result"], g["status"], has_bitmap=g["has_bitmap"],
@@ -114,52 +132,65 @@ def test_allreduce_p16384_f4_4096_scenarios_f64(ft, oracle, w):
     assert np.array_equal(att, _expected_attempts(fr, fo, f))
     assert att[100] == 2 and att[200] == 3 and att[300] == 5
 
-    sel = torch.from_numpy(idx).cuda()
-    o = oracle.allreduce_batch(P, f, x, 2, 0, len(idx), fail_rank=fr[idx], fail_round=fo[idx], want_has=True,
-                               want_out=True)
-    assert np.array_equal(g["status"].cpu().numpy()[idx], o["status"])
-    assert np.array_equal(att[idx], o["attempts"])
-    assert_values(g["result"][sel].cpu().numpy(), o["result"], 2, x, "result")
-    assert np.array_equal(g["msgs"].cpu().numpy()[idx], o["msgs"])
-    assert np.array_equal(unpack_bitmap(g["has_bitmap"].cpu().numpy()[idx], P), o["has"])
-    assert np.array_equal(g["per_process_out"][sel].cpu().numpy(), o["out"])
+    done = 0
+    for s0 in range(0, S, step):
+        w.payload_normal(seed, step, P, E, scen0=s0, threads=16, out=host)     # the oracle's input: from the host generator
+        _compare_allreduce_slice(oracle, plan, g, host, fr, fo, s0, step, att)
+        done += step
+    assert done == S
 
 
-def test_allreduce_p2e20_f8_1024_scenarios(ft, oracle, w):
-    """Allreduce, P = 2^20, f = 8, one int64 in [-2^31, 2^31) per process, failure sets of size 0..8,
-    a quarter of the failures during the operation."""
+class _P2e20:
+    """The P = 2^20 batch, run once on the GPU; the oracle takes it a quarter at a time."""
     P, f, E, S, seed = 1 << 20, 8, 1, 1024, 5
-    plan = ft.Plan(P, f, E, ft.I64, ft.SUM)
+    g = None
+
+
+@pytest.fixture(scope="module")
+def p2e20(ft, w):
+    c = _P2e20
+    plan = ft.Plan(c.P, c.f, c.E, ft.I64, ft.SUM)
     Ratt = plan.info.rounds_attempt
-    fr, fo = w.random_failure_sets(seed, S, P, f, inop_permille=250, rounds_per_attempt=Ratt, protected=f + 1)
+    fr, fo = w.random_failure_sets(c.seed, c.S, c.P, c.f, inop_permille=250, rounds_per_attempt=Ratt, protected=c.f + 1)
     fr[10], fo[10] = w.NO_RANK, 0
     fr[10, :2], fo[10, :2] = [0, 1], [0, 0]
     fr[20], fo[20] = w.NO_RANK, 0
-    fr[20, :4], fo[20, :4] = [0, P - 1, 9, 12345], [0, 5, 2 * Ratt - 1, Ratt + 1]
-    xd = ft.gen_payload_int(plan, seed, S, 32)
+    fr[20, :4], fo[20, :4] = [0, c.P - 1, 9, 12345], [0, 5, 2 * Ratt - 1, Ratt + 1]
+    xd = ft.gen_payload_int(plan, c.seed, c.S, 32)
     frd, fod = to_dev(fr), to_dev(fo)
-    g = ft.run_allreduce(plan, S, xd, frd, fod)
-    v = ft.validate(plan, 1, S, xd, frd, fod, g["result"], g["status"], has_bitmap=g["has_bitmap"],
+    g = ft.run_allreduce(plan, c.S, xd, frd, fod)
+    v = ft.validate(plan, 1, c.S, xd, frd, fod, g["result"], g["status"], has_bitmap=g["has_bitmap"],
                     per_process_out=g["per_process_out"], attempts=g["attempts"], msgs=g["msgs"])
     torch.cuda.synchronize()
-    assert v["n_invalid"] == 0
+    yield dict(plan=plan, fr=fr, fo=fo, xd=xd, g=g, n_invalid=v["n_invalid"])
+    del xd, g
+    torch.cuda.empty_cache()
+
+
+def test_allreduce_p2e20_f8_1024_scenarios_whole_batch_properties(p2e20):
+    """Allreduce, P = 2^20, f = 8, one int64 in [-2^31, 2^31) per process, failure sets of size 0..8,
+    a quarter of the failures during the operation: what holds for the batch as a whole."""
+    c, g, fr, fo = _P2e20, p2e20["g"], p2e20["fr"], p2e20["fo"]
+    assert p2e20["n_invalid"] == 0
     assert np.all(g["status"].cpu().numpy() == 0)
     att = g["attempts"].cpu().numpy().astype(np.int64)
-    assert np.array_equal(att, _expected_attempts(fr, fo, f))
+    assert np.array_equal(att, _expected_attempts(fr, fo, c.f))
     assert att[10] == 3 and att[20] == 2
 
-    idx = _sample(S, 6, extra=(10, 20))
-    x = np.concatenate([w.payload_int(seed, 1, P, E, "i64", 32, scen0=int(s)) for s in idx])
-    sel = torch.from_numpy(idx).cuda()
-    assert np.array_equal(xd[sel].cpu().numpy(), x), "device generator differs from the host generator"
-    o = oracle.allreduce_batch(P, f, x, 0, 0, len(idx), fail_rank=fr[idx], fail_round=fo[idx], want_has=True,
-                               want_out=True)
-    assert np.array_equal(g["status"].cpu().numpy()[idx], o["status"])
-    assert np.array_equal(att[idx], o["attempts"])
-    assert np.array_equal(g["result"][sel].cpu().numpy(), o["result"])
-    assert np.array_equal(g["msgs"].cpu().numpy()[idx], o["msgs"])
-    assert np.array_equal(unpack_bitmap(g["has_bitmap"].cpu().numpy()[idx], P), o["has"])
-    assert np.array_equal(g["per_process_out"][sel].cpu().numpy(), o["out"])
+
+@pytest.mark.parametrize("quarter", [0, 1, 2, 3])
+def test_allreduce_p2e20_f8_1024_scenarios_against_the_oracle(p2e20, oracle, w, quarter):
+    """The same batch, every scenario against the oracle (256 scenarios per test, 32 per call of the oracle)."""
+    c, plan, g, fr, fo = _P2e20, p2e20["plan"], p2e20["g"], p2e20["fr"], p2e20["fo"]
+    att = g["attempts"].cpu().numpy().astype(np.int64)
+    step, per = 32, c.S // 4
+    done = 0
+    for s0 in range(quarter * per, (quarter + 1) * per, step):
+        x = _host_payload_int(w, c.seed, s0, step, c.P, c.E, "i64", 32)
+        assert np.array_equal(p2e20["xd"][s0:s0 + step].cpu().numpy(), x), "device generator differs from the host generator"
+        _compare_allreduce_slice(oracle, plan, g, x, fr, fo, s0, step, att)
+        done += step
+    assert done == per
 
 
 def test_allreduce_p2e20_f1_u32_deep_binary_groups(ft, oracle, w):
