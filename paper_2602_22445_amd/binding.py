@@ -169,16 +169,21 @@ def structure(plan, root=0, stream=None):
     return out
 
 
-def run_reduce(plan, S, payload, fail_rank, fail_round, root=None, want_msgs=True, workspace=None, stream=None):
-    """ftred_run_reduce.  Returns dict(result[S][elems], status[S], msgs[S][2] or None)."""
+def run_reduce(plan, S, payload, fail_rank, fail_round, root=None, want_msgs=True, workspace=None, buffers=None,
+               stream=None):
+    """ftred_run_reduce.  Returns dict(result[S][elems], status[S], msgs[S][2] or None).
+    buffers: the dict of an earlier call, to write into the same tensors again."""
     stride = _payload_stride(plan, payload, S)
     _fail(plan, S, fail_rank, fail_round)
     dev = payload.device
     if root is not None:
         assert root.is_cuda and root.dtype == torch.uint32 and tuple(root.shape) == (S,)
-    result = torch.empty((S, plan.elems), dtype=TORCH_DTYPE[plan.dtype], device=dev)
-    status = torch.empty(S, dtype=torch.uint32, device=dev)
-    msgs = torch.empty((S, 2), dtype=torch.uint64, device=dev) if want_msgs else None
+    if buffers is not None:
+        result, status, msgs = buffers["result"], buffers["status"], buffers["msgs"]
+    else:
+        result = torch.empty((S, plan.elems), dtype=TORCH_DTYPE[plan.dtype], device=dev)
+        status = torch.empty(S, dtype=torch.uint32, device=dev)
+        msgs = torch.empty((S, 2), dtype=torch.uint64, device=dev) if want_msgs else None
     ws = workspace if workspace is not None else plan.workspace(S, dev)
     _check(lib().ftred_run_reduce(plan.handle, S, _ptr(root), _ptr(payload), stride, _ptr(fail_rank),
                                   _ptr(fail_round), _ptr(result), _ptr(status), _ptr(msgs), _ptr(ws),
