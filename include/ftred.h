@@ -91,6 +91,9 @@ typedef struct ftred_info {
     uint64_t msgs_tree_ff;       /* failure-free tree messages = P - 1 */
     uint64_t msgs_bcast_tree_ff; /* failure-free broadcast tree messages = P - 1 */
     uint64_t msgs_bcast_corr_ff; /* failure-free broadcast correction messages (= msgs_uc_ff) */
+    uint32_t fused;              /* 1: with deep_kernel 1, one workgroup per scenario folds the deepest tier, the
+                                    levels above it and the root's choice in a single launch */
+    uint32_t reserved;
 } ftred_info_t;
 
 /* Create a plan for P processes, failure bound f, `elems` values of `dtype` per
@@ -103,7 +106,9 @@ typedef struct ftred_info {
    register kernel when the tree is deep enough and f + 1 is one of 2, 3, 4, 5, 9:
    one lane per subtree, or eight lanes per subtree when elems == 1),
    bits 13..15 = 1 + log2 of the groups of subtrees one wavefront of the register
-   kernel walks through.
+   kernel walks through, bit 16 = the deepest tier and the levels above it always in
+   launches of their own (the default folds a whole scenario in one workgroup and
+   one launch where the levels above the deepest tier fit its LDS tile).
    Host call; no device work. */
 int ftred_plan(ftred_plan_t **out, uint32_t P, uint32_t f, uint32_t elems, int dtype, int op, uint32_t flags);
 int ftred_plan_info(const ftred_plan_t *plan, ftred_info_t *info /* host, written */);

@@ -37,7 +37,8 @@ class Info(ctypes.Structure):
                 ("P", "f", "elems", "dtype", "op", "groups_full", "a", "D", "rounds_reduce", "rounds_attempt",
                  "tiers", "deep_kernel")] + \
                [(n, ctypes.c_uint64) for n in
-                ("msgs_uc_ff", "msgs_tree_ff", "msgs_bcast_tree_ff", "msgs_bcast_corr_ff")]
+                ("msgs_uc_ff", "msgs_tree_ff", "msgs_bcast_tree_ff", "msgs_bcast_corr_ff")] + \
+               [("fused", ctypes.c_uint32), ("reserved", ctypes.c_uint32)]
 
 
 class Partners(ctypes.Structure):

@@ -139,7 +139,7 @@ extern "C" int ftred_plan(ftred_plan_t** out, uint32_t P, uint32_t f, uint32_t e
     }
     const bool kwalk_given = ((flags >> 8) & 0xFu) != 0;
     if (kwalk_given) kwalk = ((flags >> 8) & 0xFu) - 1u;
-    if ((flags >> 16) != 0) return fail(FTRED_EINVAL, "ftred_plan: unknown flag bits");
+    if ((flags >> 17) != 0) return fail(FTRED_EINVAL, "ftred_plan: unknown flag bits");
     ftred_plan_t* p = new (std::nothrow) ftred_plan_t;
     if (!p) return fail(FTRED_ENOMEM, "ftred_plan: out of host memory");
     memset(p, 0, sizeof(*p));
@@ -230,6 +230,10 @@ extern "C" int ftred_plan(ftred_plan_t** out, uint32_t P, uint32_t f, uint32_t e
         p->wave_gshift = most - p->wl.group_shift;                // one wavefront per workgroup
         p->wl.stage = (p->wl.group_shift > 0 && wave_can_stage(g, p->wl)) ? 1u : 0u;
         p->use_unit = g.E == 1u ? 1u : 0u;
+        if (!p->use_unit && !(flags & 0x10000u) && !((flags >> 13) & 7u)) {
+            p->fl = make_fused_layout(g, p->tiers[0].dlo);
+            p->use_fused = p->fl.ok;
+        }
         if (p->use_unit) {
             p->ul = make_unit_layout(p->tiers[0].dlo);
             const uint32_t mostu = p->tiers[0].dlo - p->ul.slot_shift;
@@ -273,6 +277,7 @@ extern "C" int ftred_plan_info(const ftred_plan_t* plan, ftred_info_t* info)
     info->rounds_attempt = g.Ratt;
     info->tiers = plan->ntiers;
     info->deep_kernel = plan->use_wave ? (plan->use_unit ? 2u : 1u) : 0u;
+    info->fused = plan->use_fused;
     info->msgs_uc_ff = msgs_uc_ff(g);
     info->msgs_tree_ff = g.P - 1;
     info->msgs_bcast_tree_ff = g.P - 1;
@@ -365,6 +370,13 @@ static hipError_t dispatch_wave_list(const ftred_plan_t* p, const RunArgs& A, ui
     return launch_wave_list_f64_sum(A, p->wl, grid, lds, st);
 }
 
+static hipError_t dispatch_fused(const ftred_plan_t* p, const RunArgs& A, uint32_t grid, uint32_t lds, hipStream_t st)
+{
+    if (p->dtype == FTRED_I64) return p->op == FTRED_SUM ? launch_fused_i64_sum(A, p->fl, grid, lds, st) : launch_fused_i64_bor(A, p->fl, grid, lds, st);
+    if (p->dtype == FTRED_U32) return p->op == FTRED_SUM ? launch_fused_u32_sum(A, p->fl, grid, lds, st) : launch_fused_u32_bor(A, p->fl, grid, lds, st);
+    return launch_fused_f64_sum(A, p->fl, grid, lds, st);
+}
+
 static hipError_t dispatch_wave(const ftred_plan_t* p, const RunArgs& A, uint32_t grid, hipStream_t st)
 {
     if (p->use_unit) {
@@ -393,6 +405,14 @@ static int launch_tiers(const ftred_plan_t* plan, RunArgs& A, uint32_t S, uint32
             A.wfix_cap = uint32_t(wgs << plan->wl.slot_shift);
             hipLaunchKernelGGL(fixlist_kernel, dim3((S + extra + 255u) / 256u), dim3(256), 0, st, A);
             HIP_TRY(hipGetLastError());
+            if (plan->use_fused && !A.info) {
+                // the listed subtrees first: their top rows are in the scratch area when the workgroup that owns
+                // the scenario folds all the others and then everything above them, down to the root's choice
+                const uint32_t lds = (1u << plan->wl.slot_shift) * kWaveRows * uint32_t(sizeof(RowInfo));
+                HIP_TRY(dispatch_wave_list(plan, A, uint32_t(wgs), lds, st));
+                HIP_TRY(dispatch_fused(plan, A, S + extra, fused_lds_bytes(plan->g, plan->tiers[0].dlo), st));
+                return FTRED_OK;
+            }
             HIP_TRY(dispatch_wave(plan, A, (S + extra) << plan->wave_gshift, st));
             if (A.wave_general) {           // every listed subtree is on the register kernel's list
                 const uint32_t lds = (1u << plan->wl.slot_shift) * kWaveRows * uint32_t(sizeof(RowInfo));

@@ -1,6 +1,7 @@
 // Instantiation of the tree-phase kernels for one value type and operator
 // (all compile-time group widths); kept in a file of its own so that the
 // instantiations compile in parallel.
+#include "ftred_fused.h"
 #include "ftred_kernels.h"
 #include "ftred_wave.h"
 #include "ftred_wave_general.h"
@@ -9,6 +10,7 @@
 namespace ftred {
 FTRED_DEFINE_LAUNCHERS(i64_bor, unsigned long long, 1)
 FTRED_DEFINE_WAVE_LAUNCHER(i64_bor, unsigned long long, 1)
+FTRED_DEFINE_FUSED_LAUNCHER(i64_bor, unsigned long long, 1)
 FTRED_DEFINE_WAVE_LIST_LAUNCHER(i64_bor, unsigned long long, 1)
 FTRED_DEFINE_UNIT_LAUNCHER(i64_bor, unsigned long long, 1)
 }  // namespace ftred

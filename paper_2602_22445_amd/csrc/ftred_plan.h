@@ -4,6 +4,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "ftred_fused.h"
 #include "ftred_kernels.h"
 #include "ftred_wave.h"
 #include "ftred_wave_general.h"
@@ -23,6 +24,8 @@ struct ftred_plan_s {
     uint32_t kwalk_given;       // the flags fix the cones a workgroup walks through
     uint32_t use_unit;          // ... with eight lanes per subtree (one value per process)
     ftred::UnitLayout ul;
+    uint32_t use_fused;         // ... and the levels above it and the root's choice in the same launch
+    ftred::FusedLayout fl;
     uint32_t wave_gshift;       // workgroups of the wavefront tier per scenario = 2^wave_gshift
     uint32_t bc_chunk;          // ranks per workgroup in the broadcast kernel
     uint32_t val_chunk;         // ranks per workgroup in the validation kernel (allreduce: inputs and receive buffers)
