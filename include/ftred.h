@@ -108,7 +108,9 @@ typedef struct ftred_info {
    bits 13..15 = 1 + log2 of the groups of subtrees one wavefront of the register
    kernel walks through, bit 16 = the deepest tier and the levels above it always in
    launches of their own (the default folds a whole scenario in one workgroup and
-   one launch where the levels above the deepest tier fit its LDS tile).
+   one launch where the levels above the deepest tier fit its LDS tile),
+   bits 17..19 = 1 + log2(KiB / 4) of the receive buffers one workgroup of the
+   broadcast writes (4 .. 64 KiB).
    Host call; no device work. */
 int ftred_plan(ftred_plan_t **out, uint32_t P, uint32_t f, uint32_t elems, int dtype, int op, uint32_t flags);
 int ftred_plan_info(const ftred_plan_t *plan, ftred_info_t *info /* host, written */);

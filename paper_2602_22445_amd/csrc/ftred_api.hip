@@ -139,7 +139,8 @@ extern "C" int ftred_plan(ftred_plan_t** out, uint32_t P, uint32_t f, uint32_t e
     }
     const bool kwalk_given = ((flags >> 8) & 0xFu) != 0;
     if (kwalk_given) kwalk = ((flags >> 8) & 0xFu) - 1u;
-    if ((flags >> 17) != 0) return fail(FTRED_EINVAL, "ftred_plan: unknown flag bits");
+    if ((flags >> 20) != 0) return fail(FTRED_EINVAL, "ftred_plan: unknown flag bits");
+    if (((flags >> 17) & 7u) > 5u) return fail(FTRED_EINVAL, "ftred_plan: flags bits 17..19 = 1 + log2(KiB / 4) of a broadcast chunk, 1..5");
     ftred_plan_t* p = new (std::nothrow) ftred_plan_t;
     if (!p) return fail(FTRED_ENOMEM, "ftred_plan: out of host memory");
     memset(p, 0, sizeof(*p));
@@ -245,12 +246,16 @@ extern "C" int ftred_plan(ftred_plan_t** out, uint32_t P, uint32_t f, uint32_t e
     p->retry_blocks = 64;
     // broadcast / validation chunks: about 32 KiB of payload, a multiple of 32 ranks
     {
-        uint32_t c = (32u * 1024u) / g.EB;
+        const uint32_t bc_bytes = ((flags >> 17) & 7u) ? (4096u << (((flags >> 17) & 7u) - 1u)) : 32u * 1024u;
+        uint32_t c = bc_bytes / g.EB;
         c = c / 32u * 32u;
         if (c < 32u) c = 32u;
         if (c > 8192u) c = 8192u;
         p->bc_chunk = c;
-        p->val_chunk = c;
+        uint32_t vc = (32u * 1024u) / g.EB / 32u * 32u;
+        if (vc < 32u) vc = 32u;
+        if (vc > 8192u) vc = 8192u;
+        p->val_chunk = vc;
         // the validation of a reduce reads the inputs only: twice the ranks for the same bytes per workgroup
         uint32_t v = (64u * 1024u) / g.EB / 32u * 32u;
         if (v < 32u) v = 32u;

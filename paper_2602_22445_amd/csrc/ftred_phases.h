@@ -250,8 +250,14 @@ __global__ void __launch_bounds__(kThreads) bcast_kernel(BcastArgs B)
     uint32_t* bits = reinterpret_cast<uint32_t*>(smem + sizeof(BcastFail));
     const Geom& g = B.g;
     const uint32_t tid = threadIdx.x;
-    const uint32_t s = fdiv(blockIdx.x, B.div_nchunks);
-    const uint32_t ch = blockIdx.x - s * B.nchunks;
+    // Workgroups are dealt to the eight XCDs in turn (workgroup b runs on XCD b mod 8).  The chunks are numbered
+    // so that each XCD writes one contiguous eighth of the receive buffers: streams of stores that interleave
+    // chunk by chunk over the XCDs reach 5.8 TB/s on this chip, one contiguous region per XCD 6.4 to 7 TB/s.
+    uint32_t bid = blockIdx.x;
+    const uint32_t per_xcd = gridDim.x >> 3;
+    if (bid < (per_xcd << 3)) bid = (bid & 7u) * per_xcd + (bid >> 3);
+    const uint32_t s = fdiv(bid, B.div_nchunks);
+    const uint32_t ch = bid - s * B.nchunks;
     const uint32_t c0 = ch * B.chunk;
     const uint32_t c1 = c0 + B.chunk < g.P ? c0 + B.chunk : g.P;
     const uint32_t nw = (c1 - c0 + 31u) / 32u;

@@ -61,7 +61,7 @@ def test_plan_tiers_and_deepest_kernel(ft, P, f, E, dtype, tiers, kernel):
 def test_plan_rejects_bad_arguments(ft):
     for args in [(2, 1, 1, ft.I64, ft.SUM), (8, 1, 0, ft.I64, ft.SUM), (8, 1, 1, 7, ft.SUM),
                  (8, 1, 1, ft.F64, ft.BOR), (8, 1, 1, ft.I64, 5), (100, 16, 1, ft.I64, ft.SUM),
-                 (8, 1, 1, ft.I64, ft.SUM, 3), (8, 1, 1, ft.I64, ft.SUM, 1 << 17)]:
+                 (8, 1, 1, ft.I64, ft.SUM, 3), (8, 1, 1, ft.I64, ft.SUM, 1 << 20)]:
         with pytest.raises(ft.FtredError) as ei:
             ft.Plan(*args)
         assert ei.value.code in (ft.EINVAL, ft.EUNSUPPORTED)
