@@ -139,7 +139,7 @@ __device__ __forceinline__ uint32_t fused_item(const Geom& g, const FailTab& ft,
 }
 
 template <class T, int OP, int WP>
-__global__ void __launch_bounds__(kFusedMaxWaves * 64) __attribute__((amdgpu_waves_per_eu(3))) fused_tree_kernel(RunArgs A, FusedLayout fl)
+__global__ void __launch_bounds__(kFusedMaxWaves * 64) __attribute__((amdgpu_waves_per_eu(WP <= 5 ? 3 : 2))) fused_tree_kernel(RunArgs A, FusedLayout fl)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     const Geom& g = A.g;
@@ -392,14 +392,7 @@ FTRED_DECLARE_FUSED_LAUNCHER(f64_sum)
     }                                                                                                \
     hipError_t launch_fused_##NAME(const RunArgs& A, const FusedLayout& fl, uint32_t grid, uint32_t lds, hipStream_t st) \
     {                                                                                                \
-        switch (A.g.W) {          /* the widths of wave_width_ok() */                                \
-            case 2: return fused_wp_##NAME<2>(A, fl, grid, lds, st);                                 \
-            case 3: return fused_wp_##NAME<3>(A, fl, grid, lds, st);                                 \
-            case 4: return fused_wp_##NAME<4>(A, fl, grid, lds, st);                                 \
-            case 5: return fused_wp_##NAME<5>(A, fl, grid, lds, st);                                 \
-            case 9: return fused_wp_##NAME<9>(A, fl, grid, lds, st);                                 \
-            default: return hipErrorInvalidValue;                                                    \
-        }                                                                                            \
+        FTRED_WAVE_WIDTH_SWITCH(A.g.W, fused_wp_##NAME, A, fl, grid, lds, st)                       \
     }
 
 }  // namespace ftred

@@ -1,0 +1,12 @@
+// Instantiation of the register kernel for the listed subtrees of the deepest tier
+// for one value type and operator, all compile-time group widths; a file of its
+// own so that the instantiations compile in parallel.
+#include "ftred_fused.h"
+#include "ftred_kernels.h"
+#include "ftred_wave.h"
+#include "ftred_wave_general.h"
+#include "ftred_wave_unit.h"
+
+namespace ftred {
+FTRED_DEFINE_WAVE_LIST_LAUNCHER(i64_bor, unsigned long long, 1)
+}  // namespace ftred

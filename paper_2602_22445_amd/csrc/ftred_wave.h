@@ -63,8 +63,26 @@ inline bool wave_can_stage(const Geom& g, const WaveLayout& w)
     return w.passes == 1u && g.RB % 8u == 0u && (uint64_t(g.RB + 4u) << (w.group_shift + w.slot_shift)) <= 12u * 1024u;
 }
 
-// group widths the kernel is built for (straight-line code per width)
-inline bool wave_width_ok(uint32_t W) { return W == 2 || W == 3 || W == 4 || W == 5 || W == 9; }
+// group widths the register kernels are built for (straight-line code per width): W = f + 1 = 2 .. 9.  A lane of
+// the walk holds (rows in flight + levels + 1) * W values; from W = 10 on that is one wavefront per SIMD, and the
+// walk with failure handling (W * (W - 1) predicated additions per visit, 31 visits) takes minutes to compile
+// per width, value type and operator.  Wider groups use the LDS-tile kernel.
+constexpr uint32_t kWaveMinW = 2, kWaveMaxW = 9;
+inline bool wave_width_ok(uint32_t W) { return W >= kWaveMinW && W <= kWaveMaxW; }
+
+// `return FN<W>(args...)` for the run-time group width W
+#define FTRED_WAVE_WIDTH_SWITCH(W, FN, ...)                     \
+    switch (W) {                                                \
+        case 2: return FN<2>(__VA_ARGS__);                      \
+        case 3: return FN<3>(__VA_ARGS__);                      \
+        case 4: return FN<4>(__VA_ARGS__);                      \
+        case 5: return FN<5>(__VA_ARGS__);                      \
+        case 6: return FN<6>(__VA_ARGS__);                      \
+        case 7: return FN<7>(__VA_ARGS__);                      \
+        case 8: return FN<8>(__VA_ARGS__);                      \
+        case 9: return FN<9>(__VA_ARGS__);                      \
+        default: return hipErrorInvalidValue;                   \
+    }
 
 inline WaveLayout make_wave_layout(const Geom& g, uint32_t dlo)
 {
@@ -445,14 +463,7 @@ FTRED_DECLARE_WAVE_LAUNCHER(f64_sum)
     }                                                                                               \
     hipError_t launch_wave_##NAME(const RunArgs& A, const WaveLayout& wl, uint32_t grid, hipStream_t st) \
     {                                                                                               \
-        switch (A.g.W) {          /* the widths of wave_width_ok() */                               \
-            case 2: return wave_wp_##NAME<2>(A, wl, grid, st);                                      \
-            case 3: return wave_wp_##NAME<3>(A, wl, grid, st);                                      \
-            case 4: return wave_wp_##NAME<4>(A, wl, grid, st);                                      \
-            case 5: return wave_wp_##NAME<5>(A, wl, grid, st);                                      \
-            case 9: return wave_wp_##NAME<9>(A, wl, grid, st);                                      \
-            default: return hipErrorInvalidValue;                                                   \
-        }                                                                                           \
+        FTRED_WAVE_WIDTH_SWITCH(A.g.W, wave_wp_##NAME, A, wl, grid, st)                             \
     }
 
 }  // namespace ftred

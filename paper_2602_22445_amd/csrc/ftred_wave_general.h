@@ -353,14 +353,7 @@ FTRED_DECLARE_WAVE_LIST_LAUNCHER(f64_sum)
     }                                                                                               \
     hipError_t launch_wave_list_##NAME(const RunArgs& A, const WaveLayout& wl, uint32_t grid, uint32_t lds, hipStream_t st) \
     {                                                                                               \
-        switch (A.g.W) {                                                                            \
-            case 2: return wave_list_wp_##NAME<2>(A, wl, grid, lds, st);                            \
-            case 3: return wave_list_wp_##NAME<3>(A, wl, grid, lds, st);                            \
-            case 4: return wave_list_wp_##NAME<4>(A, wl, grid, lds, st);                            \
-            case 5: return wave_list_wp_##NAME<5>(A, wl, grid, lds, st);                            \
-            case 9: return wave_list_wp_##NAME<9>(A, wl, grid, lds, st);                            \
-            default: return hipErrorInvalidValue;                                                   \
-        }                                                                                           \
+        FTRED_WAVE_WIDTH_SWITCH(A.g.W, wave_list_wp_##NAME, A, wl, grid, lds, st)                   \
     }
 
 }  // namespace ftred

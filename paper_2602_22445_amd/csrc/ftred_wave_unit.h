@@ -276,14 +276,7 @@ FTRED_DECLARE_UNIT_LAUNCHER(f64_sum)
     hipError_t launch_unit_##NAME(const RunArgs& A, const UnitLayout& ul, uint32_t grid, hipStream_t st) \
     {                                                                                               \
         if (A.g.E != 1u) return hipErrorInvalidValue;                                               \
-        switch (A.g.W) {          /* the widths of wave_width_ok() */                               \
-            case 2: return unit_wp_##NAME<2>(A, ul, grid, st);                                      \
-            case 3: return unit_wp_##NAME<3>(A, ul, grid, st);                                      \
-            case 4: return unit_wp_##NAME<4>(A, ul, grid, st);                                      \
-            case 5: return unit_wp_##NAME<5>(A, ul, grid, st);                                      \
-            case 9: return unit_wp_##NAME<9>(A, ul, grid, st);                                      \
-            default: return hipErrorInvalidValue;                                                   \
-        }                                                                                           \
+        FTRED_WAVE_WIDTH_SWITCH(A.g.W, unit_wp_##NAME, A, ul, grid, st)                             \
     }
 
 }  // namespace ftred

@@ -163,14 +163,14 @@ ALLREDUCE_CASES = [
 
 
 def test_the_sweeps_reach_both_kernels_of_the_deepest_tier(ft):
-    """Plans of the sweep cases: the register kernels for deep trees with f + 1 in {2,3,4,5,9} (eight lanes per
+    """Plans of the sweep cases: the register kernels for deep trees with f + 1 <= 9 (eight lanes per
     subtree when a process holds one value, one lane otherwise), LDS tiles otherwise; one case walks the value
     indices in two passes (more than 64 of them)."""
     kinds = {(P, f, E, dt): ft.Plan(P, f, E, dt, op).info.deep_kernel for P, f, E, dt, op, _, _ in ALLREDUCE_CASES}
     assert kinds[(3000, 1, 80, 1)] == 1 and kinds[(2000, 2, 4, 1)] == 1 and kinds[(9000, 3, 5, 2)] == 1
     assert kinds[(1000, 8, 1, 0)] == 2 and kinds[(33333, 4, 8, 2)] == 1 and kinds[(1 << 16, 8, 1, 0)] == 2
     assert kinds[(81, 1, 1, 0)] == 2 and kinds[(200, 1, 1, 1)] == 2 and kinds[(5000, 8, 3, 0)] == 1
-    assert kinds[(4099, 5, 3, 2)] == 0 and kinds[(3000, 12, 2, 0)] == 0 and kinds[(64, 2, 8, 1)] == 0
+    assert kinds[(4099, 5, 3, 2)] == 1 and kinds[(3000, 12, 2, 0)] == 0 and kinds[(64, 2, 8, 1)] == 0
     assert {f + 1 for (P, f, E, dt), k in kinds.items() if k == 1} >= {2, 3, 4, 5, 9}
     assert {f + 1 for (P, f, E, dt), k in kinds.items() if k == 2} >= {2, 3, 4, 5, 9}
 
@@ -291,6 +291,28 @@ def test_allreduce_sweep_lds_tile_kernel(ft, oracle, w, P, f, E, dtype, op, S, p
     x = _payload(w, seed, S, P, E, dtype)
     plan = ft.Plan(P, f, E, dtype, op, 0x1000)
     compare_allreduce(ft, oracle, plan, x, fr, fo)
+
+
+def _fused_cases(ft, cases):
+    return [c for c in cases if ft.Plan(c[0], c[1], c[2], c[3], c[4]).info.fused]
+
+
+def test_sweeps_without_the_fused_kernel(ft, oracle, w):
+    """The sweep cases whose default plan folds a whole scenario in one workgroup, with that switched off
+    (flag 0x10000): the register kernel of the deepest tier and the LDS-tile kernels above it in launches of
+    their own, allreduce and reduce with a root per scenario."""
+    cases = _fused_cases(ft, ALLREDUCE_CASES)
+    assert len(cases) >= 8
+    for P, f, E, dtype, op, S, permille in cases:
+        seed = 2000 + P + 31 * f + E
+        Rred, Ratt = _rounds(oracle, P, f)
+        plan = ft.Plan(P, f, E, dtype, op, 0x10000)
+        assert plan.info.fused == 0 and plan.info.deep_kernel == 1
+        x = _payload(w, seed, S, P, E, dtype)
+        fr, fo = w.random_failure_sets(seed, S, P, f, inop_permille=permille, rounds_per_attempt=Ratt, protected=f + 1)
+        compare_allreduce(ft, oracle, plan, x, fr, fo)
+        fr, fo = w.random_failure_sets(seed + 1, S, P, f, inop_permille=permille, rounds_per_attempt=Rred + 1)
+        compare_reduce(ft, oracle, plan, x, fr, fo, root=w.random_roots(seed, S, P))
 
 
 def test_two_streams_with_their_own_workspaces_do_not_disturb_each_other(ft, oracle, w):
