@@ -35,7 +35,9 @@ namespace ftred {
 
 constexpr uint32_t kFusedMaxWaves = 4;
 constexpr int kFusedItems = 4;                       // (row, value index) items of the upper levels per thread
-constexpr uint32_t kFusedTileBytes = 48u * 1024u;    // most LDS for the top rows of one scenario's subtrees
+// most LDS for the top rows of one scenario's subtrees: three workgroups per CU for the narrow groups (three
+// wavefronts per SIMD), two for the wider ones
+inline uint32_t fused_tile_bytes(uint32_t W) { return W <= 5u ? 48u * 1024u : 72u * 1024u; }
 
 struct FusedLayout {
     uint32_t ne, slot_shift, nact;   // lanes of a wavefront = 2^slot_shift sibling subtrees x ne value indices
@@ -55,7 +57,7 @@ inline FusedLayout make_fused_layout(const Geom& g, uint32_t dlo)
     f.wshift = rest - f.group_shift;
     const uint64_t items = ((uint64_t(1) << dlo) - 1u) * g.E;
     f.ok = (w.passes == 1u && (1u << f.wshift) <= kFusedMaxWaves &&
-            (uint64_t(g.RB) << dlo) <= kFusedTileBytes &&
+            (uint64_t(g.RB) << dlo) <= fused_tile_bytes(g.W) &&
             items <= uint64_t(kFusedItems) * 64u * (1u << f.wshift)) ? 1u : 0u;
     return f;
 }
@@ -387,6 +389,11 @@ FTRED_DECLARE_FUSED_LAUNCHER(f64_sum)
     template <int WP>                                                                                \
     static hipError_t fused_wp_##NAME(const RunArgs& A, const FusedLayout& fl, uint32_t grid, uint32_t lds, hipStream_t st) \
     {                                                                                                \
+        if (lds > 48u * 1024u) {      /* more dynamic LDS than a launch gets without asking */               \
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&fused_tree_kernel<T, OP, WP>),   \
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, int(lds));         \
+            if (e != hipSuccess) return e;                                                           \
+        }                                                                                            \
         hipLaunchKernelGGL((fused_tree_kernel<T, OP, WP>), dim3(grid), dim3(64u << fl.wshift), lds, st, A, fl); \
         return hipGetLastError();                                                                    \
     }                                                                                                \

@@ -156,6 +156,8 @@ ALLREDUCE_CASES = [
     # one 4-byte value per process: four receive buffers per store; and a P that rules that path out
     (1004, 2, 1, 1, 0, 64, 500), (1003, 2, 1, 1, 1, 64, 500),
     (5000, 8, 3, 0, 0, 24, 500),
+    # a whole scenario in one workgroup whose top rows take more LDS than a launch gets without asking (64 KiB)
+    (16384, 7, 8, 2, 0, 6, 500),
     # one value per process: eight lanes per subtree, every group width; fewer than eight subtrees in the tier
     (700, 1, 1, 2, 0, 64, 500), (2500, 3, 1, 0, 1, 48, 500), (5003, 4, 1, 2, 0, 48, 500),
     (81, 1, 1, 0, 0, 64, 500), (200, 1, 1, 1, 0, 64, 500),
