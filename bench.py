@@ -213,9 +213,10 @@ def main():
     if args.config == 4 and os.path.exists(tfile) and S == 4096 and args.lds_kib == 0:
         from paper_2602_22445_amd import profile_summary
         per_kernel, sha = profile_summary.read_traffic(tfile)
-        kname = {"tree_deep": "wave_tier_kernel", "bcast": "bcast_kernel", "val_partial": "val_partial_kernel"}[dom]
-        if sha == profile_summary.source_hash() and kname in per_kernel:
-            traffic = per_kernel[kname]
+        knames = {"tree_deep": ("fused_tree_kernel", "wave_tier_kernel"), "bcast": ("bcast_kernel",),
+                  "val_partial": ("val_partial_kernel",)}[dom]
+        if sha == profile_summary.source_hash():
+            traffic = next((per_kernel[k] for k in knames if k in per_kernel), None)
     out = {
         "metric": "simulated process-rounds/sec and HBM GB/s (P=16384, f=4 allreduce), 1 GPU",
         "value": value,
