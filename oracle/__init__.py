@@ -65,15 +65,18 @@ def _fail_arrays(fail_rank, fail_round):
     return fr, fo, fr.size
 
 
-def structure(P: int, f: int, root: int = 0) -> dict:
-    """Tree and group structure (see ``oracle_structure`` in the C file)."""
+BINARY, BINOMIAL = 2, 1        # tree shapes inside a subtree of the root: k >= 2 = k children per process, 1 = binomial
+
+
+def structure(P: int, f: int, root: int = 0, shape: int = BINARY) -> dict:
+    """Tree and group structure (see ``oracle_structure_shape`` in the C file)."""
     lib = _load()
     out = dict(
         parent=np.zeros(P, np.int64), subtree=np.zeros(P, np.uint32), group=np.zeros(P, np.int64),
         gpos=np.zeros(P, np.uint32), gsize=np.zeros(P, np.uint32), height=np.zeros(P, np.uint32),
         depth=np.zeros(P, np.uint32), send_round=np.zeros(P, np.uint32))
     D = ctypes.c_uint32(0)
-    rc = lib.oracle_structure(ctypes.c_uint32(P), ctypes.c_uint32(f), ctypes.c_uint32(root),
+    rc = lib.oracle_structure_shape(ctypes.c_uint32(P), ctypes.c_uint32(f), ctypes.c_uint32(root), ctypes.c_int(shape),
                               _p(out["parent"]), _p(out["subtree"]), _p(out["group"]), _p(out["gpos"]),
                               _p(out["gsize"]), _p(out["height"]), _p(out["depth"]),
                               _p(out["send_round"]), ctypes.byref(D))
@@ -83,8 +86,9 @@ def structure(P: int, f: int, root: int = 0) -> dict:
     return out
 
 
-def reduce(P, f, payload, dtype, op, root=0, fail_rank=(), fail_round=(), disable_uc=False, trace=False):
-    """One reduce; payload[P][elems].  Returns a dict (result, status, msgs, rounds, traces)."""
+def reduce(P, f, payload, dtype, op, root=0, fail_rank=(), fail_round=(), disable_uc=False, trace=False,
+           shape=BINARY):
+    """One reduce; payload[P][elems].  Returns a dict (result, status, msgs, rounds, detected, traces)."""
     lib = _load()
     npdt = _NP_DTYPE[dtype]
     x = np.ascontiguousarray(np.asarray(payload, dtype=npdt).reshape(P, -1))
@@ -98,14 +102,15 @@ def reduce(P, f, payload, dtype, op, root=0, fail_rank=(), fail_round=(), disabl
     sent = np.zeros(P, np.uint8) if trace else None
     flag = np.zeros(P, np.uint8) if trace else None
     tmsg = np.zeros((P, elems), npdt) if trace else None
-    rc = lib.oracle_reduce(ctypes.c_uint32(P), ctypes.c_uint32(f), ctypes.c_uint32(elems),
-                           ctypes.c_int(dtype), ctypes.c_int(op), ctypes.c_int(int(disable_uc)),
-                           ctypes.c_uint32(root), _p(x), ctypes.c_uint32(nfail), _p(fr), _p(fo),
-                           _p(result), ctypes.byref(status), _p(msgs), ctypes.byref(rounds),
-                           _p(v), _p(sent), _p(flag), _p(tmsg))
+    det = ctypes.c_uint32(0)
+    rc = lib.oracle_reduce_shape(ctypes.c_uint32(P), ctypes.c_uint32(f), ctypes.c_uint32(elems),
+                                 ctypes.c_int(dtype), ctypes.c_int(op), ctypes.c_int(int(disable_uc)), ctypes.c_int(shape),
+                                 ctypes.c_uint32(root), _p(x), ctypes.c_uint32(nfail), _p(fr), _p(fo),
+                                 _p(result), ctypes.byref(status), _p(msgs), ctypes.byref(rounds), ctypes.byref(det),
+                                 _p(v), _p(sent), _p(flag), _p(tmsg))
     if rc != 0:
-        raise ValueError("oracle_reduce: invalid arguments")
-    return dict(result=result, status=int(status.value), msgs=msgs, rounds=int(rounds.value),
+        raise ValueError("oracle_reduce_shape: invalid arguments")
+    return dict(result=result, status=int(status.value), msgs=msgs, rounds=int(rounds.value), detected=int(det.value),
                 v_after_uc=v, tree_sent=sent, tree_flag=flag, tree_msg=tmsg)
 
 
@@ -156,26 +161,39 @@ def _batch_common(P, payload, dtype, S, fail_rank, fail_round):
     return npdt, x, elems, stride, fr, fo, nfail
 
 
-def reduce_batch(P, f, payload, dtype, op, S, root=None, fail_rank=(), fail_round=(), threads=0):
-    """S independent reduces; payload[S][P][elems] or [P][elems] (shared)."""
+def latency_steps(P: int, f: int, shape: int = BINARY) -> dict:
+    """Message steps of one failure-free attempt (one port per process): per kind of message the sum over its
+    rounds of the messages the busiest process sends or receives in the round."""
+    lib = _load()
+    st = np.zeros(4, np.uint32)
+    if lib.oracle_latency_steps(ctypes.c_uint32(P), ctypes.c_uint32(f), ctypes.c_int(shape), _p(st)) != 0:
+        raise ValueError("oracle_latency_steps: invalid arguments")
+    return dict(uc=int(st[0]), tree=int(st[1]), bcast_tree=int(st[2]), bcast_corr=int(st[3]))
+
+
+def reduce_batch(P, f, payload, dtype, op, S, root=None, fail_rank=(), fail_round=(), threads=0, shape=BINARY,
+                 want_detected=False):
+    """S independent reduces; payload[S][P][elems] or [P][elems] (shared).  shape: the tree inside a subtree of
+    the root; want_detected: also `detected`[S], bit q = the process in slot q of the failure list was detected."""
     lib = _load()
     npdt, x, elems, stride, fr, fo, nfail = _batch_common(P, payload, dtype, S, fail_rank, fail_round)
     rt = None if root is None else np.ascontiguousarray(np.asarray(root, dtype=np.uint32).reshape(S))
     result = np.zeros((S, elems), npdt)
     status = np.zeros(S, np.uint32)
     msgs = np.zeros((S, 2), np.uint64)
-    used = lib.oracle_reduce_batch(ctypes.c_uint32(P), ctypes.c_uint32(f), ctypes.c_uint32(elems),
-                                   ctypes.c_int(dtype), ctypes.c_int(op), ctypes.c_uint32(S), _p(rt),
-                                   _p(x), ctypes.c_uint64(stride), ctypes.c_uint32(nfail), _p(fr), _p(fo),
-                                   _p(result), _p(status), _p(msgs), ctypes.c_int(threads))
+    det = np.zeros(S, np.uint32) if want_detected else None
+    used = lib.oracle_reduce_shape_batch(ctypes.c_uint32(P), ctypes.c_uint32(f), ctypes.c_uint32(elems),
+                                         ctypes.c_int(dtype), ctypes.c_int(op), ctypes.c_int(shape), ctypes.c_uint32(S),
+                                         _p(rt), _p(x), ctypes.c_uint64(stride), ctypes.c_uint32(nfail), _p(fr), _p(fo),
+                                         _p(result), _p(status), _p(msgs), _p(det), ctypes.c_int(threads))
     if used < 0:
-        raise ValueError("oracle_reduce_batch: invalid arguments")
-    return dict(result=result, status=status, msgs=msgs, threads=used)
+        raise ValueError("oracle_reduce_shape_batch: invalid arguments")
+    return dict(result=result, status=status, msgs=msgs, threads=used, detected=det)
 
 
 def allreduce_batch(P, f, payload, dtype, op, S, fail_rank=(), fail_round=(), threads=0,
-                    want_has=True, want_out=False):
-    """S independent allreduces; payload[S][P][elems] or [P][elems] (shared)."""
+                    want_has=True, want_out=False, shape=BINARY, want_detected=False):
+    """S independent allreduces; payload[S][P][elems] or [P][elems] (shared).  shape, want_detected: as reduce_batch."""
     lib = _load()
     npdt, x, elems, stride, fr, fo, nfail = _batch_common(P, payload, dtype, S, fail_rank, fail_round)
     result = np.zeros((S, elems), npdt)
@@ -185,15 +203,16 @@ def allreduce_batch(P, f, payload, dtype, op, S, fail_rank=(), fail_round=(), th
     msgs = np.zeros((S, 4), np.uint64)
     has = np.zeros((S, P), np.uint8) if want_has else None
     out = np.zeros((S, P, elems), npdt) if want_out else None
-    used = lib.oracle_allreduce_batch(ctypes.c_uint32(P), ctypes.c_uint32(f), ctypes.c_uint32(elems),
-                                      ctypes.c_int(dtype), ctypes.c_int(op), ctypes.c_uint32(S),
-                                      _p(x), ctypes.c_uint64(stride), ctypes.c_uint32(nfail), _p(fr), _p(fo),
-                                      _p(result), _p(status), _p(attempts), _p(msgs), _p(rounds),
-                                      _p(has), _p(out), ctypes.c_int(threads))
+    det = np.zeros(S, np.uint32) if want_detected else None
+    used = lib.oracle_allreduce_shape_batch(ctypes.c_uint32(P), ctypes.c_uint32(f), ctypes.c_uint32(elems),
+                                            ctypes.c_int(dtype), ctypes.c_int(op), ctypes.c_int(shape), ctypes.c_uint32(S),
+                                            _p(x), ctypes.c_uint64(stride), ctypes.c_uint32(nfail), _p(fr), _p(fo),
+                                            _p(result), _p(status), _p(attempts), _p(msgs), _p(rounds),
+                                            _p(has), _p(out), _p(det), ctypes.c_int(threads))
     if used < 0:
-        raise ValueError("oracle_allreduce_batch: invalid arguments")
+        raise ValueError("oracle_allreduce_shape_batch: invalid arguments")
     return dict(result=result, status=status, attempts=attempts, msgs=msgs, rounds=rounds,
-                has=has, out=out, threads=used)
+                has=has, out=out, threads=used, detected=det)
 
 
 def _child_info(child, nfail):

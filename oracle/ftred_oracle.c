@@ -47,7 +47,11 @@
  *      process does everything of rounds < r and nothing from round r on.
  *   R2 up-correction order: in round t (1..f) the member with index i of a group
  *      of size g sends to index (i+t) mod g iff t <= g-1.
- *   R3 tree inside a root subtree: filled breadth-first, two children per node.
+ *   R3 tree inside a root subtree: filled breadth-first, two children per node
+ *      (the default).  The definition of the I(f)-tree fixes only the root's
+ *      f+1 children and the sizes of their subtrees, so other shapes are offered
+ *      (entry points *_shape*): k children per node, filled breadth-first, and
+ *      the binomial tree built by doubling.
  *   R4 a tree process sends in round f + 1 + height(process).
  *   R5 root choice among child messages: lowest child number whose message is
  *      present and reports no failure.
@@ -56,6 +60,15 @@
  *   R7 broadcast (defined in a companion paper, not available): tree-down over
  *      the same tree (D rounds), then f correction rounds in which every holder
  *      sends the value to group mate (i+t) mod g.
+ *
+ *   R8 latency bookkeeping (the paper gives no cost model; section "Up-Correction"
+ *      says a receiver times out on a failed sender and asks the failure
+ *      monitor): a process is DETECTED when a process that is alive finds, in
+ *      the round in which it acts on it, that a message of the failure-free
+ *      schedule has not come, and the monitor (the failure list) says the sender
+ *      has failed.  A round COSTS as many message steps as the busiest process
+ *      sends or receives messages in it in the failure-free run (one port per
+ *      process).  Both are counted literally by the simulation.
  *
  * parity pins: every function of this file is pinned by tests (worked example
  * of the paper, brute force over all failure subsets against the survivor
@@ -122,8 +135,10 @@ typedef struct {
     uint32_t *virt_of_phys;   /* [P] */
     int64_t *parent;          /* [P] virtual parent, -1 for the root */
     uint32_t *nkids;          /* [P] */
-    uint32_t *kids;           /* [P][2] for non-roots */
+    uint32_t *kid_off;        /* [P+1] children of non-root v: kids[kid_off[v] .. kid_off[v] + nkids[v]) in the order they joined */
+    uint32_t *kids;           /* [P] */
     uint32_t *root_kids;      /* [f+1] */
+    int shape;                /* see topo_build */
     uint32_t *subtree;        /* [P] 0 for the root, else 1..f+1 */
     int64_t *group;           /* [P] group id or -1 */
     uint32_t *gpos;           /* [P] index in the group's member list */
@@ -138,23 +153,33 @@ typedef struct {
 static void topo_free(topo_t *t)
 {
     free(t->phys_of_virt); free(t->virt_of_phys); free(t->parent); free(t->nkids);
-    free(t->kids); free(t->root_kids); free(t->subtree); free(t->group); free(t->gpos);
+    free(t->kids); free(t->kid_off); free(t->root_kids); free(t->subtree); free(t->group); free(t->gpos);
     free(t->gsize); free(t->gmembers); free(t->height); free(t->depth);
     memset(t, 0, sizeof(*t));
 }
 
-static int topo_build(topo_t *t, uint32_t P, uint32_t f, uint32_t root)
+/* shape of the tree inside each subtree of the root (the definition of the I(f)-tree leaves it free):
+     k >= 2  k children per process, filled breadth-first: the next process of a subtree becomes a child of the
+             oldest process of that subtree with fewer than k children (k = 2 is the tree of the paper's second
+             tree figure and the default everywhere)
+     1       binomial tree built by doubling: the process that joins a subtree as its j-th (j >= 1, the first
+             one is number 0) becomes a child of the one that joined as number j - 2^floor(log2 j) */
+#define SHAPE_BINOMIAL 1
+#define SHAPE_DEFAULT 2
+
+static int topo_build(topo_t *t, uint32_t P, uint32_t f, uint32_t root, int shape)
 {
-    uint32_t v, k, nsub = f + 1, gcap = f + 2;
-    uint32_t *open_head, *open_tail, *open_next, *sub_count;
+    uint32_t v, k, nsub = f + 1, gcap = f + 2, cap;
+    uint32_t *open_head, *open_tail, *open_next, *sub_count, *joined, *fill;
     memset(t, 0, sizeof(*t));
-    if (P < f + 2 || root >= P) return -1;
-    t->P = P; t->f = f; t->root = root;
+    if (P < f + 2 || root >= P || shape < 1 || shape > 64) return -1;
+    t->P = P; t->f = f; t->root = root; t->shape = shape;
     t->phys_of_virt = malloc(sizeof(uint32_t) * P);
     t->virt_of_phys = malloc(sizeof(uint32_t) * P);
     t->parent = malloc(sizeof(int64_t) * P);
     t->nkids = calloc(P, sizeof(uint32_t));
-    t->kids = calloc((size_t)P * 2, sizeof(uint32_t));
+    t->kid_off = calloc((size_t)P + 1, sizeof(uint32_t));
+    t->kids = calloc((size_t)P, sizeof(uint32_t));
     t->root_kids = calloc(nsub, sizeof(uint32_t));
     t->subtree = calloc(P, sizeof(uint32_t));
     t->group = malloc(sizeof(int64_t) * P);
@@ -172,33 +197,51 @@ static int topo_build(topo_t *t, uint32_t P, uint32_t f, uint32_t root)
     if (root == 0) t->phys_of_virt[0] = 0;
     for (v = 0; v < P; ++v) t->virt_of_phys[t->phys_of_virt[v]] = v;
 
-    /* I(f)-tree: deal 1..P-1 round-robin to f+1 subtrees; inside a subtree the
-       next process becomes a child of the oldest process with a free slot */
-    open_head = malloc(sizeof(uint32_t) * nsub);   /* oldest process with < 2 children */
+    /* I(f)-tree: deal 1..P-1 round-robin to f+1 subtrees; the first process of a subtree is a child of the
+       root, every later one gets its parent inside the subtree by the rule of the shape */
+    cap = (P - 1 + nsub - 1) / nsub;               /* most processes in one subtree */
+    open_head = malloc(sizeof(uint32_t) * nsub);   /* oldest process with a free slot (breadth-first shapes) */
     open_tail = malloc(sizeof(uint32_t) * nsub);
     open_next = calloc(P, sizeof(uint32_t));       /* queue links */
     sub_count = calloc(nsub, sizeof(uint32_t));
+    joined = calloc((size_t)nsub * cap, sizeof(uint32_t));   /* [subtree][number of joining] -> process */
     t->parent[0] = -1;
     t->nkids[0] = 0;
     k = 0;
     for (v = 1; v < P; ++v) {
+        const uint32_t jn = sub_count[k];          /* v joins its subtree as number jn */
         t->subtree[v] = k + 1;
-        if (sub_count[k] == 0) {
+        joined[(size_t)k * cap + jn] = v;
+        if (jn == 0) {
             t->parent[v] = 0;
             t->root_kids[t->nkids[0]++] = v;
             open_head[k] = v;
+        } else if (shape == SHAPE_BINOMIAL) {
+            uint32_t top = 1;
+            while (2 * top <= jn) top *= 2;        /* 2^floor(log2 jn) */
+            t->parent[v] = joined[(size_t)k * cap + (jn - top)];
+            t->nkids[t->parent[v]]++;
         } else {
             uint32_t p = open_head[k];
             t->parent[v] = p;
-            t->kids[2 * (size_t)p + t->nkids[p]++] = v;
-            if (t->nkids[p] == 2) open_head[k] = open_next[p];
+            t->nkids[p]++;
+            if (t->nkids[p] == (uint32_t)shape) open_head[k] = open_next[p];
             open_next[open_tail[k]] = v;
         }
         open_tail[k] = v;
         sub_count[k]++;
         k = (k + 1) % nsub;
     }
-    free(open_head); free(open_tail); free(open_next); free(sub_count);
+    free(open_head); free(open_tail); free(open_next); free(sub_count); free(joined);
+    /* the lists of children, each in the order in which the children joined (ascending numbers) */
+    for (v = 1; v < P; ++v) t->kid_off[v + 1] = t->kid_off[v] + t->nkids[v];
+    fill = calloc(P, sizeof(uint32_t));
+    for (v = 1; v < P; ++v)
+        if (t->parent[v] > 0) {
+            uint32_t p = (uint32_t)t->parent[v];
+            t->kids[t->kid_off[p] + fill[p]++] = v;
+        }
+    free(fill);
 
     /* up-correction groups: consecutive runs of f+1 processes; a short last
        run takes the root as its last member */
@@ -263,6 +306,11 @@ typedef struct {
     /* arena for messages */
     unsigned char *arena; size_t arena_used, arena_cap;
     uint64_t sent[4];
+    /* latency bookkeeping (R8) */
+    uint32_t detected;       /* bit q: the process in slot q of the failure list was detected as failed */
+    int count_steps;         /* count the message steps of every round */
+    uint32_t steps[4];       /* per kind of message: sum over the rounds of the busiest process's messages */
+    uint32_t *port_in, *port_out;   /* [P] scratch of count_steps */
     /* broadcast state */
     unsigned char *has;      /* [P] */
     unsigned char *held;     /* [P][bytes] */
@@ -344,11 +392,33 @@ static void net_send(sim_t *s, int kind, uint32_t src, uint32_t dst, const void 
     s->sent[kind]++;
 }
 
+/* A process that is alive has waited in vain for a message of process u that was due by now: it asks the
+   failure monitor, and if u has failed, u counts as detected (R8). */
+static void monitor_query(sim_t *s, uint32_t u, uint32_t now)
+{
+    uint32_t i;
+    if (alive(s, u, now)) return;
+    for (i = 0; i < s->nfail && i < 32; ++i)
+        if (s->fail_virt[i] == u) s->detected |= 1u << i;
+}
+
 /* end of a round: messages reach the inboxes of processes alive in this round;
    a failed process gives no reaction to a message */
 static void net_deliver(sim_t *s, uint32_t round)
 {
     msg_t *m = s->inflight_head;
+    if (s->count_steps && m) {
+        /* one port per process: the round takes as many message steps as the busiest process sends or receives */
+        uint32_t most = 0;
+        int kind = m->kind;
+        msg_t *q;
+        for (q = m; q; q = q->next) {
+            if (++s->port_out[q->src] > most) most = s->port_out[q->src];
+            if (++s->port_in[q->dst] > most) most = s->port_in[q->dst];
+        }
+        for (q = m; q; q = q->next) s->port_out[q->src] = s->port_in[q->dst] = 0;
+        s->steps[kind] += most;
+    }
     while (m) {
         msg_t *nx = m->next;
         m->next = NULL;
@@ -458,7 +528,7 @@ static int run_reduce(sim_t *s, uint32_t base, void *result)
                 int flag = 0;
                 memcpy(fold, s->data + (size_t)v * s->bytes, s->bytes);
                 for (c = 0; c < t->nkids[v]; ++c) {
-                    msg_t *m = inbox_take(s, v, MSG_TREE, t->kids[2 * (size_t)v + c]);
+                    msg_t *m = inbox_take(s, v, MSG_TREE, t->kids[t->kid_off[v] + c]);
                     if (m) {
                         combine(s->dtype, s->op, s->elems, fold, m->data);
                         if (m->flag) flag = 1;
@@ -469,8 +539,9 @@ static int run_reduce(sim_t *s, uint32_t base, void *result)
                         }
                     } else {
                         flag = 1;    /* no value from this child */
+                        monitor_query(s, t->kids[t->kid_off[v] + c], now);
                         if (s->track_info) {
-                            info_append(s, v, t->kids[2 * (size_t)v + c]);
+                            info_append(s, v, t->kids[t->kid_off[v] + c]);
                             s->fcount[v] += 1;
                         }
                     }
@@ -492,12 +563,16 @@ static int run_reduce(sim_t *s, uint32_t base, void *result)
                     combine(s->dtype, s->op, s->elems, s->data + (size_t)v * s->bytes, m->data);
                     got = 1;
                 }
-                if (s->track_info && !s->disable_uc && t->group[v] >= 0 && !got) {
+                if (!s->disable_uc && t->group[v] >= 0 && !got) {
                     /* the member that sends to v in this round (R2) sent nothing */
                     uint32_t g = (uint32_t)t->group[v], gs = t->gsize[g];
                     if (r <= gs - 1) {
-                        info_append(s, v, t->gmembers[(size_t)g * gcap + (t->gpos[v] + gs - r) % gs]);
-                        s->fcount[v] += 1;
+                        uint32_t mate = t->gmembers[(size_t)g * gcap + (t->gpos[v] + gs - r) % gs];
+                        monitor_query(s, mate, now);
+                        if (s->track_info) {
+                            info_append(s, v, mate);
+                            s->fcount[v] += 1;
+                        }
                     }
                 }
             }
@@ -509,6 +584,8 @@ static int run_reduce(sim_t *s, uint32_t base, void *result)
 
     /* --- the root, at the end of the last round --- */
     if (!alive(s, 0, base + R)) return OR_ST_ROOT_FAILED;
+    for (c = 0; c < t->nkids[0]; ++c)      /* every child's message was due by now */
+        if (!inbox_peek(s, 0, MSG_TREE, t->root_kids[c])) monitor_query(s, t->root_kids[c], base + R);
     if (s->track_info) {
         /* the failure information the root received, child by child */
         for (c = 0; c < t->nkids[0]; ++c) {
@@ -573,7 +650,7 @@ static void run_broadcast(sim_t *s, uint32_t base, const void *value)
                         net_send(s, MSG_BCAST, 0, t->root_kids[c], s->held, 0);
                 } else {
                     for (c = 0; c < t->nkids[v]; ++c)
-                        net_send(s, MSG_BCAST, v, t->kids[2 * (size_t)v + c],
+                        net_send(s, MSG_BCAST, v, t->kids[t->kid_off[v] + c],
                                  s->held + (size_t)v * s->bytes, 0);
                 }
             } else if (t->group[v] >= 0) {
@@ -590,6 +667,19 @@ static void run_broadcast(sim_t *s, uint32_t base, const void *value)
         for (v = 0; v < P; ++v) {
             msg_t *m;
             if (!alive(s, v, now)) continue;
+            /* the message of the failure-free schedule for v in this round: from its parent when the value
+               reaches v's depth, from one group mate in a correction round */
+            if (r <= t->D) {
+                if (v != 0 && t->depth[v] == r && !inbox_peek(s, v, MSG_BCAST, (uint32_t)t->parent[v]))
+                    monitor_query(s, (uint32_t)t->parent[v], now);
+            } else if (t->group[v] >= 0) {
+                uint32_t tt = r - t->D;
+                uint32_t g = (uint32_t)t->group[v], gs = t->gsize[g];
+                if (tt <= gs - 1) {
+                    uint32_t mate = t->gmembers[(size_t)g * gcap + (t->gpos[v] + gs - tt) % gs];
+                    if (!inbox_peek(s, v, MSG_BCORR, mate)) monitor_query(s, mate, now);
+                }
+            }
             while ((m = inbox_take_any(s, v, r <= t->D ? MSG_BCAST : MSG_BCORR)) != NULL) {
                 if (!s->has[v]) {       /* keep the first value */
                     s->has[v] = 1;
@@ -682,6 +772,7 @@ static void sim_free(sim_t *s)
     free(s->trace_v); free(s->trace_sent); free(s->trace_flag); free(s->trace_msg);
     free(s->fl); free(s->fn); free(s->fcount); free(s->sel_ids);
     free(s->ch_state); free(s->ch_count); free(s->ch_nids); free(s->ch_ids);
+    free(s->port_in); free(s->port_out);
     arena_release(s);
 }
 
@@ -692,14 +783,14 @@ static void sim_free(sim_t *s)
    PHYSICAL rank and holding physical ranks.  parent = -1 for the root;
    group = -1 for a process in no group; send_round = round of the tree-phase
    message (0 for the root).  Returns 0, or -1 for invalid arguments. */
-int oracle_structure(uint32_t P, uint32_t f, uint32_t root,
-                     int64_t *parent, uint32_t *subtree, int64_t *group, uint32_t *gpos,
-                     uint32_t *gsize, uint32_t *height, uint32_t *depth,
-                     uint32_t *send_round, uint32_t *D_out)
+int oracle_structure_shape(uint32_t P, uint32_t f, uint32_t root, int shape,
+                           int64_t *parent, uint32_t *subtree, int64_t *group, uint32_t *gpos,
+                           uint32_t *gsize, uint32_t *height, uint32_t *depth,
+                           uint32_t *send_round, uint32_t *D_out)
 {
     topo_t t;
     uint32_t v;
-    if (topo_build(&t, P, f, root) != 0) { topo_free(&t); return -1; }
+    if (topo_build(&t, P, f, root, shape) != 0) { topo_free(&t); return -1; }
     for (v = 0; v < P; ++v) {
         uint32_t p = t.phys_of_virt[v];
         parent[p] = t.parent[v] < 0 ? -1 : (int64_t)t.phys_of_virt[t.parent[v]];
@@ -716,6 +807,15 @@ int oracle_structure(uint32_t P, uint32_t f, uint32_t root,
     return 0;
 }
 
+int oracle_structure(uint32_t P, uint32_t f, uint32_t root,
+                     int64_t *parent, uint32_t *subtree, int64_t *group, uint32_t *gpos,
+                     uint32_t *gsize, uint32_t *height, uint32_t *depth,
+                     uint32_t *send_round, uint32_t *D_out)
+{
+    return oracle_structure_shape(P, f, root, SHAPE_DEFAULT, parent, subtree, group, gpos, gsize, height, depth,
+                                  send_round, D_out);
+}
+
 /* One reduce.  payload[P][elems] by physical rank.  Failure entries with rank
    ORACLE_NO_RANK are unused.  Outputs: result[elems] (valid when *status == OK),
    msgs[2] = {up-correction, tree} messages sent, *rounds = f + D.
@@ -724,7 +824,8 @@ int oracle_structure(uint32_t P, uint32_t f, uint32_t root,
    and tree_msg[P][elems] = whether, with which failed bit and with which value
    each process sent its tree message.  disable_uc != 0 skips the up-correction
    sends (control experiment: the plain tree).  Returns 0, -1 on bad arguments. */
-static int reduce_impl(uint32_t P, uint32_t f, uint32_t elems, int dtype, int op, int disable_uc,
+static int reduce_impl(uint32_t P, uint32_t f, uint32_t elems, int dtype, int op, int disable_uc, int shape,
+                       uint32_t *detected /* bit q = slot q of the failure list was detected as failed; or NULL */,
                        uint32_t root, const void *payload,
                        uint32_t nfail, const uint32_t *fail_rank, const uint32_t *fail_round,
                        void *result, uint32_t *status, uint64_t *msgs, uint32_t *rounds,
@@ -736,8 +837,9 @@ static int reduce_impl(uint32_t P, uint32_t f, uint32_t elems, int dtype, int op
     uint32_t *fv, v;
     int st;
     if (elems == 0 || (dtype == OR_F64 && op != OR_SUM) || dtype < 0 || dtype > 2) return -1;
-    if (topo_build(&t, P, f, root) != 0) { topo_free(&t); return -1; }
+    if (topo_build(&t, P, f, root, shape) != 0) { topo_free(&t); return -1; }
     *rounds = f + t.D;
+    if (detected) *detected = 0;
     msgs[0] = msgs[1] = 0;
     if (info_count) {
         *info_count = *info_nids = 0;
@@ -763,6 +865,7 @@ static int reduce_impl(uint32_t P, uint32_t f, uint32_t elems, int dtype, int op
     *status = (uint32_t)st;
     msgs[0] = s.sent[MSG_UC];
     msgs[1] = s.sent[MSG_TREE];
+    if (detected) *detected = s.detected;
     if (info_count && st == OR_ST_OK) info_report(&s, nfail, info_count, info_nids, info_ids, info_child);
     for (v = 0; v < P; ++v) {
         uint32_t p = t.phys_of_virt[v];
@@ -783,8 +886,22 @@ int oracle_reduce(uint32_t P, uint32_t f, uint32_t elems, int dtype, int op, int
                   void *result, uint32_t *status, uint64_t *msgs, uint32_t *rounds,
                   void *v_after_uc, uint8_t *tree_sent, uint8_t *tree_flag, void *tree_msg)
 {
-    return reduce_impl(P, f, elems, dtype, op, disable_uc, root, payload, nfail, fail_rank, fail_round, result,
-                       status, msgs, rounds, v_after_uc, tree_sent, tree_flag, tree_msg, NULL, NULL, NULL, NULL);
+    return reduce_impl(P, f, elems, dtype, op, disable_uc, SHAPE_DEFAULT, NULL, root, payload, nfail, fail_rank,
+                       fail_round, result, status, msgs, rounds, v_after_uc, tree_sent, tree_flag, tree_msg, NULL, NULL,
+                       NULL, NULL);
+}
+
+/* oracle_reduce for the tree shape `shape` (see topo_build), plus *detected (bit q = the process in slot q of the
+   failure list was detected as failed, R8; may be NULL). */
+int oracle_reduce_shape(uint32_t P, uint32_t f, uint32_t elems, int dtype, int op, int disable_uc, int shape,
+                        uint32_t root, const void *payload,
+                        uint32_t nfail, const uint32_t *fail_rank, const uint32_t *fail_round,
+                        void *result, uint32_t *status, uint64_t *msgs, uint32_t *rounds, uint32_t *detected,
+                        void *v_after_uc, uint8_t *tree_sent, uint8_t *tree_flag, void *tree_msg)
+{
+    return reduce_impl(P, f, elems, dtype, op, disable_uc, shape, detected, root, payload, nfail, fail_rank,
+                       fail_round, result, status, msgs, rounds, v_after_uc, tree_sent, tree_flag, tree_msg, NULL, NULL,
+                       NULL, NULL);
 }
 
 /* One reduce with the first and second failure-information scheme tracked
@@ -804,8 +921,8 @@ int oracle_reduce_info(uint32_t P, uint32_t f, uint32_t elems, int dtype, int op
                        uint32_t *info_count, uint32_t *info_nids, uint32_t *info_ids, uint32_t *info_child)
 {
     if (!info_count || !info_nids || !info_ids) return -1;
-    return reduce_impl(P, f, elems, dtype, op, 0, root, payload, nfail, fail_rank, fail_round, result,
-                       status, msgs, rounds, NULL, NULL, NULL, NULL, info_count, info_nids, info_ids, info_child);
+    return reduce_impl(P, f, elems, dtype, op, 0, SHAPE_DEFAULT, NULL, root, payload, nfail, fail_rank, fail_round,
+                       result, status, msgs, rounds, NULL, NULL, NULL, NULL, info_count, info_nids, info_ids, info_child);
 }
 
 /* One allreduce.  Roots tried: physical ranks 0,1,..,f.  A failure listed for
@@ -816,7 +933,8 @@ int oracle_reduce_info(uint32_t P, uint32_t f, uint32_t elems, int dtype, int op
    out[P][elems] (the value held, zeros where has == 0; may be NULL);
    *attempts; msgs[4] = {up-correction, tree, broadcast tree, broadcast correction}
    summed over all attempts; *rounds = attempts * 2(f+D). */
-static int allreduce_impl(uint32_t P, uint32_t f, uint32_t elems, int dtype, int op,
+static int allreduce_impl(uint32_t P, uint32_t f, uint32_t elems, int dtype, int op, int shape,
+                          uint32_t *detected /* as in reduce_impl, over all attempts; or NULL */,
                           const void *payload,
                           uint32_t nfail, const uint32_t *fail_rank, const uint32_t *fail_round,
                           void *result, uint32_t *status, uint32_t *attempts, uint64_t *msgs,
@@ -835,6 +953,8 @@ static int allreduce_impl(uint32_t P, uint32_t f, uint32_t elems, int dtype, int
     if (out) memset(out, 0, (size_t)P * bytes);
     msgs[0] = msgs[1] = msgs[2] = msgs[3] = 0;
     *attempts = 0; *rounds = 0;
+    if (detected) *detected = 0;
+    if (shape < 1 || shape > 64) return -1;
     if (info_count) {
         *info_count = *info_nids = 0;
         for (i = 0; i < nfail; ++i) info_ids[i] = ORACLE_NO_RANK;
@@ -852,7 +972,7 @@ static int allreduce_impl(uint32_t P, uint32_t f, uint32_t elems, int dtype, int
         sim_t s;
         uint32_t Ra, n_alive = 0, n_ok = 0;
         int rst;
-        topo_build(&t, P, f, a);
+        topo_build(&t, P, f, a, shape);
         Ra = 2 * (f + t.D);
         sim_init(&s, &t, elems, dtype, op, payload, nfail, fail_rank, fail_round, fv);
         if (info_count) sim_track_info(&s);
@@ -864,9 +984,15 @@ static int allreduce_impl(uint32_t P, uint32_t f, uint32_t elems, int dtype, int
             run_broadcast(&s, base + f + t.D, result);
             msgs[2] += s.sent[MSG_BCAST];
             msgs[3] += s.sent[MSG_BCORR];
+        } else if (rst == OR_ST_ROOT_FAILED) {
+            /* the rounds of the broadcast pass all the same: the failed root sends nothing, nobody comes to
+               hold a value, and the root's children wait for its message in vain */
+            run_broadcast(&s, base + f + t.D, result);
+            memset(s.has, 0, P);
         } else {
             memset(s.has, 0, P);
         }
+        if (detected) *detected |= s.detected;
         *rounds = base + Ra;
         /* "ok <- broadcast finished successfully", judged by every process that
            is still alive in the last round of the attempt */
@@ -905,8 +1031,8 @@ int oracle_allreduce(uint32_t P, uint32_t f, uint32_t elems, int dtype, int op,
                      void *result, uint32_t *status, uint32_t *attempts, uint64_t *msgs,
                      uint32_t *rounds, uint8_t *has, void *out)
 {
-    return allreduce_impl(P, f, elems, dtype, op, payload, nfail, fail_rank, fail_round, result, status, attempts,
-                          msgs, rounds, has, out, NULL, NULL, NULL, NULL);
+    return allreduce_impl(P, f, elems, dtype, op, SHAPE_DEFAULT, NULL, payload, nfail, fail_rank, fail_round, result,
+                          status, attempts, msgs, rounds, has, out, NULL, NULL, NULL, NULL);
 }
 
 /* One allreduce with the failure information of oracle_reduce_info, taken from
@@ -919,8 +1045,8 @@ int oracle_allreduce_info(uint32_t P, uint32_t f, uint32_t elems, int dtype, int
                           uint32_t *info_count, uint32_t *info_nids, uint32_t *info_ids, uint32_t *info_child)
 {
     if (!info_count || !info_nids || !info_ids) return -1;
-    return allreduce_impl(P, f, elems, dtype, op, payload, nfail, fail_rank, fail_round, result, status, attempts,
-                          msgs, rounds, has, out, info_count, info_nids, info_ids, info_child);
+    return allreduce_impl(P, f, elems, dtype, op, SHAPE_DEFAULT, NULL, payload, nfail, fail_rank, fail_round, result,
+                          status, attempts, msgs, rounds, has, out, info_count, info_nids, info_ids, info_child);
 }
 
 /* Batches: scenario i uses payload + i*payload_stride_bytes (stride 0 = one
@@ -1055,4 +1181,97 @@ int oracle_allreduce_info_batch(uint32_t P, uint32_t f, uint32_t elems, int dtyp
         }
     }
     return bad ? -1 : used;
+}
+
+/* ------------------------------------------------------------------ */
+/* other tree shapes (R3) and the latency bookkeeping (R8)                */
+
+/* Batches as oracle_reduce_batch / oracle_allreduce_batch for the tree shape `shape` (see topo_build), plus
+   detected[S] (or NULL): bit q of detected[i] = the process in slot q of scenario i's failure list was detected
+   as failed by a process that was alive (over all attempts of an allreduce). */
+int oracle_reduce_shape_batch(uint32_t P, uint32_t f, uint32_t elems, int dtype, int op, int shape,
+                              uint32_t S, const uint32_t *root,
+                              const void *payload, uint64_t payload_stride_bytes,
+                              uint32_t nfail, const uint32_t *fail_rank, const uint32_t *fail_round,
+                              void *result, uint32_t *status, uint64_t *msgs, uint32_t *detected, int threads)
+{
+    int64_t i;
+    int bad = 0, used = 1;
+    size_t bytes = elems * elem_size(dtype);
+#ifdef _OPENMP
+    if (threads > 0) omp_set_num_threads(threads);
+    used = omp_get_max_threads();
+#endif
+#pragma omp parallel for schedule(dynamic, 1)
+    for (i = 0; i < (int64_t)S; ++i) {
+        uint32_t rounds;
+        int rc = reduce_impl(P, f, elems, dtype, op, 0, shape, detected ? detected + i : NULL, root ? root[i] : 0,
+                             (const unsigned char *)payload + (size_t)i * payload_stride_bytes,
+                             nfail, fail_rank + (size_t)i * nfail, fail_round + (size_t)i * nfail,
+                             (unsigned char *)result + (size_t)i * bytes, status + i,
+                             msgs + 2 * (size_t)i, &rounds, NULL, NULL, NULL, NULL, NULL, NULL, NULL, NULL);
+        if (rc != 0) {
+#pragma omp atomic write
+            bad = 1;
+        }
+    }
+    return bad ? -1 : used;
+}
+
+int oracle_allreduce_shape_batch(uint32_t P, uint32_t f, uint32_t elems, int dtype, int op, int shape,
+                                 uint32_t S, const void *payload, uint64_t payload_stride_bytes,
+                                 uint32_t nfail, const uint32_t *fail_rank, const uint32_t *fail_round,
+                                 void *result, uint32_t *status, uint32_t *attempts, uint64_t *msgs,
+                                 uint32_t *rounds, uint8_t *has /* [S][P] or NULL */,
+                                 void *out /* [S][P][elems] or NULL */, uint32_t *detected, int threads)
+{
+    int64_t i;
+    int bad = 0, used = 1;
+    size_t bytes = elems * elem_size(dtype);
+#ifdef _OPENMP
+    if (threads > 0) omp_set_num_threads(threads);
+    used = omp_get_max_threads();
+#endif
+#pragma omp parallel for schedule(dynamic, 1)
+    for (i = 0; i < (int64_t)S; ++i) {
+        uint8_t *h = has ? has + (size_t)i * P : malloc(P);
+        int rc = allreduce_impl(P, f, elems, dtype, op, shape, detected ? detected + i : NULL,
+                                (const unsigned char *)payload + (size_t)i * payload_stride_bytes,
+                                nfail, fail_rank + (size_t)i * nfail, fail_round + (size_t)i * nfail,
+                                (unsigned char *)result + (size_t)i * bytes, status + i,
+                                attempts + i, msgs + 4 * (size_t)i, rounds + i, h,
+                                out ? (unsigned char *)out + (size_t)i * P * bytes : NULL, NULL, NULL, NULL, NULL);
+        if (!has) free(h);
+        if (rc != 0) {
+#pragma omp atomic write
+            bad = 1;
+        }
+    }
+    return bad ? -1 : used;
+}
+
+/* Message steps of one failure-free attempt with root 0 (R8): steps[4] = per kind of message (up-correction,
+   tree, broadcast down the tree, broadcast correction) the sum over its rounds of the number of messages the
+   busiest process sends or receives in the round.  Counted from a failure-free run of the simulation with one
+   value per process.  Returns 0, -1 for invalid arguments. */
+int oracle_latency_steps(uint32_t P, uint32_t f, int shape, uint32_t *steps)
+{
+    topo_t t;
+    sim_t s;
+    uint32_t none = ORACLE_NO_RANK, zero = 0, fv[2];
+    uint64_t *payload, result = 0;
+    int k;
+    if (topo_build(&t, P, f, 0, shape) != 0) { topo_free(&t); return -1; }
+    payload = calloc(P, sizeof(uint64_t));
+    sim_init(&s, &t, 1, OR_I64, OR_SUM, payload, 1, &none, &zero, fv);
+    s.count_steps = 1;
+    s.port_in = calloc(P, sizeof(uint32_t));
+    s.port_out = calloc(P, sizeof(uint32_t));
+    run_reduce(&s, 0, &result);
+    run_broadcast(&s, f + t.D, &result);
+    for (k = 0; k < 4; ++k) steps[k] = s.steps[k];
+    sim_free(&s);
+    free(payload);
+    topo_free(&t);
+    return 0;
 }
