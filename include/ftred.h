@@ -111,6 +111,17 @@ typedef struct ftred_info {
    one launch where the levels above the deepest tier fit its LDS tile),
    bits 17..19 = 1 + log2(KiB / 4) of the receive buffers one workgroup of the
    broadcast writes (4 .. 64 KiB).
+   bits 20..26 = the shape of the tree inside each subtree of the root, which the
+   definition of the I(f)-tree leaves free: 0 or 2 = two children per process,
+   filled breadth-first (the default: the tree of the paper's second tree figure);
+   k = 3..64 = k children per process, filled breadth-first; 1 = the binomial tree
+   built by doubling (the j-th process of a subtree, j >= 1, is a child of process
+   j - 2^floor(log2 j)).  Values under failures before the operation and all
+   message counts of the reduce do not depend on the shape; the number of rounds
+   (ftred_info.D) and what a failure during the operation does do.  Other shapes
+   than the default run on plain kernels (one launch per depth of the tree, a
+   workspace as large as the payload) and do not carry the lists of failed
+   processes (the _info entry points return FTRED_EUNSUPPORTED).
    Host call; no device work. */
 int ftred_plan(ftred_plan_t **out, uint32_t P, uint32_t f, uint32_t elems, int dtype, int op, uint32_t flags);
 int ftred_plan_info(const ftred_plan_t *plan, ftred_info_t *info /* host, written */);
@@ -131,13 +142,13 @@ uint64_t ftred_workspace_bytes(const ftred_plan_t *plan, uint32_t S);
    the replication theorem's proof) and the up-correction group of section
    "Up-Correction", for operation root `root`.  All ranks physical.
    parent = FTRED_NO_RANK for the root; children: up to f+1 entries for the root,
-   two otherwise; group[0..group_size) in group order (empty if the process is in
+   two otherwise (k in a k-ary tree, up to 32 in a binomial tree); group[0..group_size) in group order (empty if the process is in
    no group), group_pos = own index in it; subtree = 0 for the root else 1..f+1;
    send_round = round of the tree message inside one reduce (0 for the root). */
 typedef struct ftred_partners {
     uint32_t parent;
     uint32_t n_children;
-    uint32_t children[FTRED_MAX_F + 1];
+    uint32_t children[32];
     uint32_t group_size, group_pos;
     uint32_t group[FTRED_MAX_F + 1];
     uint32_t subtree, depth, height, send_round;

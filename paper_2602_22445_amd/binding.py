@@ -17,6 +17,7 @@ LIB_PATH = os.path.join(HERE, "libftred.so")
 OK, EINVAL, ENOMEM, EDEVICE, EUNSUPPORTED = range(5)
 I64, U32, F64 = 0, 1, 2
 SUM, BOR = 0, 1
+SHAPE_BINARY, SHAPE_BINOMIAL = 2, 1
 ST_OK, ST_ROOT_FAILED, ST_NO_CLEAN_SUBTREE, ST_BAD_FAILURE_SET = range(4)
 BAD_VALUE, BAD_HOLDER, BAD_STATUS, BAD_COUNT = 1, 2, 4, 8
 NO_RANK = 0xFFFFFFFF
@@ -43,7 +44,7 @@ class Info(ctypes.Structure):
 
 class Partners(ctypes.Structure):
     _fields_ = [("parent", ctypes.c_uint32), ("n_children", ctypes.c_uint32),
-                ("children", ctypes.c_uint32 * (MAX_F + 1)),
+                ("children", ctypes.c_uint32 * 32),
                 ("group_size", ctypes.c_uint32), ("group_pos", ctypes.c_uint32),
                 ("group", ctypes.c_uint32 * (MAX_F + 1)),
                 ("subtree", ctypes.c_uint32), ("depth", ctypes.c_uint32), ("height", ctypes.c_uint32),
@@ -116,7 +117,10 @@ def _stream(stream):
 class Plan:
     """ftred_plan / ftred_plan_info / ftred_plan_destroy."""
 
-    def __init__(self, P, f, elems, dtype, op, flags=0):
+    def __init__(self, P, f, elems, dtype, op, flags=0, shape=0):
+        """shape: the tree inside a subtree of the root: 0 or 2 = binary (default), k = 3..64 children per
+        process, 1 = binomial (flags bits 20..26)."""
+        flags |= shape << 20
         self._h = _vp()
         _check(lib().ftred_plan(ctypes.byref(self._h), P, f, elems, dtype, op, flags))
         self.P, self.f, self.elems, self.dtype, self.op = P, f, elems, dtype, op

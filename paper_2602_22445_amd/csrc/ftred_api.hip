@@ -139,110 +139,129 @@ extern "C" int ftred_plan(ftred_plan_t** out, uint32_t P, uint32_t f, uint32_t e
     }
     const bool kwalk_given = ((flags >> 8) & 0xFu) != 0;
     if (kwalk_given) kwalk = ((flags >> 8) & 0xFu) - 1u;
-    if ((flags >> 20) != 0) return fail(FTRED_EINVAL, "ftred_plan: unknown flag bits");
+    if ((flags >> 27) != 0) return fail(FTRED_EINVAL, "ftred_plan: unknown flag bits");
+    uint32_t shape = (flags >> 20) & 0x7Fu;
+    if (shape == 0) shape = kShapeBinary;
+    if (shape > kShapeMaxArity) return fail(FTRED_EINVAL, "ftred_plan: flags bits 20..26 = tree shape: 0 or 2 binary, 1 binomial, k <= 64 children");
     if (((flags >> 17) & 7u) > 5u) return fail(FTRED_EINVAL, "ftred_plan: flags bits 17..19 = 1 + log2(KiB / 4) of a broadcast chunk, 1..5");
     ftred_plan_t* p = new (std::nothrow) ftred_plan_t;
     if (!p) return fail(FTRED_ENOMEM, "ftred_plan: out of host memory");
     memset(p, 0, sizeof(*p));
-    p->g = make_geom(P, f, elems, esz);
+    p->g = make_geom(P, f, elems, esz, shape);
+    p->retry_scratch = kRetrySlots + 64u;
     p->dtype = dtype;
     p->op = op;
     const Geom& g = p->g;
 
-    // tiers of the tree phase, deepest first.  The deepest tier reads the payload
-    // and wants many workgroups per CU (small tiles); the upper tiers are small.
-    const uint32_t stage_rows = kStageBytes / g.RB;               // rows the prefetch registers hold
-    const uint32_t per_row = g.RB + 4u + 2u * g.W;          // values, meta word, lists
-    uint32_t cap0 = budget / per_row;
-    uint32_t cap1 = (56u * 1024u) / per_row;
-    if (cap0 > stage_rows) cap0 = stage_rows;
-    if (cap1 > 2u * stage_rows + 1u) cap1 = 2u * stage_rows + 1u;
-    if (cap0 < 1 || cap1 < 3) {
-        delete p;
-        return fail(FTRED_EUNSUPPORTED, "ftred_plan: one up-correction group (%u bytes) does not fit the LDS tile", g.RB);
+    if (shape != kShapeBinary) {
+        // the plain per-depth kernels: no tiers; scratch = the root's value, the tree messages of every row, a word per row
+        p->use_shape = 1;
+        p->retry_scratch = 0;
+        p->vroot_off = 0;
+        p->shape_msg_off = align_up(g.EB, 16);
+        p->shape_meta_off = p->shape_msg_off + align_up(g.M * g.RB, 16);
+        p->ws_scen = align_up(p->shape_meta_off + g.M * 4u, 256);
+        if (uint64_t(align_up(g.EB, 16)) + uint64_t(g.M) * g.RB + uint64_t(g.M) * 4u + 512u >= (uint64_t(1) << 32)) {
+            delete p;
+            return fail(FTRED_EUNSUPPORTED, "ftred_plan: the scratch of one scenario must stay below 4 GiB");
+        }
     }
-    const uint32_t hcap0 = ilog2(cap0 + 1u) - 1u;            // 2^(h+1) - 1 <= cap0
-    const uint32_t hcap1 = ilog2(cap1 + 1u) - 2u;            // 2^(h+2) - 1 <= cap1
-    uint32_t nt = 0;
-    // the wavefront kernel leaves some subtrees to the LDS-tile kernel, which must be
-    // able to stage a whole subtree of height kWaveH
-    p->use_wave = (g.L > uint32_t(kWaveH) && !(flags & 0x1000u) && wave_width_ok(g.W) && ((2u << kWaveH) - 1u) <= cap0) ? 1u : 0u;
-    {
-        uint32_t h0 = hcap0 < g.L ? hcap0 : g.L;
-        if (p->use_wave) h0 = uint32_t(kWaveH);
-        TierDesc& t = p->tiers[nt++];
-        t.dlo = g.L - h0; t.dhi = g.L; t.child_in = 0;
-        // the levels above, split evenly over as few tiers as the tile allows: small cones are many workgroups
-        // of few threads, which is what these latency-bound launches want
-        int d = int(t.dlo) - 1;
-        const uint32_t levels = t.dlo, upper = (levels + hcap1) / (hcap1 + 1u);      // tiers above the deepest one
-        const uint32_t per = upper ? (levels + upper - 1u) / upper : 0u;             // levels of each but the top one
-        while (d >= 0) {
-            if (nt == kMaxTiers) {
-                delete p;
-                return fail(FTRED_EUNSUPPORTED, "ftred_plan: the tree needs more than %d tiers at this LDS budget", kMaxTiers);
+    if (!p->use_shape) {
+        // tiers of the tree phase, deepest first.  The deepest tier reads the payload
+        // and wants many workgroups per CU (small tiles); the upper tiers are small.
+        const uint32_t stage_rows = kStageBytes / g.RB;               // rows the prefetch registers hold
+        const uint32_t per_row = g.RB + 4u + 2u * g.W;          // values, meta word, lists
+        uint32_t cap0 = budget / per_row;
+        uint32_t cap1 = (56u * 1024u) / per_row;
+        if (cap0 > stage_rows) cap0 = stage_rows;
+        if (cap1 > 2u * stage_rows + 1u) cap1 = 2u * stage_rows + 1u;
+        if (cap0 < 1 || cap1 < 3) {
+            delete p;
+            return fail(FTRED_EUNSUPPORTED, "ftred_plan: one up-correction group (%u bytes) does not fit the LDS tile", g.RB);
+        }
+        const uint32_t hcap0 = ilog2(cap0 + 1u) - 1u;            // 2^(h+1) - 1 <= cap0
+        const uint32_t hcap1 = ilog2(cap1 + 1u) - 2u;            // 2^(h+2) - 1 <= cap1
+        uint32_t nt = 0;
+        // the wavefront kernel leaves some subtrees to the LDS-tile kernel, which must be
+        // able to stage a whole subtree of height kWaveH
+        p->use_wave = (g.L > uint32_t(kWaveH) && !(flags & 0x1000u) && wave_width_ok(g.W) && ((2u << kWaveH) - 1u) <= cap0) ? 1u : 0u;
+        {
+            uint32_t h0 = hcap0 < g.L ? hcap0 : g.L;
+            if (p->use_wave) h0 = uint32_t(kWaveH);
+            TierDesc& t = p->tiers[nt++];
+            t.dlo = g.L - h0; t.dhi = g.L; t.child_in = 0;
+            // the levels above, split evenly over as few tiers as the tile allows: small cones are many workgroups
+            // of few threads, which is what these latency-bound launches want
+            int d = int(t.dlo) - 1;
+            const uint32_t levels = t.dlo, upper = (levels + hcap1) / (hcap1 + 1u);      // tiers above the deepest one
+            const uint32_t per = upper ? (levels + upper - 1u) / upper : 0u;             // levels of each but the top one
+            while (d >= 0) {
+                if (nt == kMaxTiers) {
+                    delete p;
+                    return fail(FTRED_EUNSUPPORTED, "ftred_plan: the tree needs more than %d tiers at this LDS budget", kMaxTiers);
+                }
+                uint32_t h = per - 1u < uint32_t(d) ? per - 1u : uint32_t(d);
+                TierDesc& u = p->tiers[nt++];
+                u.dlo = uint32_t(d) - h; u.dhi = uint32_t(d); u.child_in = 1;
+                d = int(u.dlo) - 1;
             }
-            uint32_t h = per - 1u < uint32_t(d) ? per - 1u : uint32_t(d);
-            TierDesc& u = p->tiers[nt++];
-            u.dlo = uint32_t(d) - h; u.dhi = uint32_t(d); u.child_in = 1;
-            d = int(u.dlo) - 1;
         }
+        p->ntiers = nt;
+        p->kwalk_given = kwalk_given ? 1u : 0u;
+        uint32_t off = align_up(g.EB, 16);      // [0, EB): the root's value after up-correction
+        p->vroot_off = 0;
+        for (uint32_t t = 0; t < nt; ++t) {
+            TierDesc& td = p->tiers[t];
+            const uint32_t h = td.dhi - td.dlo;
+            td.is_top = td.dlo == 0 ? 1u : 0u;
+            td.lds_rows = ((2u << h) - 1u) + (td.child_in ? (2u << h) : 0u);
+            td.lds_bytes = uint32_t(sizeof(FailTab)) + align_up(td.lds_rows * 4u, 16) + align_up(td.lds_rows * g.RB, 16) +
+                           align_up(td.lds_rows * g.W * 2u, 16);      // failure table, meta words, rows, lists
+            if (td.lds_bytes > p->max_lds) p->max_lds = td.lds_bytes;
+            td.kshift = td.dlo < kwalk ? td.dlo : kwalk;
+            td.gshift = td.dlo - td.kshift;
+            // A small cone is a matter of latency and of instructions every wavefront repeats: no more wavefronts
+            // than its widest level has work for, but enough threads for the prefetch registers to hold its rows.
+            td.threads = uint32_t(kThreads);
+            if (t > 0) {
+                const uint32_t own_bytes = ((2u << h) - 1u) * g.RB, widest = (1u << h) * g.E;
+                uint32_t thr = 64;
+                while (thr < uint32_t(kThreads) && (thr * kStagePerThread < own_bytes || thr < widest)) thr *= 2u;
+                td.threads = thr;
+            }
+            if (t > 0) {
+                td.in_off = p->tiers[t - 1].out_off; td.in_meta_off = p->tiers[t - 1].out_meta_off;
+                td.in_mask_off = p->tiers[t - 1].out_mask_off;
+            }
+            if (!td.is_top) {
+                td.out_off = off;
+                off += align_up((1u << td.dlo) * g.RB, 16);
+                td.out_meta_off = off;
+                off += align_up((1u << td.dlo) * 4u, 16);
+                td.out_mask_off = off;
+                off += align_up((1u << td.dlo) * g.W * 2u, 16);
+            }
+        }
+        if (p->use_wave) {
+            p->wl = make_wave_layout(g, p->tiers[0].dlo);
+            const uint32_t most = p->tiers[0].dlo - p->wl.slot_shift;
+            if ((flags >> 13) & 7u) p->wl.group_shift = ((flags >> 13) & 7u) - 1u < most ? ((flags >> 13) & 7u) - 1u : most;
+            p->wave_gshift = most - p->wl.group_shift;                // one wavefront per workgroup
+            p->wl.stage = (p->wl.group_shift > 0 && wave_can_stage(g, p->wl)) ? 1u : 0u;
+            p->use_unit = g.E == 1u ? 1u : 0u;
+            if (!p->use_unit && !(flags & 0x10000u) && !((flags >> 13) & 7u)) {
+                p->fl = make_fused_layout(g, p->tiers[0].dlo);
+                p->use_fused = p->fl.ok;
+            }
+            if (p->use_unit) {
+                p->ul = make_unit_layout(p->tiers[0].dlo);
+                const uint32_t mostu = p->tiers[0].dlo - p->ul.slot_shift;
+                if ((flags >> 13) & 7u) p->ul.group_shift = ((flags >> 13) & 7u) - 1u < mostu ? ((flags >> 13) & 7u) - 1u : mostu;
+                p->wave_gshift = mostu - p->ul.group_shift;
+            }
+        }
+        p->ws_scen = align_up(off, 256);
     }
-    p->ntiers = nt;
-    p->kwalk_given = kwalk_given ? 1u : 0u;
-    uint32_t off = align_up(g.EB, 16);      // [0, EB): the root's value after up-correction
-    p->vroot_off = 0;
-    for (uint32_t t = 0; t < nt; ++t) {
-        TierDesc& td = p->tiers[t];
-        const uint32_t h = td.dhi - td.dlo;
-        td.is_top = td.dlo == 0 ? 1u : 0u;
-        td.lds_rows = ((2u << h) - 1u) + (td.child_in ? (2u << h) : 0u);
-        td.lds_bytes = uint32_t(sizeof(FailTab)) + align_up(td.lds_rows * 4u, 16) + align_up(td.lds_rows * g.RB, 16) +
-                       align_up(td.lds_rows * g.W * 2u, 16);      // failure table, meta words, rows, lists
-        if (td.lds_bytes > p->max_lds) p->max_lds = td.lds_bytes;
-        td.kshift = td.dlo < kwalk ? td.dlo : kwalk;
-        td.gshift = td.dlo - td.kshift;
-        // A small cone is a matter of latency and of instructions every wavefront repeats: no more wavefronts
-        // than its widest level has work for, but enough threads for the prefetch registers to hold its rows.
-        td.threads = uint32_t(kThreads);
-        if (t > 0) {
-            const uint32_t own_bytes = ((2u << h) - 1u) * g.RB, widest = (1u << h) * g.E;
-            uint32_t thr = 64;
-            while (thr < uint32_t(kThreads) && (thr * kStagePerThread < own_bytes || thr < widest)) thr *= 2u;
-            td.threads = thr;
-        }
-        if (t > 0) {
-            td.in_off = p->tiers[t - 1].out_off; td.in_meta_off = p->tiers[t - 1].out_meta_off;
-            td.in_mask_off = p->tiers[t - 1].out_mask_off;
-        }
-        if (!td.is_top) {
-            td.out_off = off;
-            off += align_up((1u << td.dlo) * g.RB, 16);
-            td.out_meta_off = off;
-            off += align_up((1u << td.dlo) * 4u, 16);
-            td.out_mask_off = off;
-            off += align_up((1u << td.dlo) * g.W * 2u, 16);
-        }
-    }
-    if (p->use_wave) {
-        p->wl = make_wave_layout(g, p->tiers[0].dlo);
-        const uint32_t most = p->tiers[0].dlo - p->wl.slot_shift;
-        if ((flags >> 13) & 7u) p->wl.group_shift = ((flags >> 13) & 7u) - 1u < most ? ((flags >> 13) & 7u) - 1u : most;
-        p->wave_gshift = most - p->wl.group_shift;                // one wavefront per workgroup
-        p->wl.stage = (p->wl.group_shift > 0 && wave_can_stage(g, p->wl)) ? 1u : 0u;
-        p->use_unit = g.E == 1u ? 1u : 0u;
-        if (!p->use_unit && !(flags & 0x10000u) && !((flags >> 13) & 7u)) {
-            p->fl = make_fused_layout(g, p->tiers[0].dlo);
-            p->use_fused = p->fl.ok;
-        }
-        if (p->use_unit) {
-            p->ul = make_unit_layout(p->tiers[0].dlo);
-            const uint32_t mostu = p->tiers[0].dlo - p->ul.slot_shift;
-            if ((flags >> 13) & 7u) p->ul.group_shift = ((flags >> 13) & 7u) - 1u < mostu ? ((flags >> 13) & 7u) - 1u : mostu;
-            p->wave_gshift = mostu - p->ul.group_shift;
-        }
-    }
-    p->ws_scen = align_up(off, 256);
     p->retry_blocks = 64;
     // broadcast / validation chunks: about 32 KiB of payload, a multiple of 32 ranks
     {
@@ -443,6 +462,58 @@ static int launch_tiers(const ftred_plan_t* plan, RunArgs& A, uint32_t S, uint32
     return FTRED_OK;
 }
 
+// The tree phase of the other tree shapes: one launch per depth, deepest first, then the root's choice; the
+// messages of attempts whose root had failed (allreduce) are counted from the failure lists.
+static int launch_shape(const ftred_plan_t* plan, RunArgs& A, uint32_t S, hipStream_t st)
+{
+    const Geom& g = plan->g;
+    TimedLaunch tl(FTRED_PH_TREE_DEEP, st);
+    for (uint32_t d = g.D; d >= 1; --d) {           // the rows of a subtree have depths 1 .. D
+        ShapeLevel lv;
+        memset(&lv, 0, sizeof(lv));
+        lv.depth = d;
+        lv.msg_off = plan->shape_msg_off;
+        lv.meta_off = plan->shape_meta_off;
+        if (g.shape == kShapeBinomial) {
+            // depth = 1 + number of one bits of the position: no range; the first such position is 2^(d-1) - 1
+            lv.j_lo = d > 32u ? g.M : uint32_t((uint64_t(1) << (d - 1u)) - 1u);
+            lv.j_hi = g.M;
+            lv.filter = 1;
+        } else {
+            // level d-1 of a k-ary heap: positions (k^(d-1) - 1) / (k - 1) .. + k^(d-1) - 1
+            uint64_t first = 0, count = 1;
+            for (uint32_t l = 1; l < d && first < g.M; ++l) { first += count; count *= g.shape; }
+            lv.j_lo = first < g.M ? uint32_t(first) : g.M;
+            lv.j_hi = first + count < g.M ? uint32_t(first + count) : g.M;
+        }
+        if (lv.j_lo >= lv.j_hi) continue;
+        const uint64_t items = uint64_t(lv.j_hi - lv.j_lo) * g.E;
+        lv.blocks_per_scen = uint32_t((items + 255u) / 256u);
+        lv.div_bps = make_fastdiv(lv.blocks_per_scen);
+        if (uint64_t(S) * lv.blocks_per_scen >= (uint64_t(1) << 31))
+            return fail(FTRED_EUNSUPPORTED, "this tree shape: S = %u scenarios need too many workgroups; split the batch", S);
+        const uint32_t grid = S * lv.blocks_per_scen;
+        hipError_t e;
+        if (plan->dtype == FTRED_I64) e = plan->op == FTRED_SUM ? launch_shape_level_i64_sum(A, lv, grid, st) : launch_shape_level_i64_bor(A, lv, grid, st);
+        else if (plan->dtype == FTRED_U32) e = plan->op == FTRED_SUM ? launch_shape_level_u32_sum(A, lv, grid, st) : launch_shape_level_u32_bor(A, lv, grid, st);
+        else e = launch_shape_level_f64_sum(A, lv, grid, st);
+        HIP_TRY(e);
+    }
+    hipError_t e;
+    if (plan->dtype == FTRED_I64) e = plan->op == FTRED_SUM ? launch_shape_root_i64_sum(A, plan->shape_msg_off, plan->shape_meta_off, S, st) : launch_shape_root_i64_bor(A, plan->shape_msg_off, plan->shape_meta_off, S, st);
+    else if (plan->dtype == FTRED_U32) e = plan->op == FTRED_SUM ? launch_shape_root_u32_sum(A, plan->shape_msg_off, plan->shape_meta_off, S, st) : launch_shape_root_u32_bor(A, plan->shape_msg_off, plan->shape_meta_off, S, st);
+    else e = launch_shape_root_f64_sum(A, plan->shape_msg_off, plan->shape_meta_off, S, st);
+    HIP_TRY(e);
+    if (A.retry_list && g.f > 0) {
+        // at most f failed attempts per scenario
+        const uint64_t most = uint64_t(S) * g.f;
+        hipLaunchKernelGGL(shape_retry_counts_kernel, dim3(uint32_t((most + 255u) / 256u)), dim3(256), 0, st, A,
+                           (unsigned long long)msgs_uc_ff(g));
+        HIP_TRY(hipGetLastError());
+    }
+    return FTRED_OK;
+}
+
 static hipError_t dispatch_retry(const ftred_plan_t* p, const RunArgs& A, uint32_t grid, uint32_t lds, hipStream_t st)
 {
     if (p->dtype == FTRED_I64) return p->op == FTRED_SUM ? launch_retry_i64_sum(A, grid, lds, st) : launch_retry_i64_bor(A, grid, lds, st);
@@ -535,6 +606,8 @@ static int run_reduce_impl(const char* who, const ftred_plan_t* plan, uint32_t S
         return fail(FTRED_EINVAL, "%s: result must be aligned to the element size", who);
     hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
     const Geom& g = plan->g;
+    if (io.any() && plan->use_shape)
+        return fail(FTRED_EUNSUPPORTED, "%s: the lists of failed processes are carried by the default tree shape only", who);
     if (io.any()) HIP_TRY(clear_info(g, S, io, st));
 
     {
@@ -559,6 +632,7 @@ static int run_reduce_impl(const char* who, const ftred_plan_t* plan, uint32_t S
     A.info_count = io.count;
     A.info_ids = io.ids;
     A.info_child = io.child;
+    if (plan->use_shape) return launch_shape(plan, A, S, st);
     return launch_tiers(plan, A, S, 0, st);
 }
 
@@ -600,6 +674,8 @@ static int run_allreduce_impl(const char* who, const ftred_plan_t* plan, uint32_
         return fail(FTRED_EINVAL, "%s: result and per_process_out must be aligned to the element size", who);
     hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
     const Geom& g = plan->g;
+    if (io.any() && plan->use_shape)
+        return fail(FTRED_EUNSUPPORTED, "%s: the lists of failed processes are carried by the default tree shape only", who);
     if (io.any()) HIP_TRY(clear_info(g, S, io, st));
 
     unsigned char* wsb = static_cast<unsigned char*>(workspace);
@@ -634,11 +710,15 @@ static int run_allreduce_impl(const char* who, const ftred_plan_t* plan, uint32_
 
     // attempts whose root had failed beforehand run as extra "scenarios" of the tier
     // launches; beyond kRetrySlots of them (unusual) the retry kernel takes over
-    if (g.f > 0) {
-        TimedLaunch tl(FTRED_PH_RETRY, st);
-        HIP_TRY(dispatch_retry(plan, A, plan->retry_blocks, plan->max_lds, st));
+    if (plan->use_shape) {
+        rc = launch_shape(plan, A, S, st);
+    } else {
+        if (g.f > 0) {
+            TimedLaunch tl(FTRED_PH_RETRY, st);
+            HIP_TRY(dispatch_retry(plan, A, plan->retry_blocks, plan->max_lds, st));
+        }
+        rc = launch_tiers(plan, A, S, slots, st);
     }
-    rc = launch_tiers(plan, A, S, slots, st);
     if (rc != FTRED_OK) return rc;
     // broadcast down the tree and correction rounds
     BcastArgs B;

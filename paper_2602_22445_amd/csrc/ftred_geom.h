@@ -20,6 +20,13 @@
 //   Inside a subtree the processes form a binary heap on j (children of j are
 //   2j+1 and 2j+2; process j = 0 is the child of the root).  A process sends its
 //   tree message in round f + 1 + height.
+//   The definition of the I(f)-tree leaves the shape inside a subtree free; a plan
+//   can ask for another one (Geom::shape): k >= 3 children per process, filled
+//   breadth-first (children of j are kj+1 .. kj+k), or the binomial tree built by
+//   doubling (the parent of j >= 1 is j without its highest one bit; the children
+//   of j are j + 2^b for every b above j's highest one bit).  The sh_* functions
+//   below work for every shape; the kernels of the default shape use the faster
+//   binary-heap forms.
 #pragma once
 #include <stdint.h>
 
@@ -75,8 +82,11 @@ FT_HD uint32_t ilog2(uint32_t x)          // floor(log2 x), x >= 1
 #endif
 }
 
+constexpr uint32_t kShapeBinomial = 1, kShapeBinary = 2, kShapeMaxArity = 64;
+
 struct Geom {
     uint32_t P, f, W, E;
+    uint32_t shape;      // tree inside a subtree: 2 = binary heap (default), k >= 3 = k-ary heap, 1 = binomial
     uint32_t esz;        // bytes of one value
     uint32_t EB;         // bytes of one process's payload = E * esz
     uint32_t RB;         // bytes of one row = W * EB
@@ -90,10 +100,13 @@ struct Geom {
     FastDiv divW, divE, divRB, divEB;
 };
 
-inline Geom make_geom(uint32_t P, uint32_t f, uint32_t E, uint32_t esz)
+FT_HD uint32_t sh_height_m(uint32_t shape, uint32_t m, uint32_t j);
+
+inline Geom make_geom(uint32_t P, uint32_t f, uint32_t E, uint32_t esz, uint32_t shape = kShapeBinary)
 {
     Geom g;
     g.P = P; g.f = f; g.W = f + 1; g.E = E; g.esz = esz;
+    g.shape = shape;
     g.EB = E * esz;
     g.RB = g.W * g.EB;
     g.M = (P - 1 + g.W - 1) / g.W;
@@ -101,6 +114,7 @@ inline Geom make_geom(uint32_t P, uint32_t f, uint32_t E, uint32_t esz)
     g.nlast = g.a == 1 ? g.W : g.a - 1;
     g.L = ilog2(g.M);
     g.D = g.L + 1;
+    if (shape != kShapeBinary) g.D = 1 + sh_height_m(shape, g.M, 0);     // the largest subtree has M processes
     g.Rred = f + g.D;
     g.Ratt = 2 * g.Rred;
     g.divW = make_fastdiv(g.W);
@@ -144,10 +158,12 @@ FT_HD uint32_t height_of(const Geom& g, uint32_t i, uint32_t j)
     return h;
 }
 
+FT_HD uint32_t sh_height(const Geom& g, uint32_t i, uint32_t j);
+
 // round (1-based, inside one reduce) in which the process sends to its parent
 FT_HD uint32_t tree_send_round(const Geom& g, uint32_t i, uint32_t j)
 {
-    return g.f + 1 + height_of(g, i, j);
+    return g.f + 1 + sh_height(g, i, j);
 }
 
 // depth below the root (children of the root have depth 1)
@@ -161,6 +177,82 @@ FT_HD bool is_proper_ancestor(uint32_t jq, uint32_t j)
 {
     uint32_t dq = ilog2(jq + 1), d = ilog2(j + 1);
     return d > dq && ((j + 1) >> (d - dq)) == jq + 1;
+}
+
+// ---------------------------------------------------------------------------
+// the same questions for any shape of the tree inside a subtree (positions j of a subtree of m processes)
+
+// height of position j: the longest chain of children below it
+FT_HD uint32_t sh_height_m(uint32_t shape, uint32_t m, uint32_t j)
+{
+    uint32_t h = 0;
+    if (shape == kShapeBinomial) {
+        // children add one bits above j's highest one: the longest chain adds the lowest of them one by one,
+        // j + (2^t - 1) 2^b0 must stay below m
+        const uint32_t b0 = j == 0 ? 0u : ilog2(j) + 1u;
+        while (b0 + h < 32u && uint64_t(j) + (((uint64_t(2) << h) - 1u) << b0) <= uint64_t(m) - 1u) ++h;
+        return h;
+    }
+    uint64_t c = j;                          // the first child, the first child of that, ..
+    while (c * shape + 1u < m) { c = c * shape + 1u; ++h; }
+    return h;
+}
+
+FT_HD uint32_t sh_height(const Geom& g, uint32_t i, uint32_t j)
+{
+    return g.shape == kShapeBinary ? height_of(g, i, j) : sh_height_m(g.shape, subtree_size(g, i), j);
+}
+
+// depth below the root (the first process of a subtree has depth 1)
+FT_HD uint32_t sh_depth(const Geom& g, uint32_t j)
+{
+    if (g.shape == kShapeBinary) return depth_of(j);
+    if (g.shape == kShapeBinomial) {
+#if defined(__HIP_DEVICE_COMPILE__)
+        return 1u + uint32_t(__popc(j));
+#else
+        return 1u + uint32_t(__builtin_popcount(j));
+#endif
+    }
+    uint32_t d = 1;
+    uint64_t first = 0, count = 1;           // positions of the current level
+    while (j >= first + count) { first += count; count *= g.shape; ++d; }
+    return d;
+}
+
+// position of the parent of position j >= 1
+FT_HD uint32_t sh_parent(const Geom& g, uint32_t j)
+{
+    if (g.shape == kShapeBinomial) return j - (1u << ilog2(j));
+    return (j - 1u) / g.shape;
+}
+
+// fn(position) for every child of position j in a subtree of m processes, in ascending order
+template <class Fn>
+FT_HD void sh_for_children(const Geom& g, uint32_t m, uint32_t j, Fn fn)
+{
+    if (g.shape == kShapeBinomial) {
+        for (uint32_t b = j == 0 ? 0u : ilog2(j) + 1u; b < 32u; ++b) {
+            const uint64_t c = uint64_t(j) + (uint64_t(1) << b);
+            if (c >= m) break;
+            fn(uint32_t(c));
+        }
+    } else {
+        for (uint32_t k = 1; k <= g.shape; ++k) {
+            const uint64_t c = uint64_t(j) * g.shape + k;
+            if (c >= m) break;
+            fn(uint32_t(c));
+        }
+    }
+}
+
+// is position jq a proper ancestor of position j (same subtree)?  Parents have smaller positions.
+FT_HD bool sh_is_proper_ancestor(const Geom& g, uint32_t jq, uint32_t j)
+{
+    if (g.shape == kShapeBinary) return is_proper_ancestor(jq, j);
+    if (j <= jq) return false;
+    while (j > jq) j = sh_parent(g, j);
+    return j == jq;
 }
 
 // failure-free message counts (theorem on the number of messages)

@@ -3,10 +3,12 @@
 // own so that the instantiations compile in parallel.
 #include "ftred_fused.h"
 #include "ftred_kernels.h"
+#include "ftred_shape.h"
 #include "ftred_wave.h"
 #include "ftred_wave_general.h"
 #include "ftred_wave_unit.h"
 
 namespace ftred {
 FTRED_DEFINE_LAUNCHERS(i64_bor, unsigned long long, 1)
+FTRED_DEFINE_SHAPE_LAUNCHER(i64_bor, unsigned long long, 1)
 }  // namespace ftred

@@ -15,7 +15,7 @@ namespace ftred {
 // partners of one process (physical ranks in, physical ranks out)
 
 struct PartnerInfo {
-    uint32_t parent, n_children, children[16];
+    uint32_t parent, n_children, children[32];      // the root has f+1 children, a process of a binomial tree up to 32
     uint32_t group_id, group_size, group_pos, group[16];
     uint32_t subtree, depth, height, send_round;
 };
@@ -43,14 +43,13 @@ FT_HD void partners_of(const Geom& g, uint32_t root, uint32_t rank, PartnerInfo&
     }
     const uint32_t j = fdiv(v - 1, g.divW);
     const uint32_t i = v - 1 - j * g.W;
-    o.parent = j == 0 ? relabel(0, root) : relabel(1 + ((j - 1) / 2) * g.W + i, root);
-    for (uint32_t c = 0; c < 2; ++c) {
-        uint32_t jc = 2 * j + 1 + c;
-        if (jc < subtree_size(g, i)) o.children[o.n_children++] = relabel(1 + jc * g.W + i, root);
-    }
+    o.parent = j == 0 ? relabel(0, root) : relabel(1 + sh_parent(g, j) * g.W + i, root);
+    sh_for_children(g, subtree_size(g, i), j, [&](uint32_t jc) {
+        if (o.n_children < 32u) o.children[o.n_children++] = relabel(1 + jc * g.W + i, root);
+    });
     o.subtree = i + 1;
-    o.depth = depth_of(j);
-    o.height = height_of(g, i, j);
+    o.depth = sh_depth(g, j);
+    o.height = sh_height(g, i, j);
     o.send_round = g.f + 1 + o.height;
     o.group_id = j;
     const uint32_t nk = row_members(g, j);
@@ -294,7 +293,7 @@ __global__ void __launch_bounds__(kThreads) bcast_kernel(BcastArgs B)
                         uint32_t fr = B.fail_round[size_t(s) * F + tid];
                         row = fdiv(vr - 1, g.divW);
                         idx = vr - 1 - row * g.W;
-                        uint32_t d = depth_of(row);
+                        uint32_t d = sh_depth(g, row);
                         ra = alive_at(fr, t0 + d) ? 1u : 0u;
                         bl = alive_at(fr, t0 + d + 1u) ? 0u : 1u;
                         // alive in correction round t iff t0 + D + t < fr
@@ -314,6 +313,7 @@ __global__ void __launch_bounds__(kThreads) bcast_kernel(BcastArgs B)
             if (used) {
                 const uint32_t j1 = j0 + nrows;            // one past the last row
                 hit = (nrows != 0 && row >= j0 && row < j1) || row == jx;
+                if (bl && g.shape != kShapeBinary) hit = true;       // rows below a position are ranges in the binary heap only
                 if (bl)
                     for (uint32_t k = 1; !hit; ++k) {
                         const uint32_t lo = ((row + 1u) << k) - 1u, hi = ((row + 2u) << k) - 2u;
@@ -358,7 +358,7 @@ __global__ void __launch_bounds__(kThreads) bcast_kernel(BcastArgs B)
                         rowfail = true;
                         if (!bf.recv_alive[q]) H &= ~(1u << bf.idx[q]);
                         if (bf.blocked[q]) blockedm |= 1u << bf.idx[q];
-                    } else if (bf.blocked[q] && bf.idx[q] < nk && is_proper_ancestor(rq, j)) {
+                    } else if (bf.blocked[q] && bf.idx[q] < nk && sh_is_proper_ancestor(g, rq, j)) {
                         H &= ~(1u << bf.idx[q]);   // an ancestor in the same subtree did not forward
                     }
                 }
@@ -366,10 +366,18 @@ __global__ void __launch_bounds__(kThreads) bcast_kernel(BcastArgs B)
             if (owner) {
                 // tree-down messages: a holder alive in its send round sends to each child
                 const uint32_t snd = H & tmask & ~blockedm;
-                const uint32_t jc = 2u * j + 1u;
-                const uint32_t m0 = jc < g.M - 1u ? 0xFFFFu : (jc == g.M - 1u ? (1u << g.nlast) - 1u : 0u);
-                const uint32_t m1 = jc + 1u < g.M - 1u ? 0xFFFFu : (jc + 1u == g.M - 1u ? (1u << g.nlast) - 1u : 0u);
-                my_tree += uint32_t(__popc(snd & m0)) + uint32_t(__popc(snd & m1));
+                if (g.shape == kShapeBinary) {
+                    const uint32_t jc = 2u * j + 1u;
+                    const uint32_t m0 = jc < g.M - 1u ? 0xFFFFu : (jc == g.M - 1u ? (1u << g.nlast) - 1u : 0u);
+                    const uint32_t m1 = jc + 1u < g.M - 1u ? 0xFFFFu : (jc + 1u == g.M - 1u ? (1u << g.nlast) - 1u : 0u);
+                    my_tree += uint32_t(__popc(snd & m0)) + uint32_t(__popc(snd & m1));
+                } else {
+                    // every child row: all members exist but in the last row, which may be short
+                    sh_for_children(g, g.M, j, [&](uint32_t jc) {
+                        const uint32_t mc = jc == g.M - 1u ? (1u << g.nlast) - 1u : 0xFFFFu;
+                        my_tree += uint32_t(__popc(snd & mc));
+                    });
+                }
             }
             // correction rounds; where everybody holds the value and lives, each of them sends in every round
             if (!rowfail && H == full) {

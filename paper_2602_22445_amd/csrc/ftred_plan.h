@@ -6,6 +6,7 @@
 
 #include "ftred_fused.h"
 #include "ftred_kernels.h"
+#include "ftred_shape.h"
 #include "ftred_wave.h"
 #include "ftred_wave_general.h"
 #include "ftred_wave_unit.h"
@@ -27,6 +28,10 @@ struct ftred_plan_s {
     uint32_t use_fused;         // ... and the levels above it and the root's choice in the same launch
     ftred::FusedLayout fl;
     uint32_t wave_gshift;       // workgroups of the wavefront tier per scenario = 2^wave_gshift
+    uint32_t use_shape;         // another tree shape than the binary heap: the plain per-depth kernels (ftred_shape.h)
+    uint32_t shape_msg_off, shape_meta_off;   // their scratch: the tree messages of every row, one word per row
+    uint32_t retry_scratch;     // scratch areas of retry entries (none for the per-depth kernels)
+    uint32_t steps[4];          // message steps of one failure-free attempt (ftred_info)
     uint32_t bc_chunk;          // ranks per workgroup in the broadcast kernel
     uint32_t val_chunk;         // ranks per workgroup in the validation kernel (allreduce: inputs and receive buffers)
     uint32_t val_chunk_reduce;  // the same for a reduce (inputs only); >= val_chunk, so the scratch for val_chunk suffices
@@ -48,7 +53,7 @@ inline uint32_t val_chunks(const ftred_plan_s* p) { return (p->g.P + p->val_chun
 inline uint64_t ws_retry_off(const ftred_plan_s* p, uint32_t S) { return uint64_t(S) * p->ws_scen; }
 inline uint64_t ws_val_off(const ftred_plan_s* p, uint32_t S)
 {
-    return (uint64_t(S) + kRetrySlots + p->retry_blocks) * p->ws_scen;
+    return (uint64_t(S) + p->retry_scratch) * p->ws_scen;
 }
 inline uint64_t ws_val_bytes(const ftred_plan_s* p, uint32_t S)
 {

@@ -35,14 +35,14 @@ def assert_values(got, want, dtype, x, what, exact_fp=True):
         assert np.array_equal(got, want), what
 
 
-def compare_reduce(ft, oracle, plan, x, fr, fo, root=None, threads=0, exact_fp=True):
+def compare_reduce(ft, oracle, plan, x, fr, fo, root=None, threads=0, exact_fp=True, shape=2):
     S = fr.shape[0]
     xd = to_dev(x)
     rd = None if root is None else to_dev(root.astype(np.uint32))
     g = ft.run_reduce(plan, S, xd, to_dev(fr), to_dev(fo), root=rd)
     torch.cuda.synchronize()
     o = oracle.reduce_batch(plan.P, plan.f, x, plan.dtype, plan.op, S, root=root, fail_rank=fr, fail_round=fo,
-                            threads=threads)
+                            threads=threads, shape=shape)
     st = g["status"].cpu().numpy()
     assert np.array_equal(st, o["status"]), "status: %s" % np.nonzero(st != o["status"])[0][:10]
     assert_values(g["result"].cpu().numpy(), o["result"], plan.dtype, x, "result", exact_fp)
@@ -50,13 +50,13 @@ def compare_reduce(ft, oracle, plan, x, fr, fo, root=None, threads=0, exact_fp=T
     return g, o
 
 
-def compare_allreduce(ft, oracle, plan, x, fr, fo, threads=0, exact_fp=True, check_out=True):
+def compare_allreduce(ft, oracle, plan, x, fr, fo, threads=0, exact_fp=True, check_out=True, shape=2):
     S = fr.shape[0]
     xd = to_dev(x)
     g = ft.run_allreduce(plan, S, xd, to_dev(fr), to_dev(fo))
     torch.cuda.synchronize()
     o = oracle.allreduce_batch(plan.P, plan.f, x, plan.dtype, plan.op, S, fail_rank=fr, fail_round=fo,
-                               threads=threads, want_has=True, want_out=check_out)
+                               threads=threads, want_has=True, want_out=check_out, shape=shape)
     st = g["status"].cpu().numpy()
     assert np.array_equal(st, o["status"]), "status: %s" % np.nonzero(st != o["status"])[0][:10]
     assert np.array_equal(g["attempts"].cpu().numpy(), o["attempts"]), "attempts"
