@@ -93,6 +93,12 @@ typedef struct ftred_info {
     uint64_t msgs_bcast_corr_ff; /* failure-free broadcast correction messages (= msgs_uc_ff) */
     uint32_t fused;              /* 1: with deep_kernel 1, one workgroup per scenario folds the deepest tier, the
                                     levels above it and the root's choice in a single launch */
+    uint32_t shape;              /* tree inside a subtree of the root: 2, k, or 1 = binomial (ftred_plan, flags) */
+    /* message steps of one failure-free attempt, one port per process: per kind of message (up-correction, tree,
+       broadcast down the tree, broadcast correction) the sum over its rounds of the number of messages the
+       busiest process sends or receives in the round (see ftred_detect); all 0 for trees of more than 2^22
+       processes per subtree, for which they are not worked out */
+    uint32_t steps_uc, steps_tree, steps_bcast_tree, steps_bcast_corr;
     uint32_t reserved;
 } ftred_info_t;
 
@@ -249,6 +255,25 @@ int ftred_run_allreduce_info(const ftred_plan_t *plan, uint32_t S,
                              uint32_t *status, uint32_t *attempts, uint64_t *msgs,
                              uint32_t *info_count, uint32_t *info_ids, uint32_t *info_child,
                              void *workspace, uint64_t workspace_bytes, void *hip_stream);
+
+/* Latency bookkeeping.  The paper names no cost model; its setting is latency-critical
+   small messages (Introduction), and a receiver that waits for a failed sender times
+   out and asks the failure monitor (section "Up-Correction", last paragraph).  This
+   library's reading: an attempt of S scenarios' operation costs
+       t_message * (steps of the plan, ftred_info.steps_*: a round takes as many message
+                    steps as its busiest process sends or receives messages, failure-free)
+     + t_timeout * (number of DETECTED processes),
+   where a listed process is detected when some process that is alive finds, in the round
+   in which it acts on it, that a message of the failure-free schedule has not come, and
+   the process has indeed failed by then.  ftred_detect works that out from the failure
+   lists alone (kind 0 = reduce with `root` (dev [S] or NULL), 1 = allreduce over all its
+   attempts): detected dev [S], bit q = the process in slot q of the scenario's failure
+   list was detected; 0 for a scenario whose failure set is not valid.  The number of
+   attempts, and with it the total of message steps, is what ftred_run_allreduce returns
+   in `attempts`. */
+int ftred_detect(const ftred_plan_t *plan, int kind, uint32_t S, const uint32_t *root,
+                 const uint32_t *fail_rank, const uint32_t *fail_round,
+                 uint32_t *detected, void *hip_stream);
 
 /* Check results against the semantics (sections "Reduce / Semantics", items 3
    and 4, and "Allreduce / Semantics", items 4 and 5; message-count theorems),

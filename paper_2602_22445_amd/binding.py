@@ -39,7 +39,8 @@ class Info(ctypes.Structure):
                  "tiers", "deep_kernel")] + \
                [(n, ctypes.c_uint64) for n in
                 ("msgs_uc_ff", "msgs_tree_ff", "msgs_bcast_tree_ff", "msgs_bcast_corr_ff")] + \
-               [("fused", ctypes.c_uint32), ("reserved", ctypes.c_uint32)]
+               [(n, ctypes.c_uint32) for n in ("fused", "shape", "steps_uc", "steps_tree", "steps_bcast_tree",
+                                               "steps_bcast_corr", "reserved")]
 
 
 class Partners(ctypes.Structure):
@@ -91,6 +92,7 @@ def lib():
                                                _vp, _vp, _u64, _vp]
         L.ftred_validate.argtypes = [_vp, _int, _u32, _vp, _vp, _u64, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp,
                                      ctypes.POINTER(_u64), _vp, _u64, _vp]
+        L.ftred_detect.argtypes = [_vp, _int, _u32, _vp, _vp, _vp, _vp, _vp]
         L.ftred_gen_failures.argtypes = [_vp, _u64, _u32, _u32, _u32, _u32, _u32, _vp, _vp, _vp, _vp]
         L.ftred_gen_payload_int.argtypes = [_vp, _u64, _u32, _u32, _u32, _vp, _vp]
         L.ftred_timing_begin.argtypes = [_u32]
@@ -299,6 +301,25 @@ def validate(plan, kind, S, payload, fail_rank, fail_round, result, status, root
                                 _ptr(status), _ptr(attempts), _ptr(msgs), _ptr(verdict),
                                 ctypes.byref(n) if count else None, _ptr(ws), ws.numel(), _stream(stream)))
     return dict(verdict=verdict, n_invalid=int(n.value) if count else None)
+
+
+def detect(plan, kind, S, fail_rank, fail_round, root=None, stream=None):
+    """ftred_detect.  Returns detected[S] (bit q = the process in slot q of the failure list was detected)."""
+    _fail(plan, S, fail_rank, fail_round)
+    det = torch.empty(S, dtype=torch.uint32, device=fail_rank.device)
+    _check(lib().ftred_detect(plan.handle, kind, S, _ptr(root), _ptr(fail_rank), _ptr(fail_round), _ptr(det),
+                              _stream(stream)))
+    return det
+
+
+def latency(plan, kind, attempts, detected, t_message=1.0, t_timeout=10.0):
+    """The latency reading of ftred_detect for every scenario (numpy in, numpy out): message steps of the plan times
+    the attempts, plus a time-out per detected process."""
+    import numpy as np
+    i = plan.info
+    steps = i.steps_uc + i.steps_tree + (i.steps_bcast_tree + i.steps_bcast_corr if kind == 1 else 0)
+    ndet = np.array([bin(int(d)).count("1") for d in np.asarray(detected)], dtype=np.int64)
+    return t_message * steps * np.asarray(attempts, dtype=np.int64) + t_timeout * ndet
 
 
 def gen_failures(plan, seed, S, scen0=0, inop_permille=0, rounds_per_attempt=0, protected=0, want_root=False,

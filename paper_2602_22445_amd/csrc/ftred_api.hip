@@ -116,6 +116,46 @@ extern "C" int ftred_timing_end(double* ms, uint64_t* launches)
 // ---------------------------------------------------------------------------
 // plan
 
+// Message steps of one failure-free attempt, one port per process (ftred_info.steps_*): in a round every process
+// sends at most one up-correction, tree or correction message, so what counts is how many tree messages arrive
+// at one process in one round (children of equal height, which send in the same round) and how many children a
+// process forwards the broadcast to.  The two sizes a subtree can have are walked position by position.
+static void plan_steps(ftred_plan_t* p)
+{
+    const Geom& g = p->g;
+    p->steps[0] = p->steps[1] = p->steps[2] = p->steps[3] = 0;
+    if (g.M > (1u << 22)) return;
+    p->steps[0] = p->steps[3] = g.f;                 // one message per process and round; a full group exists
+    uint32_t fan_in[40] = {0}, fan_out[40] = {0}, root_in[40] = {0};     // by round; D <= 33
+    for (uint32_t i = 0; i < g.W; ++i) {
+        const uint32_t hi = sh_height_m(g.shape, subtree_size(g, i), 0);
+        if (++root_in[hi + 1u] > fan_in[hi + 1u]) fan_in[hi + 1u] = root_in[hi + 1u];
+    }
+    fan_out[1] = g.W;                                 // the root forwards to its f+1 children
+    const uint32_t sizes[2] = {g.M, subtree_size(g, g.W - 1u)};
+    for (uint32_t c = 0; c < (sizes[1] != sizes[0] ? 2u : 1u); ++c) {
+        const uint32_t m = sizes[c];
+        for (uint32_t j = 0; j < m; ++j) {
+            uint32_t by_height[40] = {0}, nkids = 0;
+            sh_for_children(g, m, j, [&](uint32_t jc) {
+                ++nkids;
+                const uint32_t r = sh_height_m(g.shape, m, jc) + 1u;       // tree round of this child's message
+                if (++by_height[r] > fan_in[r]) fan_in[r] = by_height[r];
+            });
+            const uint32_t r = sh_depth(g, j) + 1u;                        // broadcast round in which j forwards
+            if (nkids > fan_out[r]) fan_out[r] = nkids;
+            if (nkids == 0) {
+                const uint32_t r0 = sh_height_m(g.shape, m, j) + 1u;       // a sender with no child: one message out
+                if (fan_in[r0] == 0) fan_in[r0] = 1;
+            }
+        }
+    }
+    for (uint32_t r = 1; r <= g.D && r < 40u; ++r) {
+        p->steps[1] += fan_in[r] ? fan_in[r] : 1u;
+        p->steps[2] += fan_out[r] ? fan_out[r] : 1u;
+    }
+}
+
 extern "C" int ftred_plan(ftred_plan_t** out, uint32_t P, uint32_t f, uint32_t elems, int dtype, int op,
                           uint32_t flags)
 {
@@ -281,6 +321,7 @@ extern "C" int ftred_plan(ftred_plan_t** out, uint32_t P, uint32_t f, uint32_t e
         if (v > 8192u) v = 8192u;
         p->val_chunk_reduce = v;
     }
+    plan_steps(p);
     *out = p;
     return FTRED_OK;
 }
@@ -302,6 +343,9 @@ extern "C" int ftred_plan_info(const ftred_plan_t* plan, ftred_info_t* info)
     info->tiers = plan->ntiers;
     info->deep_kernel = plan->use_wave ? (plan->use_unit ? 2u : 1u) : 0u;
     info->fused = plan->use_fused;
+    info->shape = g.shape;
+    info->steps_uc = plan->steps[0]; info->steps_tree = plan->steps[1];
+    info->steps_bcast_tree = plan->steps[2]; info->steps_bcast_corr = plan->steps[3];
     info->msgs_uc_ff = msgs_uc_ff(g);
     info->msgs_tree_ff = g.P - 1;
     info->msgs_bcast_tree_ff = g.P - 1;
@@ -366,6 +410,20 @@ extern "C" int ftred_structure(const ftred_plan_t* plan, uint32_t root, uint32_t
     const uint32_t grid = (plan->g.P + 255u) / 256u;
     hipLaunchKernelGGL(structure_kernel, dim3(grid), dim3(256), 0, st, plan->g, root, parent, subtree, group_id,
                        group_pos, group_size_out, depth, send_round);
+    HIP_TRY(hipGetLastError());
+    return FTRED_OK;
+}
+
+extern "C" int ftred_detect(const ftred_plan_t* plan, int kind, uint32_t S, const uint32_t* root,
+                            const uint32_t* fail_rank, const uint32_t* fail_round, uint32_t* detected, void* hip_stream)
+{
+    if (!plan) return fail(FTRED_EINVAL, "ftred_detect: plan is NULL");
+    if (kind != 0 && kind != 1) return fail(FTRED_EINVAL, "ftred_detect: kind must be 0 (reduce) or 1 (allreduce)");
+    if (S == 0) return fail(FTRED_EINVAL, "ftred_detect: S must be >= 1");
+    if (!fail_rank || !fail_round || !detected) return fail(FTRED_EINVAL, "ftred_detect: fail_rank, fail_round and detected are required");
+    hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
+    hipLaunchKernelGGL(detect_kernel, dim3((S + 255u) / 256u), dim3(256), 0, st, plan->g, uint32_t(kind), S,
+                       kind == 0 ? root : static_cast<const uint32_t*>(nullptr), fail_rank, fail_round, detected);
     HIP_TRY(hipGetLastError());
     return FTRED_OK;
 }

@@ -203,6 +203,109 @@ __global__ void __launch_bounds__(256) fixlist_kernel(RunArgs A)
 }
 
 // ---------------------------------------------------------------------------
+// Which listed processes are DETECTED as failed: a process that is alive waits in vain for a message of the
+// failure-free schedule and the failure monitor confirms that the sender has failed (section "Up-Correction",
+// last paragraph).  Whether a message of a listed process comes depends on liveness alone (a reduce sends
+// whatever it has; in the broadcast a living process that holds no value sends nothing either, but the monitor
+// then answers "alive"), so one thread per scenario walks through the messages each listed process has in the
+// failure-free schedule of every attempt: to the group mates of the up-correction rounds, to its parent (who
+// notices in the round of its own tree message, the root in the last round of the reduce), to its children in
+// the broadcast, to the group mates of the correction rounds.
+
+__device__ __forceinline__ bool listed_alive(const Geom& g, const uint32_t* fr, const uint32_t* fo, uint32_t phys,
+                                             uint32_t now)
+{
+    for (uint32_t q = 0; q < g.f; ++q)
+        if (fr[q] == phys) return alive_at(fo[q], now);
+    return true;
+}
+
+__global__ void __launch_bounds__(256) detect_kernel(Geom g, uint32_t kind /* 0 reduce, 1 allreduce */, uint32_t S,
+                                                     const uint32_t* root_in, const uint32_t* fail_rank,
+                                                     const uint32_t* fail_round, uint32_t* detected)
+{
+    const uint32_t s = blockIdx.x * blockDim.x + threadIdx.x;
+    if (s >= S) return;
+    const uint32_t F = g.f > 0 ? g.f : 1;
+    const uint32_t* fr = fail_rank + size_t(s) * F;
+    const uint32_t* fo = fail_round + size_t(s) * F;
+    // the scenario check of the run (prepass_kernel): a bad failure set is not simulated
+    bool bad = false;
+    uint32_t lead = 0;
+    for (uint32_t q = 0; q < F; ++q) {
+        const uint32_t r = fr[q];
+        if (r == kNoRank) continue;
+        if (q >= g.f || r >= g.P) { bad = true; continue; }
+        for (uint32_t q2 = 0; q2 < q; ++q2) bad = bad || fr[q2] == r;
+        if (kind == 1 && r <= g.f) {
+            if (fo[q] != 0) bad = true; else lead |= 1u << r;
+        }
+    }
+    if (kind == 0 && root_in && root_in[s] >= g.P) bad = true;
+    uint32_t natt = 1;
+    if (kind == 1) while ((lead >> (natt - 1u)) & 1u) ++natt;
+    uint32_t mask = 0;
+    for (uint32_t att = 0; att < natt && !bad; ++att) {
+        const uint32_t root = kind == 1 ? att : (root_in ? root_in[s] : 0u);
+        const uint32_t base = kind == 1 ? att * g.Ratt : 0u;
+        for (uint32_t q = 0; q < g.f; ++q) {
+            if (fr[q] == kNoRank || ((mask >> q) & 1u)) continue;
+            const uint32_t fq = fo[q];
+            const uint32_t vq = relabel(fr[q], root);
+            bool det = false;
+            // its place: position j of subtree i (also member i of group j); the root stands in the last group
+            uint32_t i = 0, j = 0, gs = 0;
+            bool in_group = true;
+            if (vq == 0) {
+                in_group = g.a > 1;
+                j = g.M - 1u; i = g.a - 1u; gs = g.a;
+            } else {
+                j = fdiv(vq - 1u, g.divW);
+                i = vq - 1u - j * g.W;
+                gs = group_size(g, j);
+            }
+            // virtual rank of member r of group j
+            auto member = [&](uint32_t r) { return (j == g.M - 1u && g.a > 1 && r == g.a - 1u) ? 0u : 1u + j * g.W + r; };
+            for (uint32_t phase = 0; phase < (kind == 1 ? 2u : 1u) && in_group; ++phase) {
+                // up-correction rounds 1..f; correction rounds of the broadcast, local rounds Rred + D + 1 ..
+                const uint32_t r0 = phase == 0 ? base : base + g.Rred + g.D;
+                for (uint32_t t = 1; t <= g.f && t + 1u <= gs && !det; ++t) {
+                    const uint32_t now = r0 + t;
+                    if (!alive_at(fq, now) && listed_alive(g, fr, fo, relabel(member((i + t) % gs), root), now)) det = true;
+                }
+            }
+            if (vq != 0 && !det) {
+                // the tree message, due in the round of its height; the parent looks for it when it sends its own
+                const uint32_t sent_round = base + tree_send_round(g, i, j);
+                if (!alive_at(fq, sent_round)) {
+                    uint32_t pv, pnow;
+                    if (j == 0) { pv = 0; pnow = base + g.Rred; }
+                    else { const uint32_t jp = sh_parent(g, j); pv = 1u + jp * g.W + i; pnow = base + tree_send_round(g, i, jp); }
+                    if (listed_alive(g, fr, fo, relabel(pv, root), pnow)) det = true;
+                }
+            }
+            if (kind == 1 && !det) {
+                // broadcast down the tree: its children wait for its message in the round of their depth
+                const uint32_t d = vq == 0 ? 0u : sh_depth(g, j);
+                const uint32_t now = base + g.Rred + d + 1u;
+                if (!alive_at(fq, now)) {
+                    if (vq == 0) {
+                        for (uint32_t k = 0; k < row_members(g, 0) && !det; ++k)
+                            if (listed_alive(g, fr, fo, relabel(1u + k, root), now)) det = true;
+                    } else {
+                        sh_for_children(g, subtree_size(g, i), j, [&](uint32_t jc) {
+                            if (!det && listed_alive(g, fr, fo, relabel(1u + jc * g.W + i, root), now)) det = true;
+                        });
+                    }
+                }
+            }
+            if (det) mask |= 1u << q;
+        }
+    }
+    detected[s] = mask;
+}
+
+// ---------------------------------------------------------------------------
 // broadcast half of the allreduce, for the attempt whose root is alive:
 // rounds 1..D send the value down the tree (a process at depth d receives in
 // round d and forwards in round d+1), rounds D+1..D+f are correction rounds in

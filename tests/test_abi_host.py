@@ -115,6 +115,18 @@ def test_partners_agree_with_the_constructive_structure(ft, oracle, P, f, shape)
                 assert q["group_pos"] == s["gpos"][p]
 
 
+@pytest.mark.parametrize("shape", [2, 3, 4, 8, 1])
+def test_message_steps_agree_with_the_oracles_count(ft, oracle, shape):
+    """ftred_info.steps_* (worked out position by position at plan time) against the oracle, which counts the
+    messages of the busiest process round by round in a failure-free run of its simulation."""
+    for P, f in [(7, 1), (8, 1), (15, 1), (16, 2), (64, 2), (100, 6), (257, 7), (1000, 8), (1024, 3), (16384, 4), (17, 15),
+                 (5, 0), (33, 0), (4099, 5), (3000, 12), (41, 1), (2, 0), (3, 1)]:
+        i = ft.Plan(P, f, 1, ft.I64, ft.SUM, shape=shape).info
+        assert i.shape == shape
+        got = dict(uc=i.steps_uc, tree=i.steps_tree, bcast_tree=i.steps_bcast_tree, bcast_corr=i.steps_bcast_corr)
+        assert got == oracle.latency_steps(P, f, shape), (P, f)
+
+
 def test_partners_of_the_paper_example(ft):
     """n = 7, f = 1 (second tree figure of the paper): 1 -> {3, 5}, 2 -> {4, 6}."""
     plan = ft.Plan(7, 1, 1, ft.I64, ft.SUM)

@@ -75,6 +75,51 @@ def test_other_tree_shapes(ft, oracle, w, P, f, E, dtype, op, S, shape):
     compare_allreduce(ft, oracle, plan, x, fr, fo, shape=shape)
 
 
+@pytest.mark.parametrize("shape", [2, 3, 8, 1])
+@pytest.mark.parametrize("P,f", [(7, 1), (8, 1), (16, 2), (64, 2), (100, 6), (257, 7), (1000, 8), (1024, 3), (4099, 5), (17, 15),
+                                 (5000, 4), (33, 0)])
+def test_detected_processes(ft, oracle, w, P, f, shape):
+    """ftred_detect (which listed processes some living process waits for in vain, worked out from the failure
+    lists) against the oracle, which marks them while it simulates: reduce with a root per scenario and allreduce
+    with its retries, failures at any time."""
+    from _cmp import to_dev
+    S, seed = 200, 12000 + P + 17 * f + shape
+    plan = ft.Plan(P, f, 1, ft.I64, ft.SUM, shape=shape)
+    Rred, Ratt = plan.info.rounds_reduce, plan.info.rounds_attempt
+    x = np.ones((P, 1), dtype=np.int64)                   # one payload for all scenarios: values do not matter here
+
+    fr, fo = w.random_failure_sets(seed, S, P, f, inop_permille=700, rounds_per_attempt=Rred + 2)
+    root = w.random_roots(seed, S, P)
+    root[: S // 4] = 0
+    if f >= 1:
+        fr[1, 0], fo[1, 0] = root[1], 0
+        fr[2, 0], fo[2, 0] = root[2], Rred                # the root fails in the last round
+    o = oracle.reduce_batch(P, f, x, 0, 0, S, root=root, fail_rank=fr, fail_round=fo, shape=shape, want_detected=True)
+    got = ft.detect(plan, 0, S, to_dev(fr), to_dev(fo), root=to_dev(root.astype(np.uint32))).cpu().numpy()
+    bad = np.nonzero(got != o["detected"])[0]
+    assert bad.size == 0, (bad[:5], got[bad[:5]], o["detected"][bad[:5]], fr[bad[:5]], fo[bad[:5]], root[bad[:5]])
+
+    fr, fo = w.random_failure_sets(seed + 1, S, P, f, inop_permille=700, rounds_per_attempt=Ratt, protected=f + 1)
+    if f >= 1:
+        fr[0], fo[0] = w.NO_RANK, 0
+        fr[0, 0], fo[0, 0] = 0, 0
+    if f >= 2:
+        fr[1], fo[1] = w.NO_RANK, 0
+        fr[1, :2], fo[1, :2] = [1, 0], [0, 0]
+        fr[2], fo[2] = w.NO_RANK, 0
+        fr[2, :2], fo[2, :2] = [0, 2], [0, 3]             # a root candidate failing during the operation: not valid
+    o = oracle.allreduce_batch(P, f, x, 0, 0, S, fail_rank=fr, fail_round=fo, shape=shape, want_has=False, want_detected=True)
+    got = ft.detect(plan, 1, S, to_dev(fr), to_dev(fo)).cpu().numpy()
+    bad = np.nonzero(got != o["detected"])[0]
+    assert bad.size == 0, (bad[:5], got[bad[:5]], o["detected"][bad[:5]], fr[bad[:5]], fo[bad[:5]])
+    # the reading as a number: message steps of the plan times the attempts, plus a time-out per detected process
+    lat = ft.latency(plan, 1, o["attempts"], got, t_message=1.0, t_timeout=10.0)
+    i = plan.info
+    per = i.steps_uc + i.steps_tree + i.steps_bcast_tree + i.steps_bcast_corr
+    ok = o["status"] == 0
+    assert np.all(lat[ok] >= per) and lat[ok].max() <= per * (f + 1) + 10.0 * f
+
+
 def test_the_default_shape_by_its_number_is_the_default(ft, oracle, w):
     """Shape 2 asked for explicitly is the default path (register / LDS-tile kernels), not the plain kernels."""
     a, b = ft.Plan(5000, 2, 4, ft.I64, ft.SUM).info, ft.Plan(5000, 2, 4, ft.I64, ft.SUM, shape=2).info
