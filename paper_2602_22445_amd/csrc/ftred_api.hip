@@ -188,12 +188,30 @@ extern "C" int ftred_plan(ftred_plan_t** out, uint32_t P, uint32_t f, uint32_t e
     if (!p) return fail(FTRED_ENOMEM, "ftred_plan: out of host memory");
     memset(p, 0, sizeof(*p));
     p->g = make_geom(P, f, elems, esz, shape);
-    p->retry_scratch = kRetrySlots + 64u;
+    p->retry_scratch = kRetrySlots;
     p->dtype = dtype;
     p->op = op;
     const Geom& g = p->g;
 
-    if (shape != kShapeBinary) {
+    // a row (one up-correction group) must fit the LDS tiles and their prefetch registers; payloads too large for
+    // that (the bandwidth regime: kilobytes per process) run on the plain per-depth kernels, which take one thread
+    // per (row, value index) and have no such limit
+    bool row_too_large = (kStageBytes / g.RB) < 1u || ((56u * 1024u) / (g.RB + 4u + 2u * g.W)) < 3u ||
+                         (budget / (g.RB + 4u + 2u * g.W)) < 1u;
+    if (!row_too_large) {
+        // ... or so few rows fit a tile that the tree would be cut into more tiers than a plan holds
+        const uint32_t stage_rows = kStageBytes / g.RB, per_row = g.RB + 4u + 2u * g.W;
+        uint32_t c0 = budget / per_row, c1 = (56u * 1024u) / per_row;
+        if (c0 > stage_rows) c0 = stage_rows;
+        if (c1 > 2u * stage_rows + 1u) c1 = 2u * stage_rows + 1u;
+        const uint32_t hc0 = ilog2(c0 + 1u) - 1u, hc1 = ilog2(c1 + 1u) - 2u;
+        const bool wave = g.L > uint32_t(kWaveH) && !(flags & 0x1000u) && wave_width_ok(g.W);
+        const uint32_t h0 = wave ? uint32_t(kWaveH) : (hc0 < g.L ? hc0 : g.L);
+        const uint32_t levels = g.L - h0;
+        if (1u + (levels + hc1) / (hc1 + 1u) > uint32_t(kMaxTiers)) row_too_large = true;
+    }
+    bool info_alt = false;
+    if (shape != kShapeBinary || row_too_large) {
         // the plain per-depth kernels: no tiers; scratch = the root's value, the tree messages of every row, a word per row
         p->use_shape = 1;
         p->retry_scratch = 0;
@@ -222,9 +240,11 @@ extern "C" int ftred_plan(ftred_plan_t** out, uint32_t P, uint32_t f, uint32_t e
         const uint32_t hcap0 = ilog2(cap0 + 1u) - 1u;            // 2^(h+1) - 1 <= cap0
         const uint32_t hcap1 = ilog2(cap1 + 1u) - 2u;            // 2^(h+2) - 1 <= cap1
         uint32_t nt = 0;
-        // the wavefront kernel leaves some subtrees to the LDS-tile kernel, which must be
-        // able to stage a whole subtree of height kWaveH
-        p->use_wave = (g.L > uint32_t(kWaveH) && !(flags & 0x1000u) && wave_width_ok(g.W) && ((2u << kWaveH) - 1u) <= cap0) ? 1u : 0u;
+        // When the lists of failed processes are asked for, the listed subtrees of the register tier run on the
+        // LDS-tile list kernel, which must stage a whole subtree of height kWaveH; where it cannot, such runs take
+        // a second plan that is on LDS tiles throughout (p->alt, below).
+        p->use_wave = (g.L > uint32_t(kWaveH) && !(flags & 0x1000u) && wave_width_ok(g.W)) ? 1u : 0u;
+        info_alt = p->use_wave && ((2u << kWaveH) - 1u) > cap0;
         {
             uint32_t h0 = hcap0 < g.L ? hcap0 : g.L;
             if (p->use_wave) h0 = uint32_t(kWaveH);
@@ -302,7 +322,6 @@ extern "C" int ftred_plan(ftred_plan_t** out, uint32_t P, uint32_t f, uint32_t e
         }
         p->ws_scen = align_up(off, 256);
     }
-    p->retry_blocks = 64;
     // broadcast / validation chunks: about 32 KiB of payload, a multiple of 32 ranks
     {
         const uint32_t bc_bytes = ((flags >> 17) & 7u) ? (4096u << (((flags >> 17) & 7u) - 1u)) : 32u * 1024u;
@@ -322,11 +341,19 @@ extern "C" int ftred_plan(ftred_plan_t** out, uint32_t P, uint32_t f, uint32_t e
         p->val_chunk_reduce = v;
     }
     plan_steps(p);
+    if (info_alt) {
+        const int rc = ftred_plan(&p->alt, P, f, elems, dtype, op, (flags & 0xFFFu) | 0x1000u | (flags & ~0x1FFFFu));
+        if (rc != FTRED_OK) { delete p; return rc; }
+    }
     *out = p;
     return FTRED_OK;
 }
 
-extern "C" void ftred_plan_destroy(ftred_plan_t* plan) { delete plan; }
+extern "C" void ftred_plan_destroy(ftred_plan_t* plan)
+{
+    if (plan) delete plan->alt;
+    delete plan;
+}
 
 extern "C" int ftred_plan_info(const ftred_plan_t* plan, ftred_info_t* info)
 {
@@ -565,18 +592,11 @@ static int launch_shape(const ftred_plan_t* plan, RunArgs& A, uint32_t S, hipStr
     if (A.retry_list && g.f > 0) {
         // at most f failed attempts per scenario
         const uint64_t most = uint64_t(S) * g.f;
-        hipLaunchKernelGGL(shape_retry_counts_kernel, dim3(uint32_t((most + 255u) / 256u)), dim3(256), 0, st, A,
-                           (unsigned long long)msgs_uc_ff(g));
+        hipLaunchKernelGGL(retry_counts_kernel, dim3(uint32_t((most + 255u) / 256u)), dim3(256), 0, st, A,
+                           (unsigned long long)msgs_uc_ff(g), 0u);
         HIP_TRY(hipGetLastError());
     }
     return FTRED_OK;
-}
-
-static hipError_t dispatch_retry(const ftred_plan_t* p, const RunArgs& A, uint32_t grid, uint32_t lds, hipStream_t st)
-{
-    if (p->dtype == FTRED_I64) return p->op == FTRED_SUM ? launch_retry_i64_sum(A, grid, lds, st) : launch_retry_i64_bor(A, grid, lds, st);
-    if (p->dtype == FTRED_U32) return p->op == FTRED_SUM ? launch_retry_u32_sum(A, grid, lds, st) : launch_retry_u32_bor(A, grid, lds, st);
-    return launch_retry_f64_sum(A, grid, lds, st);
 }
 
 static int check_common(const char* who, const ftred_plan_t* plan, uint32_t S, const void* payload,
@@ -711,6 +731,7 @@ extern "C" int ftred_run_reduce_info(const ftred_plan_t* plan, uint32_t S, const
 {
     if (!info_count && !info_ids && !info_child)
         return fail(FTRED_EINVAL, "ftred_run_reduce_info: at least one of info_count, info_ids, info_child is required");
+    if (plan && plan->alt) plan = plan->alt;
     return run_reduce_impl("ftred_run_reduce_info", plan, S, root, payload, scen_stride_elems, fail_rank, fail_round,
                            result, status, msgs, InfoOut{info_count, info_ids, info_child}, workspace, workspace_bytes,
                            hip_stream);
@@ -766,14 +787,19 @@ static int run_allreduce_impl(const char* who, const ftred_plan_t* plan, uint32_
     A.retry_slots = slots;
     A.retry_ws = wsb + ws_retry_off(plan, S);
 
-    // attempts whose root had failed beforehand run as extra "scenarios" of the tier
-    // launches; beyond kRetrySlots of them (unusual) the retry kernel takes over
+    // attempts whose root had failed beforehand run as extra "scenarios" of the tier launches
     if (plan->use_shape) {
         rc = launch_shape(plan, A, S, st);
     } else {
         if (g.f > 0) {
+            // beyond kRetrySlots of them (unusual) nothing is simulated: their messages are counted from the failure lists
             TimedLaunch tl(FTRED_PH_RETRY, st);
-            HIP_TRY(dispatch_retry(plan, A, plan->retry_blocks, plan->max_lds, st));
+            const uint64_t most = uint64_t(S) * g.f;        // at most f failed attempts per scenario
+            if (most > slots) {
+                hipLaunchKernelGGL(retry_counts_kernel, dim3(uint32_t((most - slots + 255u) / 256u)), dim3(256), 0, st, A,
+                                   (unsigned long long)msgs_uc_ff(g), slots);
+                HIP_TRY(hipGetLastError());
+            }
         }
         rc = launch_tiers(plan, A, S, slots, st);
     }
@@ -829,6 +855,7 @@ extern "C" int ftred_run_allreduce_info(const ftred_plan_t* plan, uint32_t S, co
 {
     if (!info_count && !info_ids && !info_child)
         return fail(FTRED_EINVAL, "ftred_run_allreduce_info: at least one of info_count, info_ids, info_child is required");
+    if (plan && plan->alt) plan = plan->alt;
     return run_allreduce_impl("ftred_run_allreduce_info", plan, S, payload, scen_stride_elems, fail_rank, fail_round,
                               result, has_bitmap, per_process_out, status, attempts, msgs,
                               InfoOut{info_count, info_ids, info_child}, workspace, workspace_bytes, hip_stream);

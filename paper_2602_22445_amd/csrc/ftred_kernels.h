@@ -859,42 +859,10 @@ __global__ void __launch_bounds__(kThreads) tier_list_kernel(RunArgs A)
     }
 }
 
-// Failed attempts beyond the kRetrySlots that run inside the tier launches (a
-// batch with that many failed roots is unusual): one workgroup walks through a
-// whole attempt, tier after tier, with its own scratch.
-template <class T, int OP, int WP>
-__global__ void __launch_bounds__(kThreads) retry_kernel(RunArgs A)
-{
-    extern __shared__ __align__(16) unsigned char smem[];
-    FailTab& ft = *reinterpret_cast<FailTab*>(smem);
-    uint32_t* lmeta = reinterpret_cast<uint32_t*>(smem + sizeof(FailTab));
-    uint32_t max_rows = 0;
-    for (uint32_t t = 0; t < A.ntiers; ++t)
-        if (A.tiers[t].lds_rows > max_rows) max_rows = A.tiers[t].lds_rows;
-    unsigned char* lrows = smem + sizeof(FailTab) + ((size_t(max_rows) * 4u + 15u) & ~size_t(15));
-    unsigned char* wsB = A.retry_ws + size_t(A.retry_slots + blockIdx.x) * A.ws_stride;
-    const uint32_t n = *A.retry_count;
-    for (uint32_t k = A.retry_slots + blockIdx.x; k < n; k += gridDim.x) {
-        const uint32_t s = A.retry_list[2u * k];
-        const uint32_t root = A.retry_list[2u * k + 1u];
-        const uint32_t base = root * A.g.Ratt;
-        const unsigned char* pay = A.payload + size_t(s) * A.scen_stride_bytes;
-        for (uint32_t t = 0; t < A.ntiers; ++t) {
-            const TierDesc& td = A.tiers[t];
-            const uint32_t top0 = (1u << td.dlo) - 1u;
-            uint32_t c_hi = 1u << td.dlo;
-            if (top0 + c_hi > A.g.M) c_hi = A.g.M - top0;
-            __syncthreads();          // scratch rows of the tier below are complete and visible
-            walk_cones<T, OP, WP, T>(A, td, ft, lrows, lmeta, s, root, base, 0, c_hi, pay, wsB, true, max_rows);   // element-wise staging
-        }
-    }
-}
-
 // launchers, one set per (value type, operator), defined in ftred_inst_*.hip
 #define FTRED_DECLARE_LAUNCHERS(NAME)                                                         \
     hipError_t launch_tier_##NAME(const RunArgs& A, uint32_t grid, uint32_t lds, hipStream_t st); \
-    hipError_t launch_list_##NAME(const RunArgs& A, uint32_t grid, uint32_t lds, hipStream_t st); \
-    hipError_t launch_retry_##NAME(const RunArgs& A, uint32_t grid, uint32_t lds, hipStream_t st);
+    hipError_t launch_list_##NAME(const RunArgs& A, uint32_t grid, uint32_t lds, hipStream_t st);
 
 FTRED_DECLARE_LAUNCHERS(i64_sum)
 FTRED_DECLARE_LAUNCHERS(i64_bor)
@@ -929,12 +897,6 @@ FTRED_DECLARE_LAUNCHERS(f64_sum)
             default: return list_wp_##NAME<16>(A, grid, lds, st);                                  \
         }                                                                                          \
     }                                                                                              \
-    template <int WP>                                                                              \
-    static hipError_t retry_wp_##NAME(const RunArgs& A, uint32_t grid, uint32_t lds, hipStream_t st) \
-    {                                                                                              \
-        hipLaunchKernelGGL((retry_kernel<T, OP, WP>), dim3(grid), dim3(kThreads), lds, st, A);      \
-        return hipGetLastError();                                                                  \
-    }                                                                                              \
     hipError_t launch_tier_##NAME(const RunArgs& A, uint32_t grid, uint32_t lds, hipStream_t st)    \
     {                                                                                              \
         switch (wp_bucket(A.g.W)) {                                                                \
@@ -944,17 +906,6 @@ FTRED_DECLARE_LAUNCHERS(f64_sum)
             case 5: return tier_wp_##NAME<5>(A, grid, lds, st);                                    \
             case 9: return tier_wp_##NAME<9>(A, grid, lds, st);                                    \
             default: return tier_wp_##NAME<16>(A, grid, lds, st);                                  \
-        }                                                                                          \
-    }                                                                                              \
-    hipError_t launch_retry_##NAME(const RunArgs& A, uint32_t grid, uint32_t lds, hipStream_t st)   \
-    {                                                                                              \
-        switch (wp_bucket(A.g.W)) {                                                                \
-            case 2: return retry_wp_##NAME<2>(A, grid, lds, st);                                   \
-            case 3: return retry_wp_##NAME<3>(A, grid, lds, st);                                   \
-            case 4: return retry_wp_##NAME<4>(A, grid, lds, st);                                   \
-            case 5: return retry_wp_##NAME<5>(A, grid, lds, st);                                   \
-            case 9: return retry_wp_##NAME<9>(A, grid, lds, st);                                   \
-            default: return retry_wp_##NAME<16>(A, grid, lds, st);                                 \
         }                                                                                          \
     }
 

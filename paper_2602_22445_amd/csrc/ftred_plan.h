@@ -19,7 +19,6 @@ struct ftred_plan_s {
     uint32_t max_lds;
     uint32_t vroot_off;
     uint64_t ws_scen;           // scratch bytes per scenario (tree tiers)
-    uint32_t retry_blocks;
     uint32_t use_wave;          // the deepest tier runs as one wavefront per subtree
     ftred::WaveLayout wl;
     uint32_t kwalk_given;       // the flags fix the cones a workgroup walks through
@@ -28,6 +27,8 @@ struct ftred_plan_s {
     uint32_t use_fused;         // ... and the levels above it and the root's choice in the same launch
     ftred::FusedLayout fl;
     uint32_t wave_gshift;       // workgroups of the wavefront tier per scenario = 2^wave_gshift
+    ftred_plan_s* alt;          // the same plan on LDS tiles only, for runs that carry the lists of failed processes
+                                // (set where the tile kernel that runs the listed subtrees then cannot stage a subtree)
     uint32_t use_shape;         // another tree shape than the binary heap: the plain per-depth kernels (ftred_shape.h)
     uint32_t shape_msg_off, shape_meta_off;   // their scratch: the tree messages of every row, one word per row
     uint32_t retry_scratch;     // scratch areas of retry entries (none for the per-depth kernels)
@@ -47,7 +48,7 @@ inline uint32_t align_up(uint32_t x, uint32_t a) { return (x + a - 1) / a * a; }
 inline uint32_t val_chunks(const ftred_plan_s* p) { return (p->g.P + p->val_chunk - 1) / p->val_chunk; }
 
 // workspace layout: [tree scratch of S scenarios][tree scratch of the retry
-// entries: kRetrySlots + retry_blocks][validation partials][retry list][fix list][256 bytes
+// entries: kRetrySlots][validation partials][retry list][fix list][256 bytes
 // of counters: +0 invalid scenarios (u64), +8 retry entries (u32), +12, +16 and +20 entries
 // of the lists of subtrees (u32)]
 inline uint64_t ws_retry_off(const ftred_plan_s* p, uint32_t S) { return uint64_t(S) * p->ws_scen; }
@@ -77,7 +78,12 @@ inline uint64_t ws_fix_bytes(const ftred_plan_s* p, uint32_t S)
 // two such lists: for the LDS-tile kernel and for the register kernel with failure handling
 inline uint64_t ws_wfix_off(const ftred_plan_s* p, uint32_t S) { return ws_fix_off(p, S) + ws_fix_bytes(p, S); }
 inline uint64_t ws_ctr_off(const ftred_plan_s* p, uint32_t S) { return ws_wfix_off(p, S) + ws_fix_bytes(p, S); }
-inline uint64_t ws_total(const ftred_plan_s* p, uint32_t S) { return ws_ctr_off(p, S) + 256u; }
+inline uint64_t ws_own(const ftred_plan_s* p, uint32_t S) { return ws_ctr_off(p, S) + 256u; }
+inline uint64_t ws_total(const ftred_plan_s* p, uint32_t S)
+{
+    const uint64_t a = ws_own(p, S), b = p->alt ? ws_own(p->alt, S) : 0u;
+    return a > b ? a : b;
+}
 
 // event-pair timing of kernel launches (ftred_timing_begin / ftred_timing_end)
 void tm_mark(int phase, hipStream_t st, bool start);

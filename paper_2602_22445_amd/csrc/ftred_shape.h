@@ -15,7 +15,7 @@
 // scratch area is as large as the payload: this path is for comparing shapes, not
 // for the benchmark.  Attempts of an allreduce whose root had failed deliver
 // nothing; only their messages count, and those follow from the failure list
-// alone (shape_retry_counts_kernel).
+// alone (retry_counts_kernel).
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -203,13 +203,14 @@ __global__ void __launch_bounds__(64) shape_root_kernel(RunArgs A, uint32_t msg_
     if (tid == 0) A.status[s] = st;
 }
 
-// Messages of the attempts whose root had failed beforehand: every process that is alive sends what it would
-// send anyway (a reduce does not wait for what it receives), so the counts follow from the failure list: the
-// failure-free counts (message-count theorem) less what each listed process no longer sends.
-static __global__ void __launch_bounds__(256) shape_retry_counts_kernel(RunArgs A, unsigned long long uc_ff)
+// Messages of attempts whose root had failed beforehand (entries `first`, first + 1, .. of the retry list): such an
+// attempt delivers nothing, and every process that is alive sends what it would send anyway (a reduce does not
+// wait for what it receives), so the counts follow from the failure list: the failure-free counts (message-count
+// theorem) less what each listed process no longer sends.
+static __global__ void __launch_bounds__(256) retry_counts_kernel(RunArgs A, unsigned long long uc_ff, uint32_t first)
 {
     const Geom& g = A.g;
-    const uint32_t k = blockIdx.x * blockDim.x + threadIdx.x;
+    const uint32_t k = first + blockIdx.x * blockDim.x + threadIdx.x;
     if (k >= *A.retry_count || !A.msgs) return;
     const uint32_t s = A.retry_list[2u * k], root = A.retry_list[2u * k + 1u];
     const uint32_t base = root * g.Ratt;

@@ -373,6 +373,11 @@ hipError_t launch_validate(const ValArgs& A, hipStream_t st)
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const uint32_t lds = A.g.E * 16u;
+    if (lds > 48u * 1024u) {          // more dynamic LDS than a launch gets without asking
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&val_final_kernel<T, OP>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, int(lds));
+        if (e != hipSuccess) return e;
+    }
     {
         TimedLaunch tl(FTRED_PH_VAL_FINAL, st);
         // one wavefront per scenario unless there are many value indices: the work is a few dependent loads
@@ -402,7 +407,9 @@ extern "C" int ftred_validate(const ftred_plan_t* plan, int kind, uint32_t S, co
     if (workspace_bytes < ws_total(plan, S))
         return set_error(FTRED_EINVAL, "ftred_validate: workspace of %llu bytes, %llu needed",
                          (unsigned long long)workspace_bytes, (unsigned long long)ws_total(plan, S));
-    if (g.E * 16u > 48u * 1024u) return set_error(FTRED_EUNSUPPORTED, "ftred_validate: elems too large (%u)", g.E);
+    // pass 2 keeps the reduction over the never-failed processes and its scale in LDS: 16 bytes per value index
+    if (g.E * 16u > 128u * 1024u)
+        return set_error(FTRED_EUNSUPPORTED, "ftred_validate: more than 8192 values per process (%u)", g.E);
     hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
 
     ValArgs A;

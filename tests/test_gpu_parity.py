@@ -317,6 +317,80 @@ def test_sweeps_without_the_fused_kernel(ft, oracle, w):
         compare_reduce(ft, oracle, plan, x, fr, fo, root=w.random_roots(seed, S, P))
 
 
+@pytest.mark.parametrize("P,f,E,dtype,op,S", [(1024, 3, 4096, 2, 0, 6), (300, 1, 8192, 0, 0, 4), (64, 2, 3000, 1, 1, 8),
+                                              (5000, 4, 1000, 2, 0, 3)])
+def test_large_payloads(ft, oracle, w, P, f, E, dtype, op, S):
+    """Kilobytes per process (the bandwidth regime): a row no longer fits the LDS tiles, so the plan runs the tree
+    phase on the plain per-depth kernels; the validation holds up to 8192 values per process in LDS."""
+    seed = 31000 + P + E
+    plan = ft.Plan(P, f, E, dtype, op)
+    assert plan.info.tiers == 0 and plan.info.shape == 2
+    Rred, Ratt = plan.info.rounds_reduce, plan.info.rounds_attempt
+    x = _payload(w, seed, S, P, E, dtype)
+    fr, fo = w.random_failure_sets(seed, S, P, f, inop_permille=500, rounds_per_attempt=Rred + 1)
+    root = w.random_roots(seed, S, P)
+    g, _ = compare_reduce(ft, oracle, plan, x, fr, fo, root=root)
+    xd, frd, fod, rd = to_dev(x), to_dev(fr), to_dev(fo), to_dev(root.astype(np.uint32))
+    v = ft.validate(plan, 0, S, xd, frd, fod, g["result"], g["status"], root=rd, msgs=g["msgs"])
+    assert v["n_invalid"] == 0
+    fr, fo = w.random_failure_sets(seed + 1, S, P, f, inop_permille=500, rounds_per_attempt=Ratt, protected=f + 1)
+    fr[0], fo[0] = w.NO_RANK, 0
+    fr[0, 0], fo[0, 0] = 0, 0                            # a second attempt
+    g, _ = compare_allreduce(ft, oracle, plan, x, fr, fo)
+    frd, fod = to_dev(fr), to_dev(fo)
+    v = ft.validate(plan, 1, S, xd, frd, fod, g["result"], g["status"], has_bitmap=g["has_bitmap"],
+                    per_process_out=g["per_process_out"], attempts=g["attempts"], msgs=g["msgs"])
+    assert v["n_invalid"] == 0
+    # and a wrong value is still found among that many
+    bad = g["result"].cpu().numpy().copy()
+    bad[S - 1, E - 1] = bad[S - 1, E - 1] + 1 if op == 0 else ~bad[S - 1, E - 1]
+    v = ft.validate(plan, 1, S, xd, frd, fod, to_dev(bad), g["status"], attempts=g["attempts"])
+    assert v["n_invalid"] == 1 and v["verdict"].cpu().numpy()[S - 1] & ft.BAD_VALUE
+
+
+@pytest.mark.parametrize("P,f,E,dtype", [(5000, 2, 4, 0), (16384, 4, 8, 2), (64, 2, 8, 1), (3000, 3, 48, 2), (1 << 16, 8, 1, 0)])
+def test_many_failed_roots(ft, oracle, w, P, f, E, dtype):
+    """More attempts with a failed root than ride along in the launches of the tree phase (64): the first 64 are
+    simulated as extra scenarios, the messages of the others are counted from the failure lists; every counter
+    must equal the oracle's, which simulates them all."""
+    S, seed = 150, 41000 + P
+    plan = ft.Plan(P, f, E, dtype, ft.SUM)
+    Ratt = plan.info.rounds_attempt
+    fr, fo = w.random_failure_sets(seed, S, P, f, inop_permille=600, rounds_per_attempt=Ratt, protected=f + 1)
+    for s in range(0, S, 3):                             # root 0 failed: a second attempt
+        if 0 not in fr[s].tolist():
+            fr[s, 0], fo[s, 0] = 0, 0
+    for s in range(0, S, 6):                             # roots 0 and 1 failed: a third one
+        fr[s, :2], fo[s, :2] = [0, 1], [0, 0]
+    x = _payload(w, seed, S, P, E, dtype)
+    g, o = compare_allreduce(ft, oracle, plan, x, fr, fo, check_out=P <= 20000)
+    assert int((o["attempts"].astype(np.int64) - 1).sum()) > 64
+
+
+@pytest.mark.parametrize("P,f,E,dtype,op", [(3000, 3, 48, 2, 0), (16384, 4, 32, 2, 0), (2500, 1, 100, 0, 1), (40000, 2, 24, 1, 0)])
+def test_medium_payloads_take_the_register_kernels(ft, oracle, w, P, f, E, dtype, op):
+    """A few hundred bytes per process: a subtree of the register tier no longer fits the LDS tile of the kernel
+    that runs the listed subtrees when the lists of failed processes are asked for, so such runs take a second
+    plan on LDS tiles throughout; the plain runs keep the register kernels."""
+    S, seed = 12, 43000 + P + E
+    plan = ft.Plan(P, f, E, dtype, op)
+    assert plan.info.deep_kernel == 1
+    Rred, Ratt = plan.info.rounds_reduce, plan.info.rounds_attempt
+    x = _payload(w, seed, S, P, E, dtype)
+    fr, fo = w.random_failure_sets(seed, S, P, f, inop_permille=500, rounds_per_attempt=Rred + 1)
+    root = w.random_roots(seed, S, P)
+    g, o = compare_reduce(ft, oracle, plan, x, fr, fo, root=root)
+    gi = ft.run_reduce_info(plan, S, to_dev(x), to_dev(fr), to_dev(fo), root=to_dev(root.astype(np.uint32)))
+    for k in ("result", "status", "msgs"):
+        assert np.array_equal(gi[k].cpu().numpy(), g[k].cpu().numpy()), k
+    oi = oracle.reduce_info_batch(P, f, x, dtype, op, S, root=root, fail_rank=fr, fail_round=fo)
+    assert np.array_equal(gi["info_count"].cpu().numpy(), oi["info_count"])
+    fr, fo = w.random_failure_sets(seed + 1, S, P, f, inop_permille=500, rounds_per_attempt=Ratt, protected=f + 1)
+    fr[0], fo[0] = w.NO_RANK, 0
+    fr[0, 0], fo[0, 0] = 0, 0
+    compare_allreduce(ft, oracle, plan, x, fr, fo)
+
+
 def test_two_streams_with_their_own_workspaces_do_not_disturb_each_other(ft, oracle, w):
     """Two plans run side by side on two streams (default priority), each with its own workspace and output
     buffers, several calls each: the library keeps no device state of its own between or across calls."""
