@@ -211,6 +211,26 @@ extern "C" int ftred_plan(ftred_plan_t** out, uint32_t P, uint32_t f, uint32_t e
         if (1u + (levels + hc1) / (hc1 + 1u) > uint32_t(kMaxTiers)) row_too_large = true;
     }
     bool info_alt = false;
+    // ... unless one workgroup can fold a whole scenario, block of value indices by block: that kernel and the
+    // register walk of the listed subtrees need no LDS tile of rows at all
+    if (shape == kShapeBinary && row_too_large && g.L > uint32_t(kWaveH) && !(flags & 0x11000u) && !((flags >> 13) & 7u) &&
+        wave_width_ok(g.W) && g.E > 1u && make_fused_layout(g, g.L - uint32_t(kWaveH)).ok) {
+        p->fused_only = 1;
+        p->use_wave = 1;
+        p->use_fused = 1;
+        TierDesc& t = p->tiers[0];
+        t.dlo = g.L - uint32_t(kWaveH); t.dhi = g.L;
+        p->ntiers = 1;
+        p->vroot_off = 0;
+        uint32_t off = align_up(g.EB, 16);               // [0, EB): the root's value after up-correction
+        t.out_off = off;                                 // the top rows of the listed subtrees and their words
+        off += align_up((1u << t.dlo) * g.RB, 16);
+        t.out_meta_off = off;
+        off += align_up((1u << t.dlo) * 4u, 16);
+        p->ws_scen = align_up(off, 256);
+        p->wl = make_wave_layout(g, t.dlo);
+        p->fl = make_fused_layout(g, t.dlo);
+    } else
     if (shape != kShapeBinary || row_too_large) {
         // the plain per-depth kernels: no tiers; scratch = the root's value, the tree messages of every row, a word per row
         p->use_shape = 1;
@@ -224,7 +244,7 @@ extern "C" int ftred_plan(ftred_plan_t** out, uint32_t P, uint32_t f, uint32_t e
             return fail(FTRED_EUNSUPPORTED, "ftred_plan: the scratch of one scenario must stay below 4 GiB");
         }
     }
-    if (!p->use_shape) {
+    if (!p->use_shape && !p->fused_only) {
         // tiers of the tree phase, deepest first.  The deepest tier reads the payload
         // and wants many workgroups per CU (small tiles); the upper tiers are small.
         const uint32_t stage_rows = kStageBytes / g.RB;               // rows the prefetch registers hold
@@ -519,7 +539,7 @@ static int launch_tiers(const ftred_plan_t* plan, RunArgs& A, uint32_t S, uint32
                 // the scenario folds all the others and then everything above them, down to the root's choice
                 const uint32_t lds = (1u << plan->wl.slot_shift) * kWaveRows * uint32_t(sizeof(RowInfo));
                 HIP_TRY(dispatch_wave_list(plan, A, uint32_t(wgs), lds, st));
-                HIP_TRY(dispatch_fused(plan, A, S + extra, fused_lds_bytes(plan->g, plan->tiers[0].dlo), st));
+                HIP_TRY(dispatch_fused(plan, A, S + extra, fused_lds_bytes(plan->g, plan->fl, plan->tiers[0].dlo), st));
                 return FTRED_OK;
             }
             HIP_TRY(dispatch_wave(plan, A, (S + extra) << plan->wave_gshift, st));
@@ -684,8 +704,9 @@ static int run_reduce_impl(const char* who, const ftred_plan_t* plan, uint32_t S
         return fail(FTRED_EINVAL, "%s: result must be aligned to the element size", who);
     hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
     const Geom& g = plan->g;
-    if (io.any() && plan->use_shape)
-        return fail(FTRED_EUNSUPPORTED, "%s: the lists of failed processes are carried by the default tree shape only", who);
+    if (io.any() && (plan->use_shape || plan->fused_only))
+        return fail(FTRED_EUNSUPPORTED, "%s: the lists of failed processes are carried by the default tree shape and by "
+                                        "payloads whose rows fit the LDS tiles only", who);
     if (io.any()) HIP_TRY(clear_info(g, S, io, st));
 
     {
@@ -753,8 +774,9 @@ static int run_allreduce_impl(const char* who, const ftred_plan_t* plan, uint32_
         return fail(FTRED_EINVAL, "%s: result and per_process_out must be aligned to the element size", who);
     hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
     const Geom& g = plan->g;
-    if (io.any() && plan->use_shape)
-        return fail(FTRED_EUNSUPPORTED, "%s: the lists of failed processes are carried by the default tree shape only", who);
+    if (io.any() && (plan->use_shape || plan->fused_only))
+        return fail(FTRED_EUNSUPPORTED, "%s: the lists of failed processes are carried by the default tree shape and by "
+                                        "payloads whose rows fit the LDS tiles only", who);
     if (io.any()) HIP_TRY(clear_info(g, S, io, st));
 
     unsigned char* wsb = static_cast<unsigned char*>(workspace);

@@ -26,6 +26,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <string.h>
 
 #include "ftred_geom.h"
 #include "ftred_kernels.h"
@@ -35,47 +36,61 @@ namespace ftred {
 
 constexpr uint32_t kFusedMaxWaves = 4;
 constexpr int kFusedItems = 4;                       // (row, value index) items of the upper levels per thread
-// most LDS for the top rows of one scenario's subtrees: three workgroups per CU for the narrow groups (three
-// wavefronts per SIMD), two for the wider ones
-inline uint32_t fused_tile_bytes(uint32_t W) { return W <= 5u ? 48u * 1024u : 72u * 1024u; }
 
 struct FusedLayout {
     uint32_t ne, slot_shift, nact;   // lanes of a wavefront = 2^slot_shift sibling subtrees x ne value indices
     uint32_t group_shift;            // a wavefront walks through 2^group_shift groups of subtrees
     uint32_t wshift;                 // wavefronts per workgroup = 2^wshift
-    uint32_t passes;                 // always 1: every value index has its lane (see the walk)
+    uint32_t passes;                 // blocks of ne value indices: the workgroup folds the whole tree once per block
+    uint32_t one;                    // always 1: trip count of the loop around the walk (see the kernel)
+    FastDiv div_ne;
     uint32_t ok;                     // the plan can use the fused kernel
 };
+
+// most LDS for the top rows of one scenario's subtrees (one block of value indices): three workgroups per CU for
+// the narrow groups (three wavefronts per SIMD), two for the wider ones
+inline uint32_t fused_tile_bytes(uint32_t W) { return W <= 5u ? 48u * 1024u : 72u * 1024u; }
 
 inline FusedLayout make_fused_layout(const Geom& g, uint32_t dlo)
 {
     FusedLayout f;
-    const WaveLayout w = make_wave_layout(g, dlo);
-    f.ne = w.ne; f.slot_shift = w.slot_shift; f.nact = w.nact; f.passes = 1;
-    const uint32_t rest = dlo - w.slot_shift;         // log2 of the groups of subtrees per scenario
-    f.group_shift = rest > 2u ? (rest - 2u < 2u ? rest - 2u : 2u) : 0u;
-    f.wshift = rest - f.group_shift;
-    const uint64_t items = ((uint64_t(1) << dlo) - 1u) * g.E;
-    f.ok = (w.passes == 1u && (1u << f.wshift) <= kFusedMaxWaves &&
-            (uint64_t(g.RB) << dlo) <= fused_tile_bytes(g.W) &&
-            items <= uint64_t(kFusedItems) * 64u * (1u << f.wshift)) ? 1u : 0u;
+    memset(&f, 0, sizeof(f));
+    // the block of value indices: as many as a wavefront has lanes for, fewer where the top rows of a wider block
+    // do not fit the tile, but at least a 128-byte line of every process's payload (or all of it)
+    for (uint32_t ne = g.E < 64u ? g.E : 64u; ne >= 1u; ne /= 2u) {
+        uint32_t slots = 64u / ne, sh = 0;
+        while ((2u << sh) <= slots && sh < dlo) ++sh;
+        f.ne = ne; f.slot_shift = sh; f.nact = (1u << sh) * ne;
+        f.passes = (g.E + ne - 1u) / ne;
+        f.one = 1;
+        f.div_ne = make_fastdiv(ne);
+        const uint32_t rest = dlo - sh;               // log2 of the groups of subtrees per scenario
+        f.group_shift = rest > 2u ? (rest - 2u < 2u ? rest - 2u : 2u) : 0u;
+        f.wshift = rest - f.group_shift;
+        const uint64_t items = ((uint64_t(1) << dlo) - 1u) * ne;
+        f.ok = ((1u << f.wshift) <= kFusedMaxWaves &&
+                ((uint64_t(g.W) * ne * g.esz) << dlo) <= fused_tile_bytes(g.W) &&
+                items <= uint64_t(kFusedItems) * 64u * (1u << f.wshift)) ? 1u : 0u;
+        if (f.ok || (ne / 2u) * g.esz < 128u || ne % 2u != 0u) break;
+    }
     return f;
 }
 
-// dynamic LDS: failure table, the top rows, one word of sent / failed bits and one "folded here" word per subtree
-inline uint32_t fused_lds_bytes(const Geom& g, uint32_t dlo)
+// dynamic LDS: failure table, the top rows (one block of value indices), one word of sent / failed bits and one
+// "folded here" word per subtree
+inline uint32_t fused_lds_bytes(const Geom& g, const FusedLayout& fl, uint32_t dlo)
 {
-    return uint32_t(sizeof(FailTab)) + (g.RB << dlo) + (8u << dlo);
+    return uint32_t(sizeof(FailTab)) + ((g.W * fl.ne * g.esz) << dlo) + (8u << dlo);
 }
 
 // One (row, value index) item of the levels above the deepest tier.  The row is complete (W members, the root is
 // not in its group: the last row lies on the deepest level of the tree) and so are its two children rows.
-// x: the inputs of the row's members; c0, c1: the messages of the children rows in LDS (member stride E);
+// x: the inputs of the row's members; c0, c1: the messages of the children rows in LDS (member stride ms);
 // cm0, cm1: their sent (bits 0..15) and failed (16..31) bits.  Leaves the members' tree messages in x.
 template <class T, int OP, int WP>
-__device__ __forceinline__ uint32_t fused_item(const Geom& g, const FailTab& ft, bool check_fail, uint32_t j, T (&x)[WP],
-                                               const T* c0, const T* c1, uint32_t cm0, uint32_t cm1, bool count,
-                                               uint32_t& uc_cnt, uint32_t& tree_cnt)
+__device__ __forceinline__ uint32_t fused_item(const FailTab& ft, bool check_fail, uint32_t j, T (&x)[WP],
+                                               const T* c0, const T* c1, uint32_t ms, uint32_t cm0, uint32_t cm1,
+                                               bool count, uint32_t& uc_cnt, uint32_t& tree_cnt)
 {
     constexpr uint32_t mask = (1u << WP) - 1u;
     // failures of this row: tl = packed 4-bit "rounds in which member w still sends"
@@ -119,12 +134,12 @@ __device__ __forceinline__ uint32_t fused_item(const Geom& g, const FailTab& ft,
     // sets the failed bit
     if ((cm0 & mask) == mask && (cm1 & mask) == mask) {
 #pragma unroll
-        for (int k = 0; k < WP; ++k) v[k] = comb<T, OP>(comb<T, OP>(v[k], c0[k * g.E]), c1[k * g.E]);
+        for (int k = 0; k < WP; ++k) v[k] = comb<T, OP>(comb<T, OP>(v[k], c0[k * ms]), c1[k * ms]);
     } else {
 #pragma unroll
         for (int k = 0; k < WP; ++k) {
-            if ((cm0 >> k) & 1u) v[k] = comb<T, OP>(v[k], c0[k * g.E]);
-            if ((cm1 >> k) & 1u) v[k] = comb<T, OP>(v[k], c1[k * g.E]);
+            if ((cm0 >> k) & 1u) v[k] = comb<T, OP>(v[k], c0[k * ms]);
+            if ((cm1 >> k) & 1u) v[k] = comb<T, OP>(v[k], c1[k * ms]);
         }
     }
     const uint32_t flag = (((cm0 >> 16) | ~cm0) | ((cm1 >> 16) | ~cm1)) & mask;
@@ -150,11 +165,12 @@ __global__ void __launch_bounds__(kFusedMaxWaves * 64) __attribute__((amdgpu_wav
     const uint32_t tid = threadIdx.x, nthr = blockDim.x;
     const uint32_t lane = tid & 63u;
     const uint32_t wid = __builtin_amdgcn_readfirstlane(tid >> 6);     // the same in all lanes: addresses of rows stay scalar
-    const uint32_t ncones = 1u << dlo, RE = g.W * g.E;
+    const uint32_t ncones = 1u << dlo;
+    const uint32_t ne = fl.ne, REl = g.W * ne;       // a row of the tile: W members x ne value indices of the block
     const uint32_t top0 = ncones - 1u;
     FailTab& ft = *reinterpret_cast<FailTab*>(smem);
     T* tile = reinterpret_cast<T*>(smem + sizeof(FailTab));
-    uint32_t* lmeta = reinterpret_cast<uint32_t*>(smem + sizeof(FailTab) + (size_t(g.RB) << dlo));
+    uint32_t* lmeta = reinterpret_cast<uint32_t*>(smem + sizeof(FailTab) + (size_t(REl) * g.esz << dlo));
     uint32_t* folded = lmeta + ncones;
 
     // ---- which scenario, which root
@@ -186,20 +202,30 @@ __global__ void __launch_bounds__(kFusedMaxWaves * 64) __attribute__((amdgpu_wav
     const unsigned char* pay = A.payload + size_t(s) * A.scen_stride_bytes;
     const uint32_t F = g.f > 0 ? g.f : 1;
 
-    for (uint32_t c = tid; c < ncones; c += nthr) folded[c] = 0u;
     load_failtab(ft, g, A.fail_rank, A.fail_round, s, root, base);
-    __syncthreads();
-
-    // ---- the deepest tier: every wavefront walks through its groups of subtrees (as wave_tier_kernel does)
-    {
-        const uint32_t slot = lane / fl.ne;
-        const uint32_t e = lane - slot * fl.ne;
-        const bool active = lane < fl.nact;
-        const uint32_t listed = lane < g.f ? A.fail_rank[size_t(s) * F + lane] : kNoRank;
-        const uint32_t special = subtree_of_row(special_row_of_lane(g, dlo, listed, root, lane), dlo);
-        const unsigned char* bk[WP];
+    // lane -> (subtree slot, value index of the block); the subtrees that the list kernel folded, one per lane
+    const uint32_t slot = lane / ne;
+    const uint32_t e = lane - slot * ne;
+    const bool active = lane < fl.nact;
+    const uint32_t listed = lane < g.f ? A.fail_rank[size_t(s) * F + lane] : kNoRank;
+    const uint32_t special = subtree_of_row(special_row_of_lane(g, dlo, listed, root, lane), dlo);
+    const unsigned char* bk[WP];
 #pragma unroll
-        for (int k = 0; k < WP; ++k) bk[k] = pay + size_t(k) * g.EB;
+    for (int k = 0; k < WP; ++k) bk[k] = pay + size_t(k) * g.EB;
+    uint32_t uc_cnt = 0, tree_cnt = 0;
+    uint32_t st = kStOk;
+
+    // One block of ne value indices after the other (one block unless a process holds more than 64 values): the
+    // whole tree is folded for the block, its top rows in LDS.  The walk itself sits in a loop of its own whose trip
+    // count (one) the compiler does not know, with a value index that depends on the trip: as straight-line code, or
+    // in a loop whose body does not change, the loads of a whole walk are requested ahead of it and the kernel needs
+    // 300 to 500 registers instead of 160.
+    for (uint32_t pass = 0; pass < fl.passes; ++pass) {
+        const uint32_t ecol_p = pass * ne + e;
+        for (uint32_t c = tid; c < ncones; c += nthr) folded[c] = 0u;
+        __syncthreads();                              // also: the failure table is there, the last block is done with the tile
+
+        // ---- the deepest tier: every wavefront walks through its groups of subtrees (as wave_tier_kernel does)
         for (uint32_t gi = 0; gi < (1u << fl.group_shift); ++gi) {
             // the groups of a wavefront lie a stride of wavefronts apart: side by side run wavefronts that read
             // rows side by side
@@ -219,12 +245,8 @@ __global__ void __launch_bounds__(kFusedMaxWaves * 64) __attribute__((amdgpu_wav
             }
             const bool mine = exists && !handover;
             const bool any_bottom = __ballot(mine && bottom) != 0ull;
-            // One pass; written like the loop over the passes of wave_tier_kernel, over a count the compiler does
-            // not know and with a value index that depends on the pass: as straight-line code, or as a loop whose
-            // body does not change, the loads of a whole walk are requested ahead of it and the kernel needs 300
-            // to 500 registers instead of 160.
-            for (uint32_t pass = 0; pass < fl.passes; ++pass) {
-            const uint32_t ecol = pass * fl.ne + e;
+            for (uint32_t rep = 0; rep < fl.one; ++rep) {          // one trip: see above
+            const uint32_t ecol = ecol_p + rep * ne;
             if (mine && ecol < g.E) {
                 T out[WP];
                 if (root == 0) {
@@ -253,89 +275,117 @@ __global__ void __launch_bounds__(kFusedMaxWaves * 64) __attribute__((amdgpu_wav
                     }
                 }
 #pragma unroll
-                for (int k = 0; k < WP; ++k) tile[(size_t(cone) * WP + k) * g.E + ecol] = out[k];
-                if (ecol == 0) {
-                    lmeta[cone] = (1u << WP) - 1u;                 // all sent, no failed bit
-                    folded[cone] = 1u;
+                for (int k = 0; k < WP; ++k) tile[(size_t(cone) * WP + k) * ne + e] = out[k];
+            }
+            }
+            if (mine && e == 0) {
+                lmeta[cone] = (1u << WP) - 1u;                     // all sent, no failed bit
+                folded[cone] = 1u;
+            }
+        }
+
+        // ---- the inputs of the rows above, all levels at once: item q = (row in the order deepest level first, value
+        // index of the block).  Requested here and not earlier: during the walk its registers are all in use; what the
+        // items need is worked out from a copy of the thread's number that does not exist before this point.
+        uint32_t tid_b = tid;
+        asm volatile("" : "+v"(tid_b) : : "memory");
+        const uint32_t NQ = (ncones - 1u) * ne;
+        uint32_t jx = kNoRank, kx = 0;
+        if (root != 0) {                              // the process that carries the root's number is process 0
+            jx = fdiv(root - 1u, g.divW);
+            kx = root - 1u - jx * g.W;
+        }
+        T xs[kFusedItems][WP];
+        uint32_t ij[kFusedItems], ie[kFusedItems], il[kFusedItems], ip[kFusedItems];
+#pragma unroll
+        for (int i = 0; i < kFusedItems; ++i) {
+            const uint32_t q = tid_b + uint32_t(i) * nthr;
+            const bool valid = q < NQ;
+            const uint32_t r = fdiv(valid ? q : 0u, fl.div_ne);
+            const uint32_t el = (valid ? q : 0u) - r * ne;
+            const uint32_t ec = pass * ne + el < g.E ? pass * ne + el : 0u;     // past the last value index: any valid address
+            const uint32_t t = ncones - 1u - r;           // 2^l <= t < 2^(l+1) on level l
+            const uint32_t l = ilog2(t);
+            const uint32_t p = (2u << l) - 1u - t;        // position on its level
+            const uint32_t j = (1u << l) - 1u + p;
+            ij[i] = j; ie[i] = el; ip[i] = p;
+            il[i] = (valid && pass * ne + el < g.E) ? l : kNoRank;
+            const T* src = reinterpret_cast<const T*>(pay) + (size_t(1u + j * g.W)) * g.E + ec;
+#pragma unroll
+            for (int k = 0; k < WP; ++k) xs[i][k] = src[size_t(k) * g.E];
+            if (j == jx) {
+                const T x0 = reinterpret_cast<const T*>(pay)[ec];
+#pragma unroll
+                for (int k = 0; k < WP; ++k) xs[i][k] = kx == uint32_t(k) ? x0 : xs[i][k];
+            }
+        }
+        __syncthreads();                                  // every wavefront has left its top rows
+
+        // ---- the subtrees folded by the list kernel (an earlier launch): their top rows and words from the scratch area
+        for (uint32_t c = wid; c < ncones; c += (nthr >> 6)) {
+            if (top0 + c < g.M && !folded[c]) {
+                const T* src = reinterpret_cast<const T*>(wsS + td.out_off + size_t(c) * g.RB);
+                for (uint32_t i = lane; i < REl; i += 64u) {
+                    const uint32_t k = fdiv(i, fl.div_ne), el = i - k * ne;
+                    if (pass * ne + el < g.E) tile[size_t(c) * REl + i] = src[size_t(k) * g.E + pass * ne + el];
                 }
-            }
-            }
-        }
-    }
-
-    // ---- the inputs of the rows above, all levels at once: item q = (row in the order deepest level first, value index)
-    // (requested here and not earlier: during the walk its registers are all in use; what the items need is worked
-    // out from a copy of the thread's number that does not exist before this point)
-    uint32_t tid_b = tid;
-    asm volatile("" : "+v"(tid_b) : : "memory");
-    const uint32_t NQ = (ncones - 1u) * g.E;
-    T xs[kFusedItems][WP];
-    uint32_t ij[kFusedItems], ie[kFusedItems], il[kFusedItems], ip[kFusedItems];
-    uint32_t jx = kNoRank, kx = 0;
-    if (root != 0) {                                  // the process that carries the root's number is process 0
-        jx = fdiv(root - 1u, g.divW);
-        kx = root - 1u - jx * g.W;
-    }
-#pragma unroll
-    for (int i = 0; i < kFusedItems; ++i) {
-        const uint32_t q = tid_b + uint32_t(i) * nthr;
-        const bool valid = q < NQ;
-        const uint32_t r = fdiv(valid ? q : 0u, g.divE);
-        const uint32_t e = (valid ? q : 0u) - r * g.E;
-        const uint32_t t = ncones - 1u - r;           // 2^l <= t < 2^(l+1) on level l
-        const uint32_t l = ilog2(t);
-        const uint32_t p = (2u << l) - 1u - t;        // position on its level
-        const uint32_t j = (1u << l) - 1u + p;
-        ij[i] = j; ie[i] = e; ip[i] = p;
-        il[i] = valid ? l : kNoRank;
-        const T* src = reinterpret_cast<const T*>(pay) + (size_t(1u + j * g.W)) * g.E + e;
-#pragma unroll
-        for (int k = 0; k < WP; ++k) xs[i][k] = src[size_t(k) * g.E];
-        if (j == jx) {
-            const T x0 = reinterpret_cast<const T*>(pay)[e];
-#pragma unroll
-            for (int k = 0; k < WP; ++k) xs[i][k] = kx == uint32_t(k) ? x0 : xs[i][k];
-        }
-    }
-    __syncthreads();                                  // every wavefront has left its top rows
-
-    // ---- the subtrees folded by the list kernel (an earlier launch): their top rows and words from the scratch area
-    for (uint32_t c = wid; c < ncones; c += (nthr >> 6)) {
-        if (top0 + c < g.M && !folded[c]) {
-            const T* src = reinterpret_cast<const T*>(wsS + td.out_off + size_t(c) * g.RB);
-            for (uint32_t i = lane; i < RE; i += 64u) tile[size_t(c) * RE + i] = src[i];
-            if (lane == 0) lmeta[c] = reinterpret_cast<const uint32_t*>(wsS + td.out_meta_off)[c];
-        }
-    }
-    __syncthreads();
-
-    // ---- the levels above the deepest tier, out of LDS
-    bool check_fail = false;
-    if (ft.listed != 0)
-        for (uint32_t q = 0; q < ft.n; ++q)
-            if (ft.row[q] != kNoRank && ilog2(ft.row[q] + 1u) < dlo) check_fail = true;
-    uint32_t uc_cnt = 0, tree_cnt = 0;
-    uint32_t im[kFusedItems];
-    for (int l = int(dlo) - 1; l >= 0; --l) {
-#pragma unroll
-        for (int i = 0; i < kFusedItems; ++i) {
-            if (il[i] == uint32_t(l)) {
-                const T* c0 = tile + size_t(2u * ip[i]) * RE + ie[i];
-                im[i] = fused_item<T, OP, WP>(g, ft, check_fail, ij[i], xs[i], c0, c0 + RE, lmeta[2u * ip[i]],
-                                              lmeta[2u * ip[i] + 1u], ie[i] == 0, uc_cnt, tree_cnt);
-            }
-        }
-        __syncthreads();                              // the level below has been read
-#pragma unroll
-        for (int i = 0; i < kFusedItems; ++i) {
-            if (il[i] == uint32_t(l)) {
-                T* dst = tile + size_t(ip[i]) * RE + ie[i];
-#pragma unroll
-                for (int k = 0; k < WP; ++k) dst[size_t(k) * g.E] = xs[i][k];
-                if (ie[i] == 0) lmeta[ip[i]] = im[i];
+                if (lane == 0) lmeta[c] = reinterpret_cast<const uint32_t*>(wsS + td.out_meta_off)[c];
             }
         }
         __syncthreads();
+
+        // ---- the levels above the deepest tier, out of LDS
+        bool check_fail = false;
+        if (ft.listed != 0)
+            for (uint32_t q = 0; q < ft.n; ++q)
+                if (ft.row[q] != kNoRank && ilog2(ft.row[q] + 1u) < dlo) check_fail = true;
+        uint32_t im[kFusedItems];
+        for (int l = int(dlo) - 1; l >= 0; --l) {
+#pragma unroll
+            for (int i = 0; i < kFusedItems; ++i) {
+                if (il[i] == uint32_t(l)) {
+                    const T* c0 = tile + size_t(2u * ip[i]) * REl + ie[i];
+                    im[i] = fused_item<T, OP, WP>(ft, check_fail, ij[i], xs[i], c0, c0 + REl, ne, lmeta[2u * ip[i]],
+                                                  lmeta[2u * ip[i] + 1u], pass == 0 && ie[i] == 0, uc_cnt, tree_cnt);
+                }
+            }
+            __syncthreads();                              // the level below has been read
+#pragma unroll
+            for (int i = 0; i < kFusedItems; ++i) {
+                if (il[i] == uint32_t(l)) {
+                    T* dst = tile + size_t(ip[i]) * REl + ie[i];
+#pragma unroll
+                    for (int k = 0; k < WP; ++k) dst[size_t(k) * ne] = xs[i][k];
+                    if (ie[i] == 0) lmeta[ip[i]] = im[i];
+                }
+            }
+            __syncthreads();
+        }
+        if (discard) continue;
+
+        // ---- Algorithm "reduce at the root": lowest-numbered child whose message is present and reports no failure;
+        // the root adds its own value iff that subtree holds no member of the root's group (children a .. f+1)
+        const uint32_t cm = lmeta[0];
+        const uint32_t okm = cm & ~(cm >> 16) & ((1u << WP) - 1u);
+        st = kStOk;
+        if (!ft.root_alive) st = kStRootFailed;
+        else if (okm == 0) st = kStNoCleanSubtree;
+        T* res = reinterpret_cast<T*>(A.result) + size_t(s) * g.E;
+        const T* vroot = reinterpret_cast<const T*>(wsS + A.vroot_off);       // left by the list kernel (short last group)
+        for (uint32_t el = tid; el < ne; el += nthr) {
+            const uint32_t ec = pass * ne + el;
+            if (ec >= g.E) continue;
+            T val = T(0);
+            if (st == kStOk) {
+                const uint32_t ks = uint32_t(__ffs(int(okm))) - 1u;
+                val = tile[size_t(ks) * ne + el];
+                if (ks + 1u >= g.a) {
+                    const T vr = g.a == 1 ? reinterpret_cast<const T*>(pay + size_t(root) * g.EB)[ec] : vroot[ec];
+                    val = comb<T, OP>(vr, val);
+                }
+            }
+            res[ec] = val;
+        }
     }
 
     // ---- message counters: one atomic per wavefront
@@ -350,30 +400,7 @@ __global__ void __launch_bounds__(kFusedMaxWaves * 64) __attribute__((amdgpu_wav
             if (tree_cnt) atomicAdd(&A.msgs[size_t(s) * A.nmsg + 1], (unsigned long long)tree_cnt);
         }
     }
-    if (discard) return;
-
-    // ---- Algorithm "reduce at the root": lowest-numbered child whose message is present and reports no failure;
-    // the root adds its own value iff that subtree holds no member of the root's group (children a .. f+1)
-    const uint32_t cm = lmeta[0];
-    const uint32_t okm = cm & ~(cm >> 16) & ((1u << WP) - 1u);
-    uint32_t st = kStOk;
-    if (!ft.root_alive) st = kStRootFailed;
-    else if (okm == 0) st = kStNoCleanSubtree;
-    T* res = reinterpret_cast<T*>(A.result) + size_t(s) * g.E;
-    const T* vroot = reinterpret_cast<const T*>(wsS + A.vroot_off);       // left by the list kernel (short last group)
-    for (uint32_t e = tid; e < g.E; e += nthr) {
-        T val = T(0);
-        if (st == kStOk) {
-            const uint32_t ks = uint32_t(__ffs(int(okm))) - 1u;
-            val = tile[size_t(ks) * g.E + e];
-            if (ks + 1u >= g.a) {
-                const T vr = g.a == 1 ? reinterpret_cast<const T*>(pay + size_t(root) * g.EB)[e] : vroot[e];
-                val = comb<T, OP>(vr, val);
-            }
-        }
-        res[e] = val;
-    }
-    if (tid == 0) A.status[s] = st;
+    if (!discard && tid == 0) A.status[s] = st;
 }
 
 #define FTRED_DECLARE_FUSED_LAUNCHER(NAME) \

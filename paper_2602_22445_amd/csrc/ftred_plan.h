@@ -25,6 +25,8 @@ struct ftred_plan_s {
     uint32_t use_unit;          // ... with eight lanes per subtree (one value per process)
     ftred::UnitLayout ul;
     uint32_t use_fused;         // ... and the levels above it and the root's choice in the same launch
+    uint32_t fused_only;        // rows too large for the LDS tiles: no tiers at all, the fused kernel and the register
+                                // walk of the listed subtrees do everything
     ftred::FusedLayout fl;
     uint32_t wave_gshift;       // workgroups of the wavefront tier per scenario = 2^wave_gshift
     ftred_plan_s* alt;          // the same plan on LDS tiles only, for runs that carry the lists of failed processes

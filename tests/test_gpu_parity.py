@@ -320,11 +320,14 @@ def test_sweeps_without_the_fused_kernel(ft, oracle, w):
 @pytest.mark.parametrize("P,f,E,dtype,op,S", [(1024, 3, 4096, 2, 0, 6), (300, 1, 8192, 0, 0, 4), (64, 2, 3000, 1, 1, 8),
                                               (5000, 4, 1000, 2, 0, 3)])
 def test_large_payloads(ft, oracle, w, P, f, E, dtype, op, S):
-    """Kilobytes per process (the bandwidth regime): a row no longer fits the LDS tiles, so the plan runs the tree
-    phase on the plain per-depth kernels; the validation holds up to 8192 values per process in LDS."""
+    """Kilobytes per process (the bandwidth regime): a row no longer fits the LDS tiles.  Where the tree is deep
+    enough one workgroup folds a whole scenario, block of value indices by block (no tiers of LDS tiles at all);
+    else the plan runs the tree phase on the plain per-depth kernels.  The validation holds up to 8192 values per
+    process in LDS."""
     seed = 31000 + P + E
     plan = ft.Plan(P, f, E, dtype, op)
-    assert plan.info.tiers == 0 and plan.info.shape == 2
+    assert plan.info.shape == 2
+    assert (plan.info.tiers, plan.info.fused) == ((0, 0) if P == 64 else (1, 1))
     Rred, Ratt = plan.info.rounds_reduce, plan.info.rounds_attempt
     x = _payload(w, seed, S, P, E, dtype)
     fr, fo = w.random_failure_sets(seed, S, P, f, inop_permille=500, rounds_per_attempt=Rred + 1)
