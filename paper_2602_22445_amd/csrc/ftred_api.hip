@@ -852,7 +852,8 @@ static int run_allreduce_impl(const char* who, const ftred_plan_t* plan, uint32_
     const uint32_t lds = bcast_lds_bytes(B);
     {
         TimedLaunch tl(FTRED_PH_BCAST, st);
-        hipLaunchKernelGGL(bcast_kernel, dim3(S * B.nchunks), dim3(kThreads), lds, st, B);
+        if (g.shape == kShapeBinary) hipLaunchKernelGGL(bcast_kernel<true>, dim3(S * B.nchunks), dim3(kThreads), lds, st, B);
+        else hipLaunchKernelGGL(bcast_kernel<false>, dim3(S * B.nchunks), dim3(kThreads), lds, st, B);
     }
     HIP_TRY(hipGetLastError());
     return FTRED_OK;

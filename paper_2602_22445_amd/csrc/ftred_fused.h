@@ -155,7 +155,8 @@ __device__ __forceinline__ uint32_t fused_item(const FailTab& ft, bool check_fai
     return sent | (flag << 16);
 }
 
-template <class T, int OP, int WP>
+// MULTI: more than one block of value indices (else the loop over the blocks is gone at compile time)
+template <class T, int OP, int WP, bool MULTI>
 __global__ void __launch_bounds__(kFusedMaxWaves * 64) __attribute__((amdgpu_waves_per_eu(WP <= 5 ? 3 : 2))) fused_tree_kernel(RunArgs A, FusedLayout fl)
 {
     extern __shared__ __align__(16) unsigned char smem[];
@@ -220,7 +221,8 @@ __global__ void __launch_bounds__(kFusedMaxWaves * 64) __attribute__((amdgpu_wav
     // count (one) the compiler does not know, with a value index that depends on the trip: as straight-line code, or
     // in a loop whose body does not change, the loads of a whole walk are requested ahead of it and the kernel needs
     // 300 to 500 registers instead of 160.
-    for (uint32_t pass = 0; pass < fl.passes; ++pass) {
+    const uint32_t npass = MULTI ? fl.passes : 1u;
+    for (uint32_t pass = 0; pass < npass; ++pass) {
         const uint32_t ecol_p = pass * ne + e;
         for (uint32_t c = tid; c < ncones; c += nthr) folded[c] = 0u;
         __syncthreads();                              // also: the failure table is there, the last block is done with the tile
@@ -416,12 +418,16 @@ FTRED_DECLARE_FUSED_LAUNCHER(f64_sum)
     template <int WP>                                                                                \
     static hipError_t fused_wp_##NAME(const RunArgs& A, const FusedLayout& fl, uint32_t grid, uint32_t lds, hipStream_t st) \
     {                                                                                                \
+        const void* fn = fl.passes > 1u ? reinterpret_cast<const void*>(&fused_tree_kernel<T, OP, WP, true>)  \
+                                        : reinterpret_cast<const void*>(&fused_tree_kernel<T, OP, WP, false>); \
         if (lds > 48u * 1024u) {      /* more dynamic LDS than a launch gets without asking */               \
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&fused_tree_kernel<T, OP, WP>),   \
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, int(lds));         \
+            hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, int(lds));     \
             if (e != hipSuccess) return e;                                                           \
         }                                                                                            \
-        hipLaunchKernelGGL((fused_tree_kernel<T, OP, WP>), dim3(grid), dim3(64u << fl.wshift), lds, st, A, fl); \
+        if (fl.passes > 1u)                                                                          \
+            hipLaunchKernelGGL((fused_tree_kernel<T, OP, WP, true>), dim3(grid), dim3(64u << fl.wshift), lds, st, A, fl); \
+        else                                                                                         \
+            hipLaunchKernelGGL((fused_tree_kernel<T, OP, WP, false>), dim3(grid), dim3(64u << fl.wshift), lds, st, A, fl); \
         return hipGetLastError();                                                                    \
     }                                                                                                \
     hipError_t launch_fused_##NAME(const RunArgs& A, const FusedLayout& fl, uint32_t grid, uint32_t lds, hipStream_t st) \

@@ -345,6 +345,8 @@ inline uint32_t bcast_lds_bytes(const BcastArgs& B)
     return uint32_t(sizeof(BcastFail)) + (B.chunk / 32u + 2u) * 4u;
 }
 
+// BIN: the default tree shape (binary heap inside a subtree), with its index arithmetic known at compile time
+template <bool BIN>
 __global__ void __launch_bounds__(kThreads) bcast_kernel(BcastArgs B)
 {
     extern __shared__ __align__(16) unsigned char smem[];
@@ -396,7 +398,7 @@ __global__ void __launch_bounds__(kThreads) bcast_kernel(BcastArgs B)
                         uint32_t fr = B.fail_round[size_t(s) * F + tid];
                         row = fdiv(vr - 1, g.divW);
                         idx = vr - 1 - row * g.W;
-                        uint32_t d = sh_depth(g, row);
+                        uint32_t d = BIN ? depth_of(row) : sh_depth(g, row);
                         ra = alive_at(fr, t0 + d) ? 1u : 0u;
                         bl = alive_at(fr, t0 + d + 1u) ? 0u : 1u;
                         // alive in correction round t iff t0 + D + t < fr
@@ -416,8 +418,8 @@ __global__ void __launch_bounds__(kThreads) bcast_kernel(BcastArgs B)
             if (used) {
                 const uint32_t j1 = j0 + nrows;            // one past the last row
                 hit = (nrows != 0 && row >= j0 && row < j1) || row == jx;
-                if (bl && g.shape != kShapeBinary) hit = true;       // rows below a position are ranges in the binary heap only
-                if (bl)
+                if (bl && !BIN) hit = true;       // rows below a position are ranges in the binary heap only
+                if (bl && BIN)
                     for (uint32_t k = 1; !hit; ++k) {
                         const uint32_t lo = ((row + 1u) << k) - 1u, hi = ((row + 2u) << k) - 2u;
                         if (lo >= g.M) break;
@@ -461,7 +463,7 @@ __global__ void __launch_bounds__(kThreads) bcast_kernel(BcastArgs B)
                         rowfail = true;
                         if (!bf.recv_alive[q]) H &= ~(1u << bf.idx[q]);
                         if (bf.blocked[q]) blockedm |= 1u << bf.idx[q];
-                    } else if (bf.blocked[q] && bf.idx[q] < nk && sh_is_proper_ancestor(g, rq, j)) {
+                    } else if (bf.blocked[q] && bf.idx[q] < nk && (BIN ? is_proper_ancestor(rq, j) : sh_is_proper_ancestor(g, rq, j))) {
                         H &= ~(1u << bf.idx[q]);   // an ancestor in the same subtree did not forward
                     }
                 }
@@ -469,7 +471,7 @@ __global__ void __launch_bounds__(kThreads) bcast_kernel(BcastArgs B)
             if (owner) {
                 // tree-down messages: a holder alive in its send round sends to each child
                 const uint32_t snd = H & tmask & ~blockedm;
-                if (g.shape == kShapeBinary) {
+                if constexpr (BIN) {
                     const uint32_t jc = 2u * j + 1u;
                     const uint32_t m0 = jc < g.M - 1u ? 0xFFFFu : (jc == g.M - 1u ? (1u << g.nlast) - 1u : 0u);
                     const uint32_t m1 = jc + 1u < g.M - 1u ? 0xFFFFu : (jc + 1u == g.M - 1u ? (1u << g.nlast) - 1u : 0u);
