@@ -539,7 +539,10 @@ static int launch_tiers(const ftred_plan_t* plan, RunArgs& A, uint32_t S, uint32
                 // the scenario folds all the others and then everything above them, down to the root's choice
                 const uint32_t lds = (1u << plan->wl.slot_shift) * kWaveRows * uint32_t(sizeof(RowInfo));
                 HIP_TRY(dispatch_wave_list(plan, A, uint32_t(wgs), lds, st));
-                HIP_TRY(dispatch_fused(plan, A, S + extra, fused_lds_bytes(plan->g, plan->fl, plan->tiers[0].dlo), st));
+                if ((uint64_t(S) + extra) * plan->fl.passes >= (uint64_t(1) << 31))
+                    return fail(FTRED_EUNSUPPORTED, "S = %u scenarios need too many workgroups; split the batch", S);
+                HIP_TRY(dispatch_fused(plan, A, (S + extra) * plan->fl.passes,
+                                       fused_lds_bytes(plan->g, plan->fl, plan->tiers[0].dlo), st));
                 return FTRED_OK;
             }
             HIP_TRY(dispatch_wave(plan, A, (S + extra) << plan->wave_gshift, st));

@@ -41,7 +41,8 @@ struct FusedLayout {
     uint32_t ne, slot_shift, nact;   // lanes of a wavefront = 2^slot_shift sibling subtrees x ne value indices
     uint32_t group_shift;            // a wavefront walks through 2^group_shift groups of subtrees
     uint32_t wshift;                 // wavefronts per workgroup = 2^wshift
-    uint32_t passes;                 // blocks of ne value indices: the workgroup folds the whole tree once per block
+    uint32_t passes;                 // blocks of ne value indices: a workgroup per scenario and block
+    FastDiv div_passes;
     uint32_t one;                    // always 1: trip count of the loop around the walk (see the kernel)
     FastDiv div_ne;
     uint32_t ok;                     // the plan can use the fused kernel
@@ -62,6 +63,7 @@ inline FusedLayout make_fused_layout(const Geom& g, uint32_t dlo)
         while ((2u << sh) <= slots && sh < dlo) ++sh;
         f.ne = ne; f.slot_shift = sh; f.nact = (1u << sh) * ne;
         f.passes = (g.E + ne - 1u) / ne;
+        f.div_passes = make_fastdiv(f.passes);
         f.one = 1;
         f.div_ne = make_fastdiv(ne);
         const uint32_t rest = dlo - sh;               // log2 of the groups of subtrees per scenario
@@ -155,8 +157,7 @@ __device__ __forceinline__ uint32_t fused_item(const FailTab& ft, bool check_fai
     return sent | (flag << 16);
 }
 
-// MULTI: more than one block of value indices (else the loop over the blocks is gone at compile time)
-template <class T, int OP, int WP, bool MULTI>
+template <class T, int OP, int WP>
 __global__ void __launch_bounds__(kFusedMaxWaves * 64) __attribute__((amdgpu_waves_per_eu(WP <= 5 ? 3 : 2))) fused_tree_kernel(RunArgs A, FusedLayout fl)
 {
     extern __shared__ __align__(16) unsigned char smem[];
@@ -174,8 +175,12 @@ __global__ void __launch_bounds__(kFusedMaxWaves * 64) __attribute__((amdgpu_wav
     uint32_t* lmeta = reinterpret_cast<uint32_t*>(smem + sizeof(FailTab) + (size_t(REl) * g.esz << dlo));
     uint32_t* folded = lmeta + ncones;
 
-    // ---- which scenario, which root
-    const uint32_t sv = blockIdx.x;                  // scenario, or S + retry entry
+    // ---- which scenario, which block of value indices, which root
+    uint32_t sv = blockIdx.x, pass = 0;              // scenario, or S + retry entry
+    if (fl.passes > 1u) {
+        sv = fdiv(blockIdx.x, fl.div_passes);
+        pass = blockIdx.x - sv * fl.passes;
+    }
     uint32_t s = sv, root = 0, base = 0;
     bool discard = false;
     unsigned char* wsS;
@@ -216,16 +221,15 @@ __global__ void __launch_bounds__(kFusedMaxWaves * 64) __attribute__((amdgpu_wav
     uint32_t uc_cnt = 0, tree_cnt = 0;
     uint32_t st = kStOk;
 
-    // One block of ne value indices after the other (one block unless a process holds more than 64 values): the
-    // whole tree is folded for the block, its top rows in LDS.  The walk itself sits in a loop of its own whose trip
-    // count (one) the compiler does not know, with a value index that depends on the trip: as straight-line code, or
-    // in a loop whose body does not change, the loads of a whole walk are requested ahead of it and the kernel needs
-    // 300 to 500 registers instead of 160.
-    const uint32_t npass = MULTI ? fl.passes : 1u;
-    for (uint32_t pass = 0; pass < npass; ++pass) {
+    // The workgroup folds the whole tree for ITS block of ne value indices (one block unless a process holds more
+    // than 64 values; the blocks of a scenario are workgroups of their own), the top rows in LDS.  The walk itself
+    // sits in a loop whose trip count (one) the compiler does not know, with a value index that depends on the
+    // trip: as straight-line code, or in a loop whose body does not change, the loads of a whole walk are
+    // requested ahead of it and the kernel needs 300 to 500 registers instead of 160.
+    {
         const uint32_t ecol_p = pass * ne + e;
         for (uint32_t c = tid; c < ncones; c += nthr) folded[c] = 0u;
-        __syncthreads();                              // also: the failure table is there, the last block is done with the tile
+        __syncthreads();                              // also: the failure table is there
 
         // ---- the deepest tier: every wavefront walks through its groups of subtrees (as wave_tier_kernel does)
         for (uint32_t gi = 0; gi < (1u << fl.group_shift); ++gi) {
@@ -363,8 +367,7 @@ __global__ void __launch_bounds__(kFusedMaxWaves * 64) __attribute__((amdgpu_wav
             }
             __syncthreads();
         }
-        if (discard) continue;
-
+        if (!discard) {
         // ---- Algorithm "reduce at the root": lowest-numbered child whose message is present and reports no failure;
         // the root adds its own value iff that subtree holds no member of the root's group (children a .. f+1)
         const uint32_t cm = lmeta[0];
@@ -388,9 +391,10 @@ __global__ void __launch_bounds__(kFusedMaxWaves * 64) __attribute__((amdgpu_wav
             }
             res[ec] = val;
         }
+        }
     }
 
-    // ---- message counters: one atomic per wavefront
+    // ---- message counters: one atomic per wavefront (the workgroup of the first block counts)
     if (A.msgs) {
 #pragma unroll
         for (int d = 32; d >= 1; d >>= 1) {
@@ -402,7 +406,7 @@ __global__ void __launch_bounds__(kFusedMaxWaves * 64) __attribute__((amdgpu_wav
             if (tree_cnt) atomicAdd(&A.msgs[size_t(s) * A.nmsg + 1], (unsigned long long)tree_cnt);
         }
     }
-    if (!discard && tid == 0) A.status[s] = st;
+    if (!discard && tid == 0 && pass == 0) A.status[s] = st;
 }
 
 #define FTRED_DECLARE_FUSED_LAUNCHER(NAME) \
@@ -418,16 +422,12 @@ FTRED_DECLARE_FUSED_LAUNCHER(f64_sum)
     template <int WP>                                                                                \
     static hipError_t fused_wp_##NAME(const RunArgs& A, const FusedLayout& fl, uint32_t grid, uint32_t lds, hipStream_t st) \
     {                                                                                                \
-        const void* fn = fl.passes > 1u ? reinterpret_cast<const void*>(&fused_tree_kernel<T, OP, WP, true>)  \
-                                        : reinterpret_cast<const void*>(&fused_tree_kernel<T, OP, WP, false>); \
         if (lds > 48u * 1024u) {      /* more dynamic LDS than a launch gets without asking */               \
-            hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, int(lds));     \
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&fused_tree_kernel<T, OP, WP>),   \
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, int(lds));         \
             if (e != hipSuccess) return e;                                                           \
         }                                                                                            \
-        if (fl.passes > 1u)                                                                          \
-            hipLaunchKernelGGL((fused_tree_kernel<T, OP, WP, true>), dim3(grid), dim3(64u << fl.wshift), lds, st, A, fl); \
-        else                                                                                         \
-            hipLaunchKernelGGL((fused_tree_kernel<T, OP, WP, false>), dim3(grid), dim3(64u << fl.wshift), lds, st, A, fl); \
+        hipLaunchKernelGGL((fused_tree_kernel<T, OP, WP>), dim3(grid), dim3(64u << fl.wshift), lds, st, A, fl); \
         return hipGetLastError();                                                                    \
     }                                                                                                \
     hipError_t launch_fused_##NAME(const RunArgs& A, const FusedLayout& fl, uint32_t grid, uint32_t lds, hipStream_t st) \

@@ -282,7 +282,8 @@ __device__ __forceinline__ void wave_list_entries(const RunArgs& A, const WaveLa
 
     const bool any_deep = __ballot(valid && deep) != 0ull;
     uint32_t uc_cnt = 0, tree_cnt = 0;
-    for (uint32_t pass = 0; pass < wl.passes; ++pass) {
+    // the blocks of value indices of an entry are workgroups of their own (grid dimension y)
+    for (uint32_t pass = blockIdx.y; pass < wl.passes; pass += gridDim.y) {
         const uint32_t ecol = pass * wl.ne + e;
         if (valid && ecol < g.E) {
             T out[WP];
@@ -348,7 +349,8 @@ FTRED_DECLARE_WAVE_LIST_LAUNCHER(f64_sum)
     template <int WP>                                                                               \
     static hipError_t wave_list_wp_##NAME(const RunArgs& A, const WaveLayout& wl, uint32_t grid, uint32_t lds, hipStream_t st) \
     {                                                                                               \
-        hipLaunchKernelGGL((wave_list_kernel<T, OP, WP>), dim3(grid), dim3(kWaveThreads), lds, st, A, wl); \
+        hipLaunchKernelGGL((wave_list_kernel<T, OP, WP>), dim3(grid, wl.passes < 65535u ? wl.passes : 65535u),  \
+                           dim3(kWaveThreads), lds, st, A, wl);                                       \
         return hipGetLastError();                                                                   \
     }                                                                                               \
     hipError_t launch_wave_list_##NAME(const RunArgs& A, const WaveLayout& wl, uint32_t grid, uint32_t lds, hipStream_t st) \
