@@ -489,6 +489,27 @@ static void clear_inboxes(sim_t *s)
 }
 
 /* ------------------------------------------------------------------ */
+/* who exchanges with whom inside a group (R2, R7)                      */
+
+/* up-correction round r (1 <= r <= group size - 1): the mate v sends its input to, and the mate v hears from */
+static uint32_t uc_target(const topo_t *t, uint32_t v, uint32_t r)
+{
+    const uint32_t g = (uint32_t)t->group[v], gs = t->gsize[g];
+    return t->gmembers[(size_t)g * (t->f + 2) + (t->gpos[v] + r) % gs];
+}
+
+static uint32_t uc_source(const topo_t *t, uint32_t v, uint32_t r)
+{
+    const uint32_t g = (uint32_t)t->group[v], gs = t->gsize[g];
+    return t->gmembers[(size_t)g * (t->f + 2) + (t->gpos[v] + gs - r) % gs];
+}
+
+/* correction round tt of the broadcast: the same rotation here (R7); the one place to change for another
+   correction scheme, e.g. the corrected-tree broadcast of the companion paper */
+static uint32_t correction_target(const topo_t *t, uint32_t v, uint32_t tt) { return uc_target(t, v, tt); }
+static uint32_t correction_source(const topo_t *t, uint32_t v, uint32_t tt) { return uc_source(t, v, tt); }
+
+/* ------------------------------------------------------------------ */
 /* one reduce to virtual rank 0, global rounds base+1 .. base+f+D        */
 /* returns the per-operation status; result (bytes) valid when OK        */
 
@@ -518,10 +539,8 @@ static int run_reduce(sim_t *s, uint32_t base, void *result)
                 /* up-correction round t = r */
                 if (!s->disable_uc && t->group[v] >= 0) {
                     uint32_t g = (uint32_t)t->group[v], gs = t->gsize[g];
-                    if (r <= gs - 1) {
-                        uint32_t mate = t->gmembers[(size_t)g * gcap + (t->gpos[v] + r) % gs];
-                        net_send(s, MSG_UC, v, mate, s->input + (size_t)v * s->bytes, 0);
-                    }
+                    if (r <= gs - 1)
+                        net_send(s, MSG_UC, v, uc_target(t, v, r), s->input + (size_t)v * s->bytes, 0);
                 }
             } else if (v != 0 && r == f + 1 + t->height[v]) {
                 /* tree phase: all children had their turn; fold and send up */
@@ -567,7 +586,7 @@ static int run_reduce(sim_t *s, uint32_t base, void *result)
                     /* the member that sends to v in this round (R2) sent nothing */
                     uint32_t g = (uint32_t)t->group[v], gs = t->gsize[g];
                     if (r <= gs - 1) {
-                        uint32_t mate = t->gmembers[(size_t)g * gcap + (t->gpos[v] + gs - r) % gs];
+                        uint32_t mate = uc_source(t, v, r);
                         monitor_query(s, mate, now);
                         if (s->track_info) {
                             info_append(s, v, mate);
@@ -632,7 +651,7 @@ static int run_reduce(sim_t *s, uint32_t base, void *result)
 static void run_broadcast(sim_t *s, uint32_t base, const void *value)
 {
     const topo_t *t = s->t;
-    const uint32_t P = t->P, f = t->f, gcap = t->f + 2;
+    const uint32_t P = t->P, f = t->f;
     uint32_t r, v, c;
     clear_inboxes(s);
     memset(s->has, 0, P);
@@ -657,10 +676,8 @@ static void run_broadcast(sim_t *s, uint32_t base, const void *value)
                 /* correction round tt: every holder sends to one group mate */
                 uint32_t tt = r - t->D;
                 uint32_t g = (uint32_t)t->group[v], gs = t->gsize[g];
-                if (tt <= gs - 1) {
-                    uint32_t mate = t->gmembers[(size_t)g * gcap + (t->gpos[v] + tt) % gs];
-                    net_send(s, MSG_BCORR, v, mate, s->held + (size_t)v * s->bytes, 0);
-                }
+                if (tt <= gs - 1)
+                    net_send(s, MSG_BCORR, v, correction_target(t, v, tt), s->held + (size_t)v * s->bytes, 0);
             }
         }
         net_deliver(s, now);
@@ -676,7 +693,7 @@ static void run_broadcast(sim_t *s, uint32_t base, const void *value)
                 uint32_t tt = r - t->D;
                 uint32_t g = (uint32_t)t->group[v], gs = t->gsize[g];
                 if (tt <= gs - 1) {
-                    uint32_t mate = t->gmembers[(size_t)g * gcap + (t->gpos[v] + gs - tt) % gs];
+                    uint32_t mate = correction_source(t, v, tt);
                     if (!inbox_peek(s, v, MSG_BCORR, mate)) monitor_query(s, mate, now);
                 }
             }

@@ -117,7 +117,7 @@ __device__ __forceinline__ uint32_t fused_item(const FailTab& ft, bool check_fai
         for (int i = 0; i < WP; ++i) {
             T acc = x[i];
 #pragma unroll
-            for (int t = 1; t < WP; ++t) acc = comb<T, OP>(acc, x[(i - t + WP) % WP]);
+            for (int t = 1; t < WP; ++t) acc = comb<T, OP>(acc, x[exchange_source(uint32_t(i), uint32_t(t), uint32_t(WP))]);
             v[i] = acc;
         }
     } else {
@@ -126,7 +126,7 @@ __device__ __forceinline__ uint32_t fused_item(const FailTab& ft, bool check_fai
             T acc = x[i];
 #pragma unroll
             for (int t = 1; t < WP; ++t) {
-                const int w = (i - t + WP) % WP;
+                const int w = int(exchange_source(uint32_t(i), uint32_t(t), uint32_t(WP)));
                 if (uint32_t(t) <= uint32_t((tl >> (4 * w)) & 15ull)) acc = comb<T, OP>(acc, x[w]);
             }
             v[i] = acc;

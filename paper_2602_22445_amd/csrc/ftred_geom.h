@@ -148,6 +148,19 @@ FT_HD uint32_t group_size(const Geom& g, uint32_t j)
     return (j == g.M - 1 && g.a > 1) ? g.a : g.W;
 }
 
+// Who exchanges with whom inside a group of gs members (up-correction of the reduce, correction rounds of the
+// broadcast; sections "Reduce / Algorithm" and "Allreduce"): in round t = 1 .. gs - 1 member i sends to member
+// exchange_target and hears from member exchange_source; the message of member w is due at member i in round
+// exchange_round.  Every kernel takes the pairing from here, so another correction scheme replaces these four.
+FT_HD constexpr uint32_t exchange_target(uint32_t i, uint32_t t, uint32_t gs) { return (i + t) % gs; }
+FT_HD constexpr uint32_t exchange_source(uint32_t i, uint32_t t, uint32_t gs) { return (i + gs - t) % gs; }
+FT_HD constexpr uint32_t exchange_round(uint32_t w, uint32_t i, uint32_t gs) { return w < i ? i - w : i + gs - w; }
+// the same for a whole group: bit i of the result is set iff the member that sends to i in round t is in `senders`
+FT_HD constexpr uint32_t exchange_targets(uint32_t senders, uint32_t t, uint32_t gs, uint32_t full)
+{
+    return ((senders << t) | (senders >> (gs - t))) & full;
+}
+
 // height of process (subtree i, position j) above the leaves of its subtree:
 // the largest h with (j+1) * 2^h <= size of the subtree
 FT_HD uint32_t height_of(const Geom& g, uint32_t i, uint32_t j)

@@ -261,12 +261,12 @@ __device__ __forceinline__ void process_item(const Geom& g, const FailTab& ft, T
             T acc = x[i];
 #pragma unroll
             for (int w = i - 1; w >= 0; --w) {
-                uint32_t t = uint32_t(i - w);
+                const uint32_t t = exchange_round(uint32_t(w), uint32_t(i), gs);
                 if (t <= uint32_t((tl >> (4 * w)) & 15ull)) acc = comb<T, OP>(acc, x[w]);
             }
 #pragma unroll
             for (int w = WP - 1; w > i; --w) {
-                uint32_t t = uint32_t(i) + gs - uint32_t(w);
+                const uint32_t t = exchange_round(uint32_t(w), uint32_t(i), gs);
                 if (uint32_t(w) < gs && t <= uint32_t((tl >> (4 * w)) & 15ull)) acc = comb<T, OP>(acc, x[w]);
             }
             v[i] = acc;
@@ -350,7 +350,7 @@ __device__ __forceinline__ void process_lists(const Geom& g, const FailTab& ft, 
             for (uint32_t q = 0; q < ft.n; ++q) {
                 if (ft.row[q] != j || ft.idx[q] == i) continue;
                 const uint32_t w = ft.idx[q];
-                const uint32_t t = w < i ? i - w : i + gs - w;
+                const uint32_t t = exchange_round(w, i, gs);
                 if (t > ft.uc[q]) mk |= 1u << q;
             }
         }

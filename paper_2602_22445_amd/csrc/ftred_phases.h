@@ -271,7 +271,7 @@ __global__ void __launch_bounds__(256) detect_kernel(Geom g, uint32_t kind /* 0 
                 const uint32_t r0 = phase == 0 ? base : base + g.Rred + g.D;
                 for (uint32_t t = 1; t <= g.f && t + 1u <= gs && !det; ++t) {
                     const uint32_t now = r0 + t;
-                    if (!alive_at(fq, now) && listed_alive(g, fr, fo, relabel(member((i + t) % gs), root), now)) det = true;
+                    if (!alive_at(fq, now) && listed_alive(g, fr, fo, relabel(member(exchange_target(i, t, gs)), root), now)) det = true;
                 }
             }
             if (vq != 0 && !det) {
@@ -495,8 +495,7 @@ __global__ void __launch_bounds__(kThreads) bcast_kernel(BcastArgs B)
                             if (bf.row[q] == j && bf.corr[q] < tt) am &= ~(1u << bf.idx[q]);
                     const uint32_t snd = H & am;
                     if (owner) my_corr += uint32_t(__popc(snd));
-                    const uint32_t rot = ((snd << tt) | (snd >> (gs - tt))) & full;
-                    H |= rot & am;
+                    H |= exchange_targets(snd, tt, gs, full) & am;
                 }
             }
             // record the holders among the row's tree members, by physical rank

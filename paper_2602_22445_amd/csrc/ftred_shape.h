@@ -106,10 +106,12 @@ __global__ void __launch_bounds__(256) shape_level_kernel(RunArgs A, ShapeLevel 
             T acc = x[i];
 #pragma unroll
             for (int w = i - 1; w >= 0; --w)
-                if (uint32_t(i - w) <= uint32_t((tl >> (4 * w)) & 15ull)) acc = comb<T, OP>(acc, x[w]);
+                if (exchange_round(uint32_t(w), uint32_t(i), gs) <= uint32_t((tl >> (4 * w)) & 15ull))
+                    acc = comb<T, OP>(acc, x[w]);
 #pragma unroll
             for (int w = WP - 1; w > i; --w)
-                if (uint32_t(w) < gs && uint32_t(i) + gs - uint32_t(w) <= uint32_t((tl >> (4 * w)) & 15ull))
+                if (uint32_t(w) < gs &&
+                    exchange_round(uint32_t(w), uint32_t(i), gs) <= uint32_t((tl >> (4 * w)) & 15ull))
                     acc = comb<T, OP>(acc, x[w]);
             v[i] = acc;
         }

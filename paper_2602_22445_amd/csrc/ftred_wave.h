@@ -185,7 +185,7 @@ struct SubtreeWalk {
         for (int i = 0; i < WP; ++i) {
             T acc = xq[N % PD][i];
 #pragma unroll
-            for (int t = 1; t < WP; ++t) acc = comb<T, OP>(acc, xq[N % PD][(i - t + WP) % WP]);
+            for (int t = 1; t < WP; ++t) acc = comb<T, OP>(acc, xq[N % PD][exchange_source(uint32_t(i), uint32_t(t), uint32_t(WP))]);
             v[i] = acc;
         }
         if constexpr (N + PD < NR) issue<N + PD>();            // the ring slot is free again

@@ -126,12 +126,12 @@ struct GeneralWalk {
 #pragma unroll
             for (int w = i - 1; w >= 0; --w) {                 // rounds 1 .. i
                 const T sum = comb<T, OP>(acc, xq[N % PD][w]);
-                acc = uint32_t(i - w) <= uint32_t((tl >> (4 * w)) & 15ull) ? sum : acc;
+                acc = exchange_round(uint32_t(w), uint32_t(i), gs) <= uint32_t((tl >> (4 * w)) & 15ull) ? sum : acc;
             }
 #pragma unroll
             for (int w = WP - 1; w > i; --w) {                 // rounds i + 1 .. gs - 1
                 const T sum = comb<T, OP>(acc, xq[N % PD][w]);
-                const uint32_t t = uint32_t(i) + gs - uint32_t(w);
+                const uint32_t t = exchange_round(uint32_t(w), uint32_t(i), gs);
                 acc = (uint32_t(w) < gs && t <= uint32_t((tl >> (4 * w)) & 15ull)) ? sum : acc;
             }
             v[i] = acc;

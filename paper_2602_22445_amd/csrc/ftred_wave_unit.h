@@ -76,7 +76,7 @@ struct UnitRow {
         for (int i = 0; i < WP; ++i) {
             T acc = r[i];
 #pragma unroll
-            for (int t = 1; t < WP; ++t) acc = comb<T, OP>(acc, r[(i - t + WP) % WP]);
+            for (int t = 1; t < WP; ++t) acc = comb<T, OP>(acc, r[exchange_source(uint32_t(i), uint32_t(t), uint32_t(WP))]);
             v[i] = acc;
         }
     }
