@@ -105,7 +105,11 @@ typedef struct ftred_info {
 /* Create a plan for P processes, failure bound f, `elems` values of `dtype` per
    process and reduction `op`.  Requires P >= f + 2 (the root needs f+1 children:
    definition of the I(f)-tree), f <= FTRED_MAX_F, elems >= 1, P * elems * size
-   < 2^31 bytes, no BOR on FTRED_F64.  flags: 0 for the defaults; tuning knobs of
+   < 2^31 bytes, no BOR on FTRED_F64.  Payloads of more than 64 values per process
+   run as blocks of value indices with one failure pattern; a payload whose
+   up-correction group fits no LDS tile where the tree is too shallow for the
+   register kernels runs on the plain per-depth kernels of the other tree shapes
+   (below).  flags: 0 for the defaults; tuning knobs of
    the tree kernels otherwise: bits 0..7 = LDS budget in KiB of the deepest tier's
    tiles (4..24), bits 8..11 = 1 + log2 of the tiles one workgroup walks through,
    bit 12 = LDS-tile kernel also for the deepest tier (the default there is a

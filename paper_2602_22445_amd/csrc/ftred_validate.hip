@@ -129,7 +129,7 @@ __global__ void __launch_bounds__(256) val_partial_kernel(ValArgs A)
 
     // a chunk without listed ranks: every process must hold the result; the words of
     // the bitmap are checked here, once (chunks start at multiples of 32 ranks)
-    if (check_holders && hb && !chunk_listed) {
+    if (check_holders && hb && !chunk_listed && blockIdx.y == 0) {
         const uint32_t w0 = c0 >> 5, nw = (c1 - c0 + 31u) >> 5;
         if (tid < nw) {
             const uint32_t left = c1 - c0 - tid * 32u;
@@ -142,8 +142,9 @@ __global__ void __launch_bounds__(256) val_partial_kernel(ValArgs A)
     const uint32_t cols = EV < 256u ? EV : 256u;
     const uint32_t ngr = 256u / cols;
     const uint32_t col = tid % cols, gr = tid / cols;
-    for (uint32_t e0 = 0; e0 < EV; e0 += cols) {         // same trip count for every thread
-        const uint32_t ev = e0 + col;
+    {
+        // more than 256 columns: the blocks of 256 are workgroups of their own (second grid dimension)
+        const uint32_t ev = blockIdx.y * cols + col;
         const uint32_t e = ev * uint32_t(V);
         const bool active = ev < EV && gr < ngr;
         T acc[V];
@@ -314,10 +315,23 @@ __global__ void __launch_bounds__(256) val_final_kernel(ValArgs A)
     for (uint32_t e = tid; e < g.E; e += nthr) {
         T acc = T(0);
         double sa = 0.0;
-        for (uint32_t c = 0; c < A.nchunks; ++c) {
-            const size_t o = (size_t(s) * A.nchunks + c) * g.E + e;
-            acc = vcomb<T, OP>(acc, reinterpret_cast<const T*>(A.partial)[o * (8 / sizeof(T))]);
-            sa += A.scale[o];
+        constexpr uint32_t kAhead = 8;                   // loads in flight; folded in chunk order all the same
+        for (uint32_t c0 = 0; c0 < A.nchunks; c0 += kAhead) {
+            T pv[kAhead];
+            double ps[kAhead];
+#pragma unroll
+            for (uint32_t u = 0; u < kAhead; ++u) {
+                const uint32_t c = c0 + u < A.nchunks ? c0 + u : A.nchunks - 1u;
+                const size_t o = (size_t(s) * A.nchunks + c) * g.E + e;
+                pv[u] = reinterpret_cast<const T*>(A.partial)[o * (8 / sizeof(T))];
+                ps[u] = A.scale[o];
+            }
+#pragma unroll
+            for (uint32_t u = 0; u < kAhead; ++u) {
+                if (c0 + u >= A.nchunks) continue;
+                acc = vcomb<T, OP>(acc, pv[u]);
+                sa += ps[u];
+            }
         }
         base[e] = acc;
         scale[e] = sa;
@@ -328,6 +342,28 @@ __global__ void __launch_bounds__(256) val_final_kernel(ValArgs A)
         const uint32_t k = s_ninop;
         const uint32_t nsub = 1u << k;
         uint32_t found = 0;
+        if (g.E >= 64u) {
+            // many value indices: a wavefront per subset, its lanes side by side over the value indices; a wrong
+            // subset is dropped at the first 64 values that do not agree
+            const uint32_t lane = tid & 63u, nw = nthr >> 6;
+            for (uint32_t sub = tid >> 6; sub < nsub && !found; sub += nw) {
+                bool all = true;
+                for (uint32_t e0 = 0; e0 < g.E && all; e0 += 64u) {
+                    const uint32_t e = e0 + lane;
+                    bool ok = true;
+                    if (e < g.E) {
+                        T cand = base[e];
+                        for (uint32_t b = 0; b < k; ++b)
+                            if ((sub >> b) & 1u) cand = vcomb<T, OP>(cand, x[size_t(s_inop[b]) * g.E + e]);
+                        const T r = res[e];
+                        if constexpr (std::is_floating_point<T>::value) ok = fabs(double(r) - double(cand)) <= 1e-12 * scale[e];
+                        else ok = r == cand;
+                    }
+                    all = __all(ok) != 0;
+                }
+                if (all) found = 1;
+            }
+        } else
         for (uint32_t sub = tid; sub < nsub && !found; sub += nthr) {
             bool all = true;
             for (uint32_t e = 0; e < g.E && all; ++e) {
@@ -367,8 +403,12 @@ hipError_t launch_validate(const ValArgs& A, hipStream_t st)
         const bool wide = A.g.E % uint32_t(VMAX) == 0 && A.scen_stride_bytes % 16u == 0 &&
                           reinterpret_cast<uintptr_t>(A.payload) % 16u == 0 &&
                           (!A.out || reinterpret_cast<uintptr_t>(A.out) % 16u == 0);
-        if (wide) hipLaunchKernelGGL((val_partial_kernel<T, OP, VMAX>), dim3(A.S * A.nchunks), dim3(256), 0, st, A);
-        else hipLaunchKernelGGL((val_partial_kernel<T, OP, 1>), dim3(A.S * A.nchunks), dim3(256), 0, st, A);
+        if (wide) {
+            const uint32_t ev = A.g.E / uint32_t(VMAX);
+            hipLaunchKernelGGL((val_partial_kernel<T, OP, VMAX>), dim3(A.S * A.nchunks, (ev + 255u) / 256u), dim3(256), 0, st, A);
+        } else {
+            hipLaunchKernelGGL((val_partial_kernel<T, OP, 1>), dim3(A.S * A.nchunks, (A.g.E + 255u) / 256u), dim3(256), 0, st, A);
+        }
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
