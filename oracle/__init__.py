@@ -191,6 +191,31 @@ def reduce_batch(P, f, payload, dtype, op, S, root=None, fail_rank=(), fail_roun
     return dict(result=result, status=status, msgs=msgs, threads=used, detected=det)
 
 
+NEVER = 0xFFFFFFFFFFFFFFFF
+
+
+def reduce_timed_batch(P, f, payload, dtype, op, S, t_msg, t_timeout, root=None, fail_rank=(), fail_round=(), threads=0,
+                       shape=BINARY, want_proc=True):
+    """S independent reduces with the event-driven times of every process (``oracle_reduce_timed_batch``):
+    reduce_batch's outputs plus t_done[S] and t_proc[S][P] (NEVER = did not get there)."""
+    lib = _load()
+    npdt, x, elems, stride, fr, fo, nfail = _batch_common(P, payload, dtype, S, fail_rank, fail_round)
+    rt = None if root is None else np.ascontiguousarray(np.asarray(root, dtype=np.uint32).reshape(S))
+    result = np.zeros((S, elems), npdt)
+    status = np.zeros(S, np.uint32)
+    msgs = np.zeros((S, 2), np.uint64)
+    t_done = np.zeros(S, np.uint64)
+    t_proc = np.zeros((S, P), np.uint64) if want_proc else None
+    used = lib.oracle_reduce_timed_batch(ctypes.c_uint32(P), ctypes.c_uint32(f), ctypes.c_uint32(elems),
+                                         ctypes.c_int(dtype), ctypes.c_int(op), ctypes.c_int(shape), ctypes.c_uint32(S),
+                                         _p(rt), _p(x), ctypes.c_uint64(stride), ctypes.c_uint32(nfail), _p(fr), _p(fo),
+                                         ctypes.c_uint64(t_msg), ctypes.c_uint64(t_timeout),
+                                         _p(result), _p(status), _p(msgs), _p(t_done), _p(t_proc), ctypes.c_int(threads))
+    if used < 0:
+        raise ValueError("oracle_reduce_timed_batch: invalid arguments")
+    return dict(result=result, status=status, msgs=msgs, threads=used, t_done=t_done, t_proc=t_proc)
+
+
 def allreduce_batch(P, f, payload, dtype, op, S, fail_rank=(), fail_round=(), threads=0,
                     want_has=True, want_out=False, shape=BINARY, want_detected=False):
     """S independent allreduces; payload[S][P][elems] or [P][elems] (shared).  shape, want_detected: as reduce_batch."""

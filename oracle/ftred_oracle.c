@@ -69,6 +69,25 @@
  *      has failed.  A round COSTS as many message steps as the busiest process
  *      sends or receives messages in it in the failure-free run (one port per
  *      process).  Both are counted literally by the simulation.
+ *   R9 event-driven times of the reduce (section "Related work", last
+ *      paragraph: a process runs its phases one after the other without regard
+ *      to the progress of the others; section "Up-Correction", last paragraph,
+ *      and the liveness part of the proof in "Reduce / Properties": a receive
+ *      from a failed sender ends by a time-out and the monitor's confirmation,
+ *      and is retried while the monitor says the sender lives).  Every process
+ *      starts at time 0 and has a clock of its own.  A send takes t_msg of the
+ *      sender's time and the message is at the receiver when the send ends.  A
+ *      receive ends at once if the message is there, at its arrival otherwise;
+ *      if the sender has stopped without sending it, the receiver asks the
+ *      monitor after every t_timeout of waiting and gives up at the first such
+ *      moment that lies after the moment the sender stopped.  A process stops
+ *      when it reaches the first step whose round (R1, R4) is >= its
+ *      fail_round; what is sent and received, hence every value, status and
+ *      message count, is that of the round model, because a process awaits
+ *      named senders in a fixed order (R2, R5) and never whoever comes first.
+ *      The simulation stamps these times onto its round loop (entry point
+ *      oracle_reduce_timed_batch); event_sim.py beside this file runs the same
+ *      model as a discrete-event simulation with blocking receives and pins it.
  *
  * parity pins: every function of this file is pinned by tests (worked example
  * of the paper, brute force over all failure subsets against the survivor
@@ -85,6 +104,7 @@
 #endif
 
 #define ORACLE_NO_RANK 0xFFFFFFFFu
+#define ORACLE_NEVER UINT64_MAX
 
 enum { OR_I64 = 0, OR_U32 = 1, OR_F64 = 2 };
 enum { OR_SUM = 0, OR_BOR = 1 };
@@ -286,6 +306,7 @@ typedef struct msg {
     uint32_t nids;           /* first scheme: the list itself (virtual ranks) */
     uint32_t *ids;
     unsigned char *data;
+    uint64_t time;           /* timed mode (R9): the moment the message is at the receiver */
 } msg_t;
 
 typedef struct {
@@ -311,6 +332,12 @@ typedef struct {
     int count_steps;         /* count the message steps of every round */
     uint32_t steps[4];       /* per kind of message: sum over the rounds of the busiest process's messages */
     uint32_t *port_in, *port_out;   /* [P] scratch of count_steps */
+    /* event-driven times of the reduce (R9); tracked iff timed */
+    int timed;
+    uint64_t t_msg, t_timeout;
+    uint64_t *clock;         /* [P] each process's own time: advances by its sends and its waits only */
+    uint64_t *finish;        /* [P] the moment a process has done its part; ORACLE_NEVER while it has not */
+    uint64_t t_done;         /* the moment the root delivers (or gives up) */
     /* broadcast state */
     unsigned char *has;      /* [P] */
     unsigned char *held;     /* [P][bytes] */
@@ -387,9 +414,33 @@ static void net_send(sim_t *s, int kind, uint32_t src, uint32_t dst, const void 
     }
     m->data = arena_alloc(s, s->bytes);
     memcpy(m->data, data, s->bytes);
+    m->time = 0;
+    if (s->timed) {
+        /* the send takes t_msg of the sender's time; the message is at the receiver when the send ends */
+        s->clock[src] += s->t_msg;
+        m->time = s->clock[src];
+    }
     if (s->inflight_tail) s->inflight_tail->next = m; else s->inflight_head = m;
     s->inflight_tail = m;
     s->sent[kind]++;
+}
+
+/* Timed mode (R9).  Process v takes the message m it was waiting for: at once if it is there already, at its
+   arrival otherwise. */
+static void clock_receive(sim_t *s, uint32_t v, const msg_t *m)
+{
+    if (s->timed && m->time > s->clock[v]) s->clock[v] = m->time;
+}
+
+/* Timed mode (R9).  Process v waits for a message of process u that never comes (u has stopped: its clock stands
+   at that moment).  After every t_timeout of waiting v asks the monitor and gives up at the first such moment
+   that lies after the moment u stopped. */
+static void clock_give_up(sim_t *s, uint32_t v, uint32_t u)
+{
+    uint64_t k = 1;
+    if (!s->timed) return;
+    if (s->clock[u] >= s->clock[v] + s->t_timeout) k = (s->clock[u] - s->clock[v]) / s->t_timeout + 1;
+    s->clock[v] += k * s->t_timeout;
 }
 
 /* A process that is alive has waited in vain for a message of process u that was due by now: it asks the
@@ -550,6 +601,7 @@ static int run_reduce(sim_t *s, uint32_t base, void *result)
                     msg_t *m = inbox_take(s, v, MSG_TREE, t->kids[t->kid_off[v] + c]);
                     if (m) {
                         combine(s->dtype, s->op, s->elems, fold, m->data);
+                        clock_receive(s, v, m);
                         if (m->flag) flag = 1;
                         if (s->track_info) {       /* the parent adds the child's list to its own */
                             uint32_t i;
@@ -559,6 +611,7 @@ static int run_reduce(sim_t *s, uint32_t base, void *result)
                     } else {
                         flag = 1;    /* no value from this child */
                         monitor_query(s, t->kids[t->kid_off[v] + c], now);
+                        clock_give_up(s, v, t->kids[t->kid_off[v] + c]);
                         if (s->track_info) {
                             info_append(s, v, t->kids[t->kid_off[v] + c]);
                             s->fcount[v] += 1;
@@ -566,6 +619,7 @@ static int run_reduce(sim_t *s, uint32_t base, void *result)
                     }
                 }
                 net_send(s, MSG_TREE, v, (uint32_t)t->parent[v], fold, flag);
+                if (s->timed) s->finish[v] = s->clock[v];
                 if (s->trace_sent) s->trace_sent[v] = 1;
                 if (s->trace_flag) s->trace_flag[v] = (unsigned char)flag;
                 if (s->trace_msg) memcpy(s->trace_msg + (size_t)v * s->bytes, fold, s->bytes);
@@ -580,6 +634,7 @@ static int run_reduce(sim_t *s, uint32_t base, void *result)
                 if (!alive(s, v, now)) continue;
                 while ((m = inbox_take_any(s, v, MSG_UC)) != NULL) {
                     combine(s->dtype, s->op, s->elems, s->data + (size_t)v * s->bytes, m->data);
+                    clock_receive(s, v, m);
                     got = 1;
                 }
                 if (!s->disable_uc && t->group[v] >= 0 && !got) {
@@ -588,6 +643,7 @@ static int run_reduce(sim_t *s, uint32_t base, void *result)
                     if (r <= gs - 1) {
                         uint32_t mate = uc_source(t, v, r);
                         monitor_query(s, mate, now);
+                        clock_give_up(s, v, mate);
                         if (s->track_info) {
                             info_append(s, v, mate);
                             s->fcount[v] += 1;
@@ -620,6 +676,9 @@ static int run_reduce(sim_t *s, uint32_t base, void *result)
         msg_t *m = inbox_take(s, 0, MSG_TREE, child);
         int included = 0;
         uint32_t i;
+        /* the root takes its children in order and stops at the first it can use */
+        if (m) clock_receive(s, 0, m); else clock_give_up(s, 0, child);
+        if (s->timed) s->t_done = s->finish[0] = s->clock[0];
         if (!m || m->flag) continue;      /* absent, or failure in that subtree */
         /* is the root's value already in this message?  Yes iff the sender's
            subtree holds a member of the root's up-correction group. */
@@ -790,6 +849,7 @@ static void sim_free(sim_t *s)
     free(s->fl); free(s->fn); free(s->fcount); free(s->sel_ids);
     free(s->ch_state); free(s->ch_count); free(s->ch_nids); free(s->ch_ids);
     free(s->port_in); free(s->port_out);
+    free(s->clock); free(s->finish);
     arena_release(s);
 }
 
@@ -1263,6 +1323,75 @@ int oracle_allreduce_shape_batch(uint32_t P, uint32_t f, uint32_t elems, int dty
 #pragma omp atomic write
             bad = 1;
         }
+    }
+    return bad ? -1 : used;
+}
+
+/* Event-driven times of the reduce (R9), a batch: as oracle_reduce_shape_batch, plus t_done[S] = the moment the
+   root delivers (with status NO_CLEAN_SUBTREE: the moment it has gone through all its children; ORACLE_NEVER
+   when the root has failed or the failure set is bad) and t_proc[S][P] (may be NULL; by physical rank) = the
+   moment each process has done its part (sent to its parent; the root: t_done), ORACLE_NEVER for a process that
+   stops before.  t_msg, t_timeout >= 1. */
+int oracle_reduce_timed_batch(uint32_t P, uint32_t f, uint32_t elems, int dtype, int op, int shape,
+                              uint32_t S, const uint32_t *root,
+                              const void *payload, uint64_t payload_stride_bytes,
+                              uint32_t nfail, const uint32_t *fail_rank, const uint32_t *fail_round,
+                              uint64_t t_msg, uint64_t t_timeout,
+                              void *result, uint32_t *status, uint64_t *msgs, uint64_t *t_done, uint64_t *t_proc,
+                              int threads)
+{
+    int64_t i;
+    int bad = 0, used = 1;
+    size_t bytes = elems * elem_size(dtype);
+    if (t_msg == 0 || t_timeout == 0 || elems == 0 || (dtype == OR_F64 && op != OR_SUM) || dtype < 0 || dtype > 2)
+        return -1;
+#ifdef _OPENMP
+    if (threads > 0) omp_set_num_threads(threads);
+    used = omp_get_max_threads();
+#endif
+#pragma omp parallel for schedule(dynamic, 1)
+    for (i = 0; i < (int64_t)S; ++i) {
+        topo_t t;
+        sim_t s;
+        uint32_t *fv, v;
+        int st;
+        const uint32_t *fr = fail_rank + (size_t)i * nfail, *fo = fail_round + (size_t)i * nfail;
+        unsigned char *res = (unsigned char *)result + (size_t)i * bytes;
+        memset(res, 0, bytes);
+        msgs[2 * i] = msgs[2 * i + 1] = 0;
+        t_done[i] = ORACLE_NEVER;
+        if (t_proc) for (v = 0; v < P; ++v) t_proc[(size_t)i * P + v] = ORACLE_NEVER;
+        if (topo_build(&t, P, f, root ? root[i] : 0, shape) != 0) {
+            topo_free(&t);
+#pragma omp atomic write
+            bad = 1;
+            continue;
+        }
+        if (check_failures(P, nfail, fr) != 0) {
+            status[i] = OR_ST_BAD_FAILURE_SET;
+            topo_free(&t);
+            continue;
+        }
+        fv = malloc(sizeof(uint32_t) * (nfail + 1));
+        sim_init(&s, &t, elems, dtype, op, (const unsigned char *)payload + (size_t)i * payload_stride_bytes,
+                 nfail, fr, fo, fv);
+        s.timed = 1;
+        s.t_msg = t_msg;
+        s.t_timeout = t_timeout;
+        s.clock = calloc(P, sizeof(uint64_t));
+        s.finish = malloc(sizeof(uint64_t) * P);
+        for (v = 0; v < P; ++v) s.finish[v] = ORACLE_NEVER;
+        s.t_done = ORACLE_NEVER;
+        st = run_reduce(&s, 0, res);
+        if (st != OR_ST_OK) memset(res, 0, bytes);
+        status[i] = (uint32_t)st;
+        msgs[2 * i] = s.sent[MSG_UC];
+        msgs[2 * i + 1] = s.sent[MSG_TREE];
+        t_done[i] = s.t_done;
+        if (t_proc) for (v = 0; v < P; ++v) t_proc[(size_t)i * P + t.phys_of_virt[v]] = s.finish[v];
+        sim_free(&s);
+        free(fv);
+        topo_free(&t);
     }
     return bad ? -1 : used;
 }
