@@ -279,6 +279,38 @@ int ftred_detect(const ftred_plan_t *plan, int kind, uint32_t S, const uint32_t 
                  const uint32_t *fail_rank, const uint32_t *fail_round,
                  uint32_t *detected, void *hip_stream);
 
+/* Event-driven times of the reduce.  In the paper a process runs its phases one after
+   the other without regard to the progress of the others (section "Related work", last
+   paragraph), and a receive from a failed sender ends by a time-out and the failure
+   monitor's confirmation, and is retried while the monitor says the sender lives
+   (section "Up-Correction", last paragraph; liveness part of the proof in "Reduce /
+   Properties").  This library's model of that: every process starts at time 0 with a
+   clock of its own; it exchanges with its up-correction group (round t: send to its
+   target, then receive from its source), receives from its children in ascending
+   order, sends to its parent; the root receives from its children in order until a
+   message without the failed bit is there.  A send takes t_msg of the sender's time
+   and the message is at the receiver when the send ends; a receive ends at once if
+   the message is there, at its arrival otherwise; if the sender has stopped without
+   sending it, the receiver asks the monitor after every t_timeout of waiting and
+   gives up at the first such moment that lies AFTER the moment the sender stopped.
+   A process with fail_round r stops when it reaches the first step of a round >= r
+   (rounds as in ftred_run_reduce).  What is sent and received is what the round model
+   sends and receives, so results, statuses and counters are ftred_run_reduce's; this
+   call works out the clocks, from the failure lists alone (no payload):
+     t_done dev [S]     the moment the root delivers (status NO_CLEAN_SUBTREE: the moment
+                        it has gone through all its children); FTRED_NEVER for a root that
+                        has failed and for a failure set that is not valid
+     t_proc dev [S][P]  required, also the working storage: the moment each process has
+                        done its part (sent to its parent; the root: t_done), by physical
+                        rank; FTRED_NEVER for a process that stops before
+   root dev [S] or NULL (process 0).  t_msg, t_timeout in 1 .. 2^32 - 1.  One launch per
+   depth of the tree and one for the roots, on hip_stream. */
+#define FTRED_NEVER 0xFFFFFFFFFFFFFFFFull
+int ftred_reduce_times(const ftred_plan_t *plan, uint32_t S, const uint32_t *root,
+                       const uint32_t *fail_rank, const uint32_t *fail_round,
+                       uint64_t t_msg, uint64_t t_timeout,
+                       uint64_t *t_done, uint64_t *t_proc, void *hip_stream);
+
 /* Check results against the semantics (sections "Reduce / Semantics", items 3
    and 4, and "Allreduce / Semantics", items 4 and 5; message-count theorems),
    independently of the protocol: per scenario the reduction over the never-failed

@@ -93,6 +93,7 @@ def lib():
         L.ftred_validate.argtypes = [_vp, _int, _u32, _vp, _vp, _u64, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp,
                                      ctypes.POINTER(_u64), _vp, _u64, _vp]
         L.ftred_detect.argtypes = [_vp, _int, _u32, _vp, _vp, _vp, _vp, _vp]
+        L.ftred_reduce_times.argtypes = [_vp, _u32, _vp, _vp, _vp, ctypes.c_uint64, ctypes.c_uint64, _vp, _vp, _vp]
         L.ftred_gen_failures.argtypes = [_vp, _u64, _u32, _u32, _u32, _u32, _u32, _vp, _vp, _vp, _vp]
         L.ftred_gen_payload_int.argtypes = [_vp, _u64, _u32, _u32, _u32, _vp, _vp]
         L.ftred_timing_begin.argtypes = [_u32]
@@ -310,6 +311,23 @@ def detect(plan, kind, S, fail_rank, fail_round, root=None, stream=None):
     _check(lib().ftred_detect(plan.handle, kind, S, _ptr(root), _ptr(fail_rank), _ptr(fail_round), _ptr(det),
                               _stream(stream)))
     return det
+
+
+NEVER = 0xFFFFFFFFFFFFFFFF
+
+
+def reduce_times(plan, S, fail_rank, fail_round, t_msg, t_timeout, root=None, t_done=None, t_proc=None, stream=None):
+    """ftred_reduce_times.  Returns (t_done[S], t_proc[S][P]) as uint64 tensors (NEVER = did not get there)."""
+    _fail(plan, S, fail_rank, fail_round)
+    dev = fail_rank.device
+    if t_done is None:
+        t_done = torch.empty(S, dtype=torch.uint64, device=dev)
+    if t_proc is None:
+        t_proc = torch.empty((S, plan.P), dtype=torch.uint64, device=dev)
+    assert t_proc.is_contiguous() and t_proc.numel() == S * plan.P and t_done.numel() == S
+    _check(lib().ftred_reduce_times(plan.handle, S, _ptr(root), _ptr(fail_rank), _ptr(fail_round), int(t_msg),
+                                    int(t_timeout), _ptr(t_done), _ptr(t_proc), _stream(stream)))
+    return t_done, t_proc
 
 
 def latency(plan, kind, attempts, detected, t_message=1.0, t_timeout=10.0):

@@ -60,16 +60,23 @@ def needs_build() -> bool:
     return built_hash() != source_hash()
 
 
-def build(force: bool = True, jobs: int = 8, verbose: bool = False) -> str:
-    """Compile every .hip source and link the shared library.  Returns its path."""
+def build(force: bool = True, jobs: int = 8, verbose: bool = False, incremental: bool = False) -> str:
+    """Compile every .hip source and link the shared library.  Returns its path.
+    incremental: keep an object that is newer than its source and every header (the file that carries the
+    source hash is compiled every time)."""
     if not force and not needs_build():
         return LIB
     os.makedirs(OBJ, exist_ok=True)
     sha = source_hash()
+    newest_header = max(os.path.getmtime(p) for p in _deps())
 
     def compile_one(src):
         obj = os.path.join(OBJ, os.path.basename(src)[:-4] + ".o")
-        cmd = [HIPCC] + FLAGS + ["-DFTRED_SOURCE_HASH=\"%s\"" % sha, "-c", src, "-o", obj]
+        carries_hash = os.path.basename(src) == "ftred_api.hip"
+        if (incremental and not carries_hash and os.path.exists(obj)
+                and os.path.getmtime(obj) > max(os.path.getmtime(src), newest_header)):
+            return obj
+        cmd = [HIPCC] + FLAGS + (["-DFTRED_SOURCE_HASH=\"%s\"" % sha] if carries_hash else []) + ["-c", src, "-o", obj]
         r = subprocess.run(cmd, capture_output=True, text=True)
         if r.returncode != 0:
             raise RuntimeError("hipcc failed for %s:\n%s\n%s" % (src, r.stdout, r.stderr))
@@ -87,4 +94,4 @@ def build(force: bool = True, jobs: int = 8, verbose: bool = False) -> str:
 
 
 if __name__ == "__main__":
-    print(build(force=True, verbose=True))
+    print(build(force=True, verbose=True, incremental="--incremental" in sys.argv))
