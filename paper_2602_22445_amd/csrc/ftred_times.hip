@@ -15,15 +15,19 @@
 // fixed order), so values, statuses and counters are those of ftred_run_reduce;
 // here only the clocks are worked out, from the failure lists alone.
 //
-// One launch per depth of the tree, deepest first; one thread per process.  A
-// thread works out its clock after the exchange in its up-correction group
-// (Algorithm "Up-correction": send, then receive, round by round; closed form
-// where nobody of the group is listed), takes its children's entries from t_proc,
-// where an earlier launch left them (a time with the failed bit of the message,
-// or the moment the child stopped), waits for each child in order, sends, and
-// leaves its own entry; it rewrites its children's entries in their final form.
-// A last launch is the root: children in order until a message without the
-// failed bit is there (Algorithm "reduce at the root").
+// Two launches.  The first writes, for every process, the time it is done when
+// nobody fails: t_msg x (f + 1 + its height), where a short last group (fewer
+// exchange rounds than f) counts as absent, because its members' messages are at
+// their parents before those have ended their own exchange.  The second, one
+// wavefront per scenario, redoes what the failures touch: a process's time differs
+// from that only if its group or the group of somebody below it holds a listed
+// process, so the members of the listed processes' groups and their ancestors are
+// worked out level by level from the deepest: the clock after the exchange in the
+// up-correction group (Algorithm "Up-correction": send, then receive, round by
+// round), the children's entries (a time with the failed bit of the message, or
+// the moment the child stopped), the send.  Last the root: children in order
+// until a message without the failed bit is there (Algorithm "reduce at the
+// root").
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <string.h>
@@ -41,6 +45,8 @@ constexpr unsigned long long kStopped = 1ull << 63;      // working entry of a p
 constexpr unsigned long long kFailedBit = 1ull << 62;    // working entry of a sender: its message carries the failed bit
 constexpr unsigned long long kTimeMask = kFailedBit - 1ull;
 
+constexpr uint32_t kFillChunk = 4096;    // entries one workgroup of the first launch writes
+
 struct TimeArgs {
     Geom g;
     const uint32_t* root;          // [S] or nullptr
@@ -52,11 +58,6 @@ struct TimeArgs {
     uint32_t S;
 };
 
-struct TimeLevel {
-    uint32_t depth, j_lo, j_hi, filter;
-    uint32_t blocks_per_scen;
-    FastDiv div_bps;
-};
 
 // the receiver's clock when it gives up on a sender that stopped at `stopped`: the first moment own + k * tau
 // (k >= 1) that lies after it
@@ -68,13 +69,15 @@ __device__ __forceinline__ unsigned long long give_up(unsigned long long own, un
     return own + k * tau;
 }
 
-// Clocks of the members of row j's up-correction group (gs members) after the exchange, all of them: a member's
-// waits depend on the others' clocks.
-__device__ void exchange_clocks(const Geom& g, const FailTab& ft, uint32_t j, uint32_t gs, unsigned long long m,
-                                unsigned long long tau, unsigned long long* clock /* [16] */)
+// Clock of member `me` of row j's up-correction group (gs members) after the exchange; the clocks of all members
+// are worked out, since a member's waits depend on the others' clocks (Algorithm "Up-correction": in round t send
+// to the target, then receive from the source).  The arrays are indexed by member numbers known at run time only
+// and live in private memory; LDS for them (20 KiB per wavefront) was measured slower on large batches.
+__device__ unsigned long long exchange_clock(const Geom& g, const FailTab& ft, uint32_t j, uint32_t gs, uint32_t me,
+                                             unsigned long long m, unsigned long long tau)
 {
     uint32_t lim[16];              // exchange rounds in which member w takes part
-    unsigned long long stamp[16];
+    unsigned long long clock[16], stamp[16];
     for (uint32_t w = 0; w < 16u; ++w) { lim[w] = gs; clock[w] = 0; }
     for (uint32_t q = 0; q < ft.n; ++q)
         if (ft.row[q] == j) lim[ft.idx[q] & 15u] = ft.uc[q];
@@ -91,6 +94,7 @@ __device__ void exchange_clocks(const Geom& g, const FailTab& ft, uint32_t j, ui
             else clock[w] = give_up(clock[w], clock[src], tau);      // src has stopped: its clock stands
         }
     }
+    return clock[me & 15u];
 }
 
 // is the scenario's failure set one the semantics cover (ranks below P, no rank twice, root below P)?
@@ -105,54 +109,39 @@ __device__ bool bad_failure_set(const Geom& g, const uint32_t* fr, uint32_t root
     return bad;
 }
 
-// Takes the working entry of a child, advances the parent's clock (if it waits for it at all) and leaves the
-// child's entry in its final form.
-__device__ __forceinline__ void take_child(unsigned long long* cp, bool waits, unsigned long long tau,
-                                           unsigned long long& clock, bool& flag, bool& present)
+// Working entries are read and written past the first-level cache: lanes of the wavefront hand them to each other
+// through memory between two barriers.
+__device__ __forceinline__ unsigned long long ld_entry(const unsigned long long* p)
 {
-    const unsigned long long raw = *cp;
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void st_entry(unsigned long long* p, unsigned long long v)
+{
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// The parent's clock after it has dealt with one child (working entry `raw`), and the failed bit it passes on.
+__device__ __forceinline__ void take_child(unsigned long long raw, unsigned long long tau, unsigned long long& clock,
+                                           bool& flag, bool& present)
+{
     present = (raw & kStopped) == 0ull;
     if (present) {
         const unsigned long long t = raw & kTimeMask;
-        if (waits) {
-            clock = clock > t ? clock : t;
-            flag = flag || (raw & kFailedBit) != 0ull;
-        }
-        *cp = t;
+        clock = clock > t ? clock : t;
+        flag = flag || (raw & kFailedBit) != 0ull;
     } else {
-        if (waits) {
-            clock = give_up(clock, raw & kTimeMask, tau);
-            flag = true;
-        }
-        *cp = kNever;
+        clock = give_up(clock, raw & kTimeMask, tau);
+        flag = true;
     }
 }
 
-__global__ void __launch_bounds__(256) times_level_kernel(TimeArgs A, TimeLevel lv)
+// Working entry of the process at position j of subtree i: its clock after the exchange, its children in ascending
+// order, its send (Algorithm "reduce at non-roots").  A process that has stopped by its send round waits for nobody:
+// its clock stands where the exchange left it.
+__device__ unsigned long long node_entry(const TimeArgs& A, const FailTab& ft, const unsigned long long* tp, uint32_t root,
+                                         uint32_t j, uint32_t i)
 {
-    __shared__ FailTab ft;
-    __shared__ uint32_t s_bad;
     const Geom& g = A.g;
-    const uint32_t tid = threadIdx.x;
-    const uint32_t s = fdiv(blockIdx.x, lv.div_bps);
-    const uint32_t b = blockIdx.x - s * lv.blocks_per_scen;
-    const uint32_t root = A.root ? A.root[s] : 0u;
-    const uint32_t F = g.f > 0 ? g.f : 1u;
-    load_failtab(ft, g, A.fail_rank, A.fail_round, s, root, 0u);
-    if (tid == 64) s_bad = bad_failure_set(g, A.fail_rank + size_t(s) * F, root) ? 1u : 0u;
-    __syncthreads();
-
-    const uint32_t W = g.W;
-    const uint32_t it = b * 256u + tid;
-    const uint32_t r = fdiv(it, g.divW);
-    const uint32_t i = it - r * W;
-    const uint32_t j = lv.j_lo + r;
-    if (j >= lv.j_hi || (lv.filter && sh_depth(g, j) != lv.depth) || i >= row_members(g, j)) return;
-    unsigned long long* tp = A.t_proc + size_t(s) * g.P;
-    unsigned long long* own = tp + relabel(1u + j * W + i, root);
-    if (s_bad) { *own = kNever; return; }
-
-    // the exchange in the up-correction group
     const uint32_t gs = group_size(g, j);
     bool listed_row = false, sends = true;
     for (uint32_t q = 0; q < ft.n; ++q)
@@ -164,57 +153,141 @@ __global__ void __launch_bounds__(256) times_level_kernel(TimeArgs A, TimeLevel 
     if (!listed_row) {
         clock = (unsigned long long)(g.f < gs - 1u ? g.f : gs - 1u) * A.t_msg;
     } else {
-        unsigned long long ck[16];
-        exchange_clocks(g, ft, j, gs, A.t_msg, A.t_timeout, ck);
-        clock = ck[i & 15u];
+        clock = exchange_clock(g, ft, j, gs, i, A.t_msg, A.t_timeout);
     }
-    // the children in order, then the send to the parent (Algorithm "reduce at non-roots"); a process that has
-    // stopped by its send round waits for nobody, and its clock stands where the exchange left it
+    if (!sends) return clock | kStopped;
     bool flag = false;
     sh_for_children(g, subtree_size(g, i), j, [&](uint32_t jc) {
         bool present;
-        take_child(tp + relabel(1u + jc * W + i, root), sends, A.t_timeout, clock, flag, present);
+        take_child(ld_entry(tp + relabel(1u + jc * g.W + i, root)), A.t_timeout, clock, flag, present);
     });
-    if (sends) *own = (clock + A.t_msg) | (flag ? kFailedBit : 0ull);
-    else *own = clock | kStopped;
+    return (clock + A.t_msg) | (flag ? kFailedBit : 0ull);
 }
 
-__global__ void __launch_bounds__(64) times_root_kernel(TimeArgs A)
+// Every process's time when nobody fails (a failure set outside the semantics: "never").
+__global__ void __launch_bounds__(256) times_fill_kernel(TimeArgs A, uint32_t blocks_per_scen, FastDiv div_bps)
 {
-    __shared__ FailTab ft;
+    __shared__ uint32_t s_bad;
     const Geom& g = A.g;
-    const uint32_t s = blockIdx.x;
+    const uint32_t s = fdiv(blockIdx.x, div_bps);
+    const uint32_t b = blockIdx.x - s * blocks_per_scen;
     const uint32_t root = A.root ? A.root[s] : 0u;
     const uint32_t F = g.f > 0 ? g.f : 1u;
-    load_failtab(ft, g, A.fail_rank, A.fail_round, s, root, 0u);
+    if (threadIdx.x == 0) s_bad = bad_failure_set(g, A.fail_rank + size_t(s) * F, root) ? 1u : 0u;
     __syncthreads();
-    if (threadIdx.x != 0) return;
+    // a workgroup writes kFillChunk consecutive entries (a few KiB of work per look at the failure list)
+    for (uint32_t p = b * kFillChunk + threadIdx.x; p < g.P && p < (b + 1u) * kFillChunk; p += 256u) {
+        unsigned long long* own = A.t_proc + size_t(s) * g.P + p;
+        if (s_bad) { *own = kNever; continue; }
+        const uint32_t v = relabel(p, root);
+        if (v == 0) continue;                                // the root: the second launch
+        const uint32_t j = fdiv(v - 1u, g.divW), i = v - 1u - j * g.W;
+        unsigned long long rounds;
+        if (j == g.M - 1u) {
+            // the deepest position of its subtree: its exchange (shorter in a short group), its send
+            const uint32_t gs = group_size(g, j);
+            rounds = (g.f < gs - 1u ? g.f : gs - 1u) + 1u;
+        } else {
+            // f exchange rounds, then a send one t_msg after the last child's; a member of a short last group
+            // sends no later than its parent ends its exchange, so for heights it is not there
+            uint32_t m = subtree_size(g, i);
+            if (group_size(g, g.M - 1u) <= g.f && i < g.nlast) m -= 1u;
+            uint32_t h;
+            if (g.shape == kShapeBinary) {
+                // the largest h with (j + 1) 2^h <= m
+                h = ilog2(m) - ilog2(j + 1u);
+                if (((j + 1u) << h) > m) --h;
+            } else {
+                h = sh_height_m(g.shape, m, j);
+            }
+            rounds = g.f + 1u + h;
+        }
+        *own = rounds * A.t_msg;
+    }
+}
+
+// What the failures of one scenario touch, by one wavefront.
+__global__ void __launch_bounds__(64) times_fix_kernel(TimeArgs A)
+{
+    __shared__ FailTab ft;
+    __shared__ uint32_t seed_j[256], seed_i[256];
+    __shared__ uint32_t nseeds;
+    const Geom& g = A.g;
+    const uint32_t s = blockIdx.x, lane = threadIdx.x;
+    const uint32_t root = A.root ? A.root[s] : 0u;
+    const uint32_t F = g.f > 0 ? g.f : 1u;
     unsigned long long* tp = A.t_proc + size_t(s) * g.P;
-    if (bad_failure_set(g, A.fail_rank + size_t(s) * F, root)) {
-        // the level launches have left "never" for every process with a place in the tree; the one left is the
-        // root, or process 0 if the root is no process at all
-        A.t_done[s] = kNever;
-        tp[root < g.P ? root : 0u] = kNever;
+    if (bad_failure_set(g, A.fail_rank + size_t(s) * F, root)) {      // the same answer in every lane
+        if (lane == 0) A.t_done[s] = kNever;
         return;
     }
-    // the root's exchange: member a-1 of the short last group, if it is in one (section "Up-Correction")
-    unsigned long long clock = 0;
-    if (g.a > 1) {
-        unsigned long long ck[16];
-        exchange_clocks(g, ft, g.M - 1u, g.a, A.t_msg, A.t_timeout, ck);
-        clock = ck[(g.a - 1u) & 15u];
+    load_failtab(ft, g, A.fail_rank, A.fail_round, s, root, 0u);
+    __syncthreads();
+    // the members of every group that holds a listed process (the root is no tree member: it comes last)
+    if (lane == 0) {
+        uint32_t n = 0;
+        for (uint32_t q = 0; q < ft.n; ++q) {
+            const uint32_t j = ft.row[q];
+            if (ft.vr[q] == kNoRank || j == kNoRank) continue;
+            bool seen = false;
+            for (uint32_t q2 = 0; q2 < q; ++q2) seen = seen || (ft.vr[q2] != kNoRank && ft.row[q2] == j);
+            if (seen) continue;
+            for (uint32_t i = 0; i < row_members(g, j); ++i) { seed_j[n] = j; seed_i[n] = i; ++n; }
+        }
+        nseeds = n;
     }
-    // its children in order until a message without the failed bit is there (Algorithm "reduce at the root"); a
-    // root that has stopped waits for nobody
-    bool waits = ft.root_alive != 0u;
-    for (uint32_t k = 0; k < g.W; ++k) {
-        bool flag = false, present;
-        take_child(tp + relabel(1u + k, root), waits, A.t_timeout, clock, flag, present);
-        if (waits && present && !flag) waits = false;
+    __syncthreads();
+    const uint32_t n = nseeds;
+    // them and their ancestors, the deepest first: a level reads what the one below has left
+    for (uint32_t d = n > 0u ? g.D : 0u; d >= 1u; --d) {
+        for (uint32_t k = lane; k < n; k += 64u) {
+            uint32_t j = seed_j[k];
+            const uint32_t i = seed_i[k];
+            uint32_t dj = sh_depth(g, j);
+            if (dj < d) continue;
+            for (; dj > d; --dj) j = sh_parent(g, j);
+            st_entry(tp + relabel(1u + j * g.W + i, root), node_entry(A, ft, tp, root, j, i));
+        }
+        __syncthreads();
     }
-    const unsigned long long done = ft.root_alive ? clock : kNever;
-    A.t_done[s] = done;
-    tp[root] = done;
+    if (lane == 0) {
+        // the root's exchange: member a-1 of the last group, if it is in one (section "Up-Correction")
+        unsigned long long clock = 0;
+        if (g.a > 1) clock = exchange_clock(g, ft, g.M - 1u, g.a, g.a - 1u, A.t_msg, A.t_timeout);
+        // its children in order until a message without the failed bit is there (Algorithm "reduce at the root")
+        bool waits = ft.root_alive != 0u;
+        for (uint32_t k = 0; k < g.W && waits; ++k) {
+            bool flag = false, present;
+            take_child(ld_entry(tp + relabel(1u + k, root)), A.t_timeout, clock, flag, present);
+            if (present && !flag) waits = false;
+        }
+        const unsigned long long done = ft.root_alive ? clock : kNever;
+        A.t_done[s] = done;
+        tp[root] = done;
+    }
+    __syncthreads();
+    // working entries into their final form: a time, or "never" for a process that stopped; four ancestors at a
+    // time, so that their loads are in flight together
+    for (uint32_t k = lane; k < n; k += 64u) {
+        uint32_t j = seed_j[k];
+        const uint32_t i = seed_i[k];
+        bool more = true;
+        while (more) {
+            unsigned long long* e[4];
+            unsigned long long raw[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                e[u] = more ? tp + relabel(1u + j * g.W + i, root) : nullptr;
+                if (more && j == 0) more = false;
+                else if (more) j = sh_parent(g, j);
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) raw[u] = e[u] ? ld_entry(e[u]) : 0ull;
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                if (e[u]) st_entry(e[u], (raw[u] & kStopped) ? kNever : (raw[u] & kTimeMask));
+        }
+    }
 }
 
 }  // namespace
@@ -245,32 +318,12 @@ extern "C" int ftred_reduce_times(const ftred_plan_t* plan, uint32_t S, const ui
     A.t_done = reinterpret_cast<unsigned long long*>(t_done);
     A.t_proc = reinterpret_cast<unsigned long long*>(t_proc);
     A.S = S;
-    for (uint32_t d = g.D; d >= 1; --d) {           // the rows of a subtree have depths 1 .. D
-        TimeLevel lv;
-        memset(&lv, 0, sizeof(lv));
-        lv.depth = d;
-        if (g.shape == kShapeBinomial) {
-            // depth = 1 + number of one bits of the position: no range; the first such position is 2^(d-1) - 1
-            lv.j_lo = d > 32u ? g.M : uint32_t((uint64_t(1) << (d - 1u)) - 1u);
-            lv.j_hi = g.M;
-            lv.filter = 1;
-        } else {
-            // level d-1 of a k-ary heap: positions (k^(d-1) - 1) / (k - 1) .. + k^(d-1) - 1
-            uint64_t first = 0, count = 1;
-            for (uint32_t l = 1; l < d && first < g.M; ++l) { first += count; count *= g.shape; }
-            lv.j_lo = first < g.M ? uint32_t(first) : g.M;
-            lv.j_hi = first + count < g.M ? uint32_t(first + count) : g.M;
-        }
-        if (lv.j_lo >= lv.j_hi) continue;
-        const uint64_t items = uint64_t(lv.j_hi - lv.j_lo) * g.W;
-        lv.blocks_per_scen = uint32_t((items + 255u) / 256u);
-        lv.div_bps = make_fastdiv(lv.blocks_per_scen);
-        if (uint64_t(S) * lv.blocks_per_scen >= (uint64_t(1) << 31))
-            return set_error(FTRED_EUNSUPPORTED, "ftred_reduce_times: S = %u scenarios need too many workgroups; split the batch", S);
-        hipLaunchKernelGGL(times_level_kernel, dim3(S * lv.blocks_per_scen), dim3(256), 0, st, A, lv);
-        HIP_TRY(hipGetLastError());
-    }
-    hipLaunchKernelGGL(times_root_kernel, dim3(S), dim3(64), 0, st, A);
+    const uint32_t bps = (g.P + kFillChunk - 1u) / kFillChunk;
+    if (uint64_t(S) * bps >= (uint64_t(1) << 31))
+        return set_error(FTRED_EUNSUPPORTED, "ftred_reduce_times: S = %u scenarios need too many workgroups; split the batch", S);
+    hipLaunchKernelGGL(times_fill_kernel, dim3(S * bps), dim3(256), 0, st, A, bps, make_fastdiv(bps));
+    HIP_TRY(hipGetLastError());
+    hipLaunchKernelGGL(times_fix_kernel, dim3(S), dim3(64), 0, st, A);
     HIP_TRY(hipGetLastError());
     return FTRED_OK;
 }
