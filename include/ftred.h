@@ -113,8 +113,9 @@ typedef struct ftred_info {
    the tree kernels otherwise: bits 0..7 = LDS budget in KiB of the deepest tier's
    tiles (4..24), bits 8..11 = 1 + log2 of the tiles one workgroup walks through,
    bit 12 = LDS-tile kernel also for the deepest tier (the default there is a
-   register kernel when the tree is deep enough and f + 1 <= 9:
-   one lane per subtree, or eight lanes per subtree when elems == 1),
+   register kernel when the tree is deep enough: one lane per subtree, or eight
+   lanes per subtree when elems == 1; for f + 1 >= 10 only while 31 up-correction
+   groups of f + 1 payloads fit 24 KiB),
    bits 13..15 = 1 + log2 of the groups of subtrees one wavefront of the register
    kernel walks through, bit 16 = the deepest tier and the levels above it always in
    launches of their own (the default folds a whole scenario in one workgroup and

@@ -156,6 +156,17 @@ static void plan_steps(ftred_plan_t* p)
     }
 }
 
+// Can the deepest tier run on the register walks?  For every width they are built for; beyond the widths of the walk
+// with failure handling the listed subtrees go to the LDS-tile list kernel, which stages a whole subtree of the
+// walk's height: its rows must fit the prefetch registers and a tile of at most 40 KiB.
+static bool wave_usable(const Geom& g)
+{
+    if (!wave_width_ok(g.W)) return false;
+    if (wave_list_width_ok(g.W)) return true;
+    const uint32_t per_row = g.RB + 4u + 2u * g.W;
+    return kWaveRows <= kStageBytes / g.RB && kWaveRows * per_row <= 40u * 1024u;
+}
+
 extern "C" int ftred_plan(ftred_plan_t** out, uint32_t P, uint32_t f, uint32_t elems, int dtype, int op,
                           uint32_t flags)
 {
@@ -205,7 +216,7 @@ extern "C" int ftred_plan(ftred_plan_t** out, uint32_t P, uint32_t f, uint32_t e
         if (c0 > stage_rows) c0 = stage_rows;
         if (c1 > 2u * stage_rows + 1u) c1 = 2u * stage_rows + 1u;
         const uint32_t hc0 = ilog2(c0 + 1u) - 1u, hc1 = ilog2(c1 + 1u) - 2u;
-        const bool wave = g.L > uint32_t(kWaveH) && !(flags & 0x1000u) && wave_width_ok(g.W);
+        const bool wave = g.L > uint32_t(kWaveH) && !(flags & 0x1000u) && wave_usable(g);
         const uint32_t h0 = wave ? uint32_t(kWaveH) : (hc0 < g.L ? hc0 : g.L);
         const uint32_t levels = g.L - h0;
         if (1u + (levels + hc1) / (hc1 + 1u) > uint32_t(kMaxTiers)) row_too_large = true;
@@ -214,7 +225,7 @@ extern "C" int ftred_plan(ftred_plan_t** out, uint32_t P, uint32_t f, uint32_t e
     // ... unless one workgroup can fold a whole scenario, block of value indices by block: that kernel and the
     // register walk of the listed subtrees need no LDS tile of rows at all
     if (shape == kShapeBinary && row_too_large && g.L > uint32_t(kWaveH) && !(flags & 0x11000u) && !((flags >> 13) & 7u) &&
-        wave_width_ok(g.W) && g.E > 1u && make_fused_layout(g, g.L - uint32_t(kWaveH)).ok) {
+        wave_list_width_ok(g.W) && g.E > 1u && make_fused_layout(g, g.L - uint32_t(kWaveH)).ok) {
         p->fused_only = 1;
         p->use_wave = 1;
         p->use_fused = 1;
@@ -249,6 +260,11 @@ extern "C" int ftred_plan(ftred_plan_t** out, uint32_t P, uint32_t f, uint32_t e
         // and wants many workgroups per CU (small tiles); the upper tiers are small.
         const uint32_t stage_rows = kStageBytes / g.RB;               // rows the prefetch registers hold
         const uint32_t per_row = g.RB + 4u + 2u * g.W;          // values, meta word, lists
+        // groups too wide for the register walk with failure handling: the deepest tier's tile serves the list of
+        // subtrees with listed processes alone, and must hold one such subtree whatever the budget asked for
+        const bool list_tile = g.L > uint32_t(kWaveH) && !(flags & 0x1000u) && !wave_list_width_ok(g.W) &&
+                               wave_usable(g);
+        if (list_tile && budget < kWaveRows * per_row) budget = kWaveRows * per_row;
         uint32_t cap0 = budget / per_row;
         uint32_t cap1 = (56u * 1024u) / per_row;
         if (cap0 > stage_rows) cap0 = stage_rows;
@@ -263,7 +279,8 @@ extern "C" int ftred_plan(ftred_plan_t** out, uint32_t P, uint32_t f, uint32_t e
         // When the lists of failed processes are asked for, the listed subtrees of the register tier run on the
         // LDS-tile list kernel, which must stage a whole subtree of height kWaveH; where it cannot, such runs take
         // a second plan that is on LDS tiles throughout (p->alt, below).
-        p->use_wave = (g.L > uint32_t(kWaveH) && !(flags & 0x1000u) && wave_width_ok(g.W)) ? 1u : 0u;
+        p->use_wave = (g.L > uint32_t(kWaveH) && !(flags & 0x1000u) && wave_usable(g)) ? 1u : 0u;
+        p->list_tile = list_tile ? 1u : 0u;
         info_alt = p->use_wave && ((2u << kWaveH) - 1u) > cap0;
         {
             uint32_t h0 = hcap0 < g.L ? hcap0 : g.L;
@@ -329,7 +346,7 @@ extern "C" int ftred_plan(ftred_plan_t** out, uint32_t P, uint32_t f, uint32_t e
             p->wave_gshift = most - p->wl.group_shift;                // one wavefront per workgroup
             p->wl.stage = (p->wl.group_shift > 0 && wave_can_stage(g, p->wl)) ? 1u : 0u;
             p->use_unit = g.E == 1u ? 1u : 0u;
-            if (!p->use_unit && !(flags & 0x10000u) && !((flags >> 13) & 7u)) {
+            if (!p->use_unit && !p->list_tile && !(flags & 0x10000u) && !((flags >> 13) & 7u)) {
                 p->fl = make_fused_layout(g, p->tiers[0].dlo);
                 p->use_fused = p->fl.ok;
             }
@@ -527,7 +544,9 @@ static int launch_tiers(const ftred_plan_t* plan, RunArgs& A, uint32_t S, uint32
         if (t == 0 && plan->use_wave) {
             // subtrees with listed processes, the short last group or a ragged bottom are listed and run by the
             // list kernels; the plain register kernel runs all the others
-            A.wave_general = A.info ? 0u : 1u;     // the lists of failed processes travel through the tile kernel only
+            // the lists of failed processes travel through the tile kernel only; so do the listed subtrees of
+            // groups the register walk with failure handling is not built for
+            A.wave_general = (A.info || plan->list_tile) ? 0u : 1u;
             // room for f + 3 listed subtrees per scenario or retry entry (at most f + 1 occur), 2^slot_shift of
             // them per wavefront
             const uint64_t wgs = ((uint64_t(S) + extra) * (plan->g.f + 3u) + (1u << plan->wl.slot_shift) - 1u) >> plan->wl.slot_shift;

@@ -23,6 +23,7 @@ struct ftred_plan_s {
     ftred::WaveLayout wl;
     uint32_t kwalk_given;       // the flags fix the cones a workgroup walks through
     uint32_t use_unit;          // ... with eight lanes per subtree (one value per process)
+    uint32_t list_tile;         // ... and the subtrees with listed processes on the LDS-tile list kernel (wide groups)
     ftred::UnitLayout ul;
     uint32_t use_fused;         // ... and the levels above it and the root's choice in the same launch
     uint32_t fused_only;        // rows too large for the LDS tiles: no tiers at all, the fused kernel and the register

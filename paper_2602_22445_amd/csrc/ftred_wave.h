@@ -63,14 +63,19 @@ inline bool wave_can_stage(const Geom& g, const WaveLayout& w)
     return w.passes == 1u && g.RB % 8u == 0u && (uint64_t(g.RB + 4u) << (w.group_shift + w.slot_shift)) <= 12u * 1024u;
 }
 
-// group widths the register kernels are built for (straight-line code per width): W = f + 1 = 2 .. 9.  A lane of
-// the walk holds (rows in flight + levels + 1) * W values; from W = 10 on that is one wavefront per SIMD, and the
-// walk with failure handling (W * (W - 1) predicated additions per visit, 31 visits) takes minutes to compile
-// per width, value type and operator.  Wider groups use the LDS-tile kernel.
-constexpr uint32_t kWaveMinW = 2, kWaveMaxW = 9;
+// Group widths the register kernels are built for (straight-line code per width).  The plain walks (one lane per
+// subtree, eight lanes per subtree) exist for W = f + 1 = 2 .. 16; a lane holds (rows in flight + levels + 1) * W
+// values, which is two wavefronts per SIMD at W = 10, 11 and one from W = 12 on (still several times faster than LDS
+// tiles).  The walk with failure handling and the kernel that folds a whole scenario are built for W <= 9 only:
+// W * (W - 1) predicated additions per visit, 31 visits, take minutes to compile per width, value type and
+// operator (all widths: a build of 16 instead of 4 minutes); for wider groups the listed subtrees run on the
+// LDS-tile list kernel.
+constexpr uint32_t kWaveMinW = 2, kWaveMaxW = 16, kWaveListMaxW = 9;
 inline bool wave_width_ok(uint32_t W) { return W >= kWaveMinW && W <= kWaveMaxW; }
+inline bool wave_list_width_ok(uint32_t W) { return W >= kWaveMinW && W <= kWaveListMaxW; }
 
-// `return FN<W>(args...)` for the run-time group width W
+// `return FN<W>(args...)` for the run-time group width W: the widths of the walk with failure handling and the
+// fused kernel, and all widths of the plain walks
 #define FTRED_WAVE_WIDTH_SWITCH(W, FN, ...)                     \
     switch (W) {                                                \
         case 2: return FN<2>(__VA_ARGS__);                      \
@@ -81,6 +86,25 @@ inline bool wave_width_ok(uint32_t W) { return W >= kWaveMinW && W <= kWaveMaxW;
         case 7: return FN<7>(__VA_ARGS__);                      \
         case 8: return FN<8>(__VA_ARGS__);                      \
         case 9: return FN<9>(__VA_ARGS__);                      \
+        default: return hipErrorInvalidValue;                   \
+    }
+#define FTRED_WAVE_WIDTH_SWITCH_WIDE(W, FN, ...)                \
+    switch (W) {                                                \
+        case 2: return FN<2>(__VA_ARGS__);                      \
+        case 3: return FN<3>(__VA_ARGS__);                      \
+        case 4: return FN<4>(__VA_ARGS__);                      \
+        case 5: return FN<5>(__VA_ARGS__);                      \
+        case 6: return FN<6>(__VA_ARGS__);                      \
+        case 7: return FN<7>(__VA_ARGS__);                      \
+        case 8: return FN<8>(__VA_ARGS__);                      \
+        case 9: return FN<9>(__VA_ARGS__);                      \
+        case 10: return FN<10>(__VA_ARGS__);                    \
+        case 11: return FN<11>(__VA_ARGS__);                    \
+        case 12: return FN<12>(__VA_ARGS__);                    \
+        case 13: return FN<13>(__VA_ARGS__);                    \
+        case 14: return FN<14>(__VA_ARGS__);                    \
+        case 15: return FN<15>(__VA_ARGS__);                    \
+        case 16: return FN<16>(__VA_ARGS__);                    \
         default: return hipErrorInvalidValue;                   \
     }
 
@@ -463,7 +487,7 @@ FTRED_DECLARE_WAVE_LAUNCHER(f64_sum)
     }                                                                                               \
     hipError_t launch_wave_##NAME(const RunArgs& A, const WaveLayout& wl, uint32_t grid, hipStream_t st) \
     {                                                                                               \
-        FTRED_WAVE_WIDTH_SWITCH(A.g.W, wave_wp_##NAME, A, wl, grid, st)                             \
+        FTRED_WAVE_WIDTH_SWITCH_WIDE(A.g.W, wave_wp_##NAME, A, wl, grid, st)                        \
     }
 
 }  // namespace ftred

@@ -276,7 +276,7 @@ FTRED_DECLARE_UNIT_LAUNCHER(f64_sum)
     hipError_t launch_unit_##NAME(const RunArgs& A, const UnitLayout& ul, uint32_t grid, hipStream_t st) \
     {                                                                                               \
         if (A.g.E != 1u) return hipErrorInvalidValue;                                               \
-        FTRED_WAVE_WIDTH_SWITCH(A.g.W, unit_wp_##NAME, A, ul, grid, st)                             \
+        FTRED_WAVE_WIDTH_SWITCH_WIDE(A.g.W, unit_wp_##NAME, A, ul, grid, st)                        \
     }
 
 }  // namespace ftred

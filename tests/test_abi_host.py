@@ -48,7 +48,9 @@ def test_plan_info_matches_the_closed_forms(ft, P, f, D, uc, groups, a):
     (1024, 3, 16, 0, 2, 1),                 # deepest tier in registers (one lane per subtree) + the top tier
     (16384, 4, 8, 2, 3, 1),                 # depths 7..11 in registers, 3..6 and 0..2 in LDS tiles
     (1 << 20, 8, 1, 0, 3, 2),               # one value per process: eight lanes per subtree
-    (3000, 12, 2, 0, 2, 0),                 # a group width the register kernels are not built for
+    (3000, 12, 2, 0, 2, 1),                 # a wide group: registers, the listed subtrees on the LDS-tile list kernel
+    (16384, 15, 8, 2, 3, 0),                # a wide group whose subtrees do not fit that kernel's tile: LDS tiles
+    (100, 16 - 1, 1, 0, 1, 0),              # too shallow a tree for the register kernels
 ])
 def test_plan_tiers_and_deepest_kernel(ft, P, f, E, dtype, tiers, kernel):
     """Launches of one tree phase and the kernel of the deepest tier for the shapes of the workloads: the levels

@@ -116,7 +116,7 @@ REDUCE_CASES = [
     (100, 6, 5, 2, 0, 128, 600), (257, 7, 2, 0, 1, 128, 600), (1000, 8, 1, 0, 0, 96, 500),
     (1024, 3, 16, 0, 0, 256, 400), (1500, 4, 8, 2, 0, 128, 500), (4099, 5, 3, 2, 0, 48, 500),
     (5000, 0, 2, 0, 0, 16, 0), (20000, 2, 4, 1, 0, 24, 500), (33333, 4, 8, 2, 0, 12, 500),
-    (3000, 12, 2, 0, 0, 32, 500), (1 << 16, 8, 1, 0, 0, 6, 500),
+    (3000, 12, 2, 0, 0, 32, 500), (1 << 16, 8, 1, 0, 0, 6, 500), (3000, 12, 40, 2, 0, 12, 500),
     # the register kernel of the deepest tier: two passes over the value indices, bitwise or, every group width
     (3000, 1, 80, 1, 0, 24, 500), (2000, 2, 4, 1, 1, 64, 500), (700, 1, 3, 0, 1, 64, 500), (9000, 3, 5, 2, 0, 24, 500),
     (5000, 8, 3, 0, 0, 24, 500),
@@ -151,7 +151,7 @@ ALLREDUCE_CASES = [
     (9, 2, 3, 1, 0, 64, 700), (17, 15, 1, 0, 0, 64, 500), (64, 2, 8, 1, 1, 128, 500), (100, 6, 5, 2, 0, 128, 600),
     (257, 7, 2, 0, 1, 128, 600), (1000, 8, 1, 0, 0, 96, 250), (1024, 3, 16, 0, 0, 128, 400),
     (1500, 4, 8, 2, 0, 128, 500), (4099, 5, 3, 2, 0, 48, 500), (20000, 2, 4, 1, 0, 24, 500),
-    (33333, 4, 8, 2, 0, 12, 500), (3000, 12, 2, 0, 0, 32, 500), (1 << 16, 8, 1, 0, 0, 6, 250),
+    (33333, 4, 8, 2, 0, 12, 500), (3000, 12, 2, 0, 0, 32, 500), (1 << 16, 8, 1, 0, 0, 6, 250), (3000, 12, 40, 2, 0, 12, 500),
     (3000, 1, 80, 1, 0, 24, 500), (2000, 2, 4, 1, 1, 64, 500), (700, 1, 3, 0, 1, 64, 500), (9000, 3, 5, 2, 0, 24, 500),
     # one 4-byte value per process: four receive buffers per store; and a P that rules that path out
     (1004, 2, 1, 1, 0, 64, 500), (1003, 2, 1, 1, 1, 64, 500),
@@ -165,14 +165,16 @@ ALLREDUCE_CASES = [
 
 
 def test_the_sweeps_reach_both_kernels_of_the_deepest_tier(ft):
-    """Plans of the sweep cases: the register kernels for deep trees with f + 1 <= 9 (eight lanes per
-    subtree when a process holds one value, one lane otherwise), LDS tiles otherwise; one case walks the value
-    indices in two passes (more than 64 of them)."""
+    """Plans of the sweep cases: the register kernels for deep trees (eight lanes per subtree when a process holds
+    one value, one lane otherwise; groups of more than 9 with the listed subtrees on the LDS-tile list kernel, as
+    long as a subtree fits its tile), LDS tiles otherwise; one case walks the value indices in two passes (more
+    than 64 of them)."""
     kinds = {(P, f, E, dt): ft.Plan(P, f, E, dt, op).info.deep_kernel for P, f, E, dt, op, _, _ in ALLREDUCE_CASES}
     assert kinds[(3000, 1, 80, 1)] == 1 and kinds[(2000, 2, 4, 1)] == 1 and kinds[(9000, 3, 5, 2)] == 1
     assert kinds[(1000, 8, 1, 0)] == 2 and kinds[(33333, 4, 8, 2)] == 1 and kinds[(1 << 16, 8, 1, 0)] == 2
     assert kinds[(81, 1, 1, 0)] == 2 and kinds[(200, 1, 1, 1)] == 2 and kinds[(5000, 8, 3, 0)] == 1
-    assert kinds[(4099, 5, 3, 2)] == 1 and kinds[(3000, 12, 2, 0)] == 0 and kinds[(64, 2, 8, 1)] == 0
+    assert kinds[(4099, 5, 3, 2)] == 1 and kinds[(3000, 12, 2, 0)] == 1 and kinds[(64, 2, 8, 1)] == 0
+    assert kinds[(3000, 12, 40, 2)] == 0
     assert {f + 1 for (P, f, E, dt), k in kinds.items() if k == 1} >= {2, 3, 4, 5, 9}
     assert {f + 1 for (P, f, E, dt), k in kinds.items() if k == 2} >= {2, 3, 4, 5, 9}
 
