@@ -62,21 +62,29 @@ def needs_build() -> bool:
 
 def build(force: bool = True, jobs: int = 8, verbose: bool = False, incremental: bool = False) -> str:
     """Compile every .hip source and link the shared library.  Returns its path.
-    incremental: keep an object that is newer than its source and every header (the file that carries the
-    source hash is compiled every time)."""
+    incremental: keep an object that is newer than its source and every header it includes (the file that
+    carries the source hash is compiled every time)."""
     if not force and not needs_build():
         return LIB
     os.makedirs(OBJ, exist_ok=True)
     sha = source_hash()
-    newest_header = max(os.path.getmtime(p) for p in _deps())
+    def up_to_date(obj, dep_file):
+        # the object is newer than everything the compiler read for it (its dependency file lists that)
+        if not (os.path.exists(obj) and os.path.exists(dep_file)):
+            return False
+        words = open(dep_file).read().replace("\\\n", " ").split()
+        deps = [w for w in words[1:] if not w.endswith(":")]
+        t = os.path.getmtime(obj)
+        return all(os.path.exists(d) and os.path.getmtime(d) < t for d in deps)
 
     def compile_one(src):
         obj = os.path.join(OBJ, os.path.basename(src)[:-4] + ".o")
+        dep_file = obj[:-2] + ".d"
         carries_hash = os.path.basename(src) == "ftred_api.hip"
-        if (incremental and not carries_hash and os.path.exists(obj)
-                and os.path.getmtime(obj) > max(os.path.getmtime(src), newest_header)):
+        if incremental and not carries_hash and up_to_date(obj, dep_file):
             return obj
-        cmd = [HIPCC] + FLAGS + (["-DFTRED_SOURCE_HASH=\"%s\"" % sha] if carries_hash else []) + ["-c", src, "-o", obj]
+        cmd = ([HIPCC] + FLAGS + (["-DFTRED_SOURCE_HASH=\"%s\"" % sha] if carries_hash else []) +
+               ["-MMD", "-MF", dep_file, "-c", src, "-o", obj])
         r = subprocess.run(cmd, capture_output=True, text=True)
         if r.returncode != 0:
             raise RuntimeError("hipcc failed for %s:\n%s\n%s" % (src, r.stdout, r.stderr))
