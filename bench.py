@@ -76,6 +76,9 @@ def main():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (reference for HBM counters under rocprofv3)")
     ap.add_argument("--cpu-sample", type=int, default=0, help="scenarios timed on the CPU oracle (default: per configuration)")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture the step into one HIP graph and time its replays (the launch-bound small "
+                         "configurations; no per-kernel times, so no rooflines)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: the library runs on ONE GPU (scenarios are independent; nothing is sharded); "
@@ -162,6 +165,34 @@ def main():
         dst.copy_(src)
         torch.cuda.synchronize()
         del dst, src
+
+    if args.graph:
+        # the library only enqueues kernels on the caller's stream (workspace and outputs are the caller's, no
+        # memset, no copy, no synchronisation), so the whole step records into one graph
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step()
+        graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        last = bufs[-1] if is_all else red[-1]
+        assert int((verdict.cpu().numpy() != 0).sum()) == 0, "validation rejected scenarios"
+        attempts = last["attempts"].cpu().numpy().astype(np.int64) if is_all else np.ones(S, dtype=np.int64)
+        process_rounds = int((attempts * rounds * P).sum()) * len(plans)
+        print(json.dumps({
+            "metric": "simulated process-rounds/sec and HBM GB/s (P=16384, f=4 allreduce), 1 GPU",
+            "value": process_rounds * args.steps / (t1 - t0), "unit": "process-rounds/s", "n_gpus": 1,
+            "steps": args.steps, "warmup": args.warmup, "ms_per_step": (t1 - t0) / args.steps * 1e3,
+            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": c["dtype"], "data": "synthetic",
+            "config": {"workload": c["text"] + "; step = one replay of the captured HIP graph of "
+                                   + ("generate failures + " if c["failures"] == "random" else "") + kind + " + validate",
+                       "config_id": args.config, "scenarios": S, "plan_flags": args.lds_kib, "graph": True},
+            "roofline": None, "cpu_baseline": None}))
+        return
 
     # ---- timed region: exactly K steps, HIP events around every kernel launch
     ft.timing_begin(args.steps * 24 * len(plans))
