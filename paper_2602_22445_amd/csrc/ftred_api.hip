@@ -282,6 +282,12 @@ extern "C" int ftred_plan(ftred_plan_t** out, uint32_t P, uint32_t f, uint32_t e
         p->use_wave = (g.L > uint32_t(kWaveH) && !(flags & 0x1000u) && wave_usable(g)) ? 1u : 0u;
         p->list_tile = list_tile ? 1u : 0u;
         info_alt = p->use_wave && ((2u << kWaveH) - 1u) > cap0;
+        // one value per process: the kernel of the deepest tier (eight lanes per subtree) also folds the levels up
+        // to the common ancestor of the sibling subtrees a wavefront walks, so the tiers above start that much
+        // higher.  The lists of failed processes do not travel through those levels: such runs take the second plan.
+        uint32_t lift = 0;
+        if (p->use_wave && g.E == 1u && !(flags & 0x10000u)) lift = unit_lift(g.L - uint32_t(kWaveH));
+        if (lift) info_alt = true;
         {
             uint32_t h0 = hcap0 < g.L ? hcap0 : g.L;
             if (p->use_wave) h0 = uint32_t(kWaveH);
@@ -289,8 +295,8 @@ extern "C" int ftred_plan(ftred_plan_t** out, uint32_t P, uint32_t f, uint32_t e
             t.dlo = g.L - h0; t.dhi = g.L; t.child_in = 0;
             // the levels above, split evenly over as few tiers as the tile allows: small cones are many workgroups
             // of few threads, which is what these latency-bound launches want
-            int d = int(t.dlo) - 1;
-            const uint32_t levels = t.dlo, upper = (levels + hcap1) / (hcap1 + 1u);      // tiers above the deepest one
+            int d = int(t.dlo) - int(lift) - 1;
+            const uint32_t levels = t.dlo - lift, upper = (levels + hcap1) / (hcap1 + 1u);      // tiers above the deepest one
             const uint32_t per = upper ? (levels + upper - 1u) / upper : 0u;             // levels of each but the top one
             while (d >= 0) {
                 if (nt == kMaxTiers) {
@@ -330,6 +336,15 @@ extern "C" int ftred_plan(ftred_plan_t** out, uint32_t P, uint32_t f, uint32_t e
                 td.in_off = p->tiers[t - 1].out_off; td.in_meta_off = p->tiers[t - 1].out_meta_off;
                 td.in_mask_off = p->tiers[t - 1].out_mask_off;
             }
+            if (t == 1 && lift) {
+                // the children of this tier's deepest rows are the rows the kernel of the deepest tier has lifted
+                const uint32_t rows = 1u << (p->tiers[0].dlo - lift);
+                p->lift_off = off;
+                off += align_up(rows * g.RB, 16);
+                p->lift_meta_off = off;
+                off += align_up(rows * 4u, 16);
+                td.in_off = p->lift_off; td.in_meta_off = p->lift_meta_off;
+            }
             if (!td.is_top) {
                 td.out_off = off;
                 off += align_up((1u << td.dlo) * g.RB, 16);
@@ -352,6 +367,7 @@ extern "C" int ftred_plan(ftred_plan_t** out, uint32_t P, uint32_t f, uint32_t e
             }
             if (p->use_unit) {
                 p->ul = make_unit_layout(p->tiers[0].dlo);
+                p->ul.lift = lift;
                 const uint32_t mostu = p->tiers[0].dlo - p->ul.slot_shift;
                 if ((flags >> 13) & 7u) p->ul.group_shift = ((flags >> 13) & 7u) - 1u < mostu ? ((flags >> 13) & 7u) - 1u : mostu;
                 p->wave_gshift = mostu - p->ul.group_shift;
@@ -535,6 +551,19 @@ static hipError_t dispatch_wave(const ftred_plan_t* p, const RunArgs& A, uint32_
     return launch_wave_f64_sum(A, p->wl, grid, st);
 }
 
+// the subtrees of the deepest tier that the plain register kernel leaves out
+static int launch_listed(const ftred_plan_t* plan, const RunArgs& A, uint32_t S, uint32_t extra, uint64_t wgs, hipStream_t st)
+{
+    if (A.wave_general) {           // every listed subtree is on the register kernel's list
+        const uint32_t lds = (1u << plan->wl.slot_shift) * kWaveRows * uint32_t(sizeof(RowInfo));
+        HIP_TRY(dispatch_wave_list(plan, A, uint32_t(wgs), lds, st));
+    } else {                        // every listed subtree is on the LDS-tile kernel's list
+        uint64_t cap = (uint64_t(S) + extra) * (plan->g.f + 3u);
+        HIP_TRY(dispatch_list(plan, A, uint32_t(cap < 4096u ? cap : 4096u), plan->tiers[0].lds_bytes, st));
+    }
+    return FTRED_OK;
+}
+
 // all tiers of one tree phase; `extra` = retry entries that ride along as extra scenarios
 static int launch_tiers(const ftred_plan_t* plan, RunArgs& A, uint32_t S, uint32_t extra, hipStream_t st)
 {
@@ -564,13 +593,16 @@ static int launch_tiers(const ftred_plan_t* plan, RunArgs& A, uint32_t S, uint32
                                        fused_lds_bytes(plan->g, plan->fl, plan->tiers[0].dlo), st));
                 return FTRED_OK;
             }
+            // where the plain kernel goes on above its subtrees (A.lift) it needs the listed subtrees' top rows:
+            // the list kernel runs first
+            if (A.lift) {
+                const int rc = launch_listed(plan, A, S, extra, wgs, st);
+                if (rc != FTRED_OK) return rc;
+            }
             HIP_TRY(dispatch_wave(plan, A, (S + extra) << plan->wave_gshift, st));
-            if (A.wave_general) {           // every listed subtree is on the register kernel's list
-                const uint32_t lds = (1u << plan->wl.slot_shift) * kWaveRows * uint32_t(sizeof(RowInfo));
-                HIP_TRY(dispatch_wave_list(plan, A, uint32_t(wgs), lds, st));
-            } else {                        // every listed subtree is on the LDS-tile kernel's list
-                uint64_t cap = (uint64_t(S) + extra) * (plan->g.f + 3u);
-                HIP_TRY(dispatch_list(plan, A, uint32_t(cap < 4096u ? cap : 4096u), plan->tiers[0].lds_bytes, st));
+            if (!A.lift) {
+                const int rc = launch_listed(plan, A, S, extra, wgs, st);
+                if (rc != FTRED_OK) return rc;
             }
         } else {
             // Tiers above the deepest one: how many cones a workgroup walks through follows the batch, unless the
@@ -684,6 +716,9 @@ static void fill_run_args(RunArgs& A, const ftred_plan_t* p, uint32_t S, const v
     A.vec16 = (g.EB % 16 == 0 && reinterpret_cast<uintptr_t>(payload) % 16 == 0 && A.scen_stride_bytes % 16 == 0) ? 1u : 0u;
     A.ntiers = p->ntiers;
     for (uint32_t t = 0; t < p->ntiers; ++t) A.tiers[t] = p->tiers[t];
+    A.lift = p->use_unit ? p->ul.lift : 0u;
+    A.lift_off = p->lift_off;
+    A.lift_meta_off = p->lift_meta_off;
     A.fix_list = reinterpret_cast<uint32_t*>(A.ws + ws_fix_off(p, S));
     A.fix_count = reinterpret_cast<uint32_t*>(A.ws + ws_ctr_off(p, S) + 12u);
     A.wfix_list = reinterpret_cast<uint32_t*>(A.ws + ws_wfix_off(p, S));

@@ -104,6 +104,8 @@ struct RunArgs {
     const uint32_t* retry_list;  // pairs (scenario, attempt) of attempts whose root had failed, or nullptr
     const uint32_t* retry_count; // entries in retry_list
     uint32_t retry_slots;        // entries run by the tier launches (the rest by the retry kernel)
+    uint32_t lift;               // levels above the deepest tier that its kernel folds as well (eight lanes per subtree)
+    uint32_t lift_off, lift_meta_off;   // where it leaves those rows' messages and words (inside a scenario's scratch)
     uint32_t pad0;
     unsigned char* retry_ws;     // scratch of the retry entries, ws_stride bytes each
     uint32_t* fix_list;          // four words per entry (scenario or S + retry entry, subtree, scenario, root):

@@ -165,8 +165,25 @@ __global__ void __launch_bounds__(256) fixlist_kernel(RunArgs A)
             if ((((rs + 2u) << kWaveH) - 2u) < g.M) --n_full;
             else if ((((rs + 1u) << kWaveH) - 1u) >= g.M) --n_flat;
         }
-        const unsigned long long rows = (unsigned long long)n_full * ((2u << kWaveH) - 1u) +
-                                        (unsigned long long)n_flat * ((1u << kWaveH) - 1u);
+        unsigned long long rows = (unsigned long long)n_full * ((2u << kWaveH) - 1u) +
+                                  (unsigned long long)n_flat * ((1u << kWaveH) - 1u);
+        if (A.lift) {
+            // the levels the plain kernel folds above its subtrees (depths dlo - lift .. dlo - 1, complete rows
+            // all): the same count for every row without a listed member; the kernel counts the others
+            uint32_t lrows[16], nl = 0;
+            for (uint32_t q = 0; q < g.f; ++q) {
+                const uint32_t rank = A.fail_rank[size_t(s) * F + q];
+                if (rank == kNoRank) continue;
+                const uint32_t vr = relabel(rank, root);
+                if (vr == 0) continue;                           // the root is in the last row, if in any
+                const uint32_t jr = fdiv(vr - 1u, g.divW), d = ilog2(jr + 1u);
+                if (d + A.lift < dlo || d >= dlo) continue;
+                bool dup = false;
+                for (uint32_t k = 0; k < nl; ++k) dup = dup || lrows[k] == jr;
+                if (!dup) lrows[nl++] = jr;
+            }
+            rows += (1u << dlo) - (1u << (dlo - A.lift)) - nl;
+        }
         if (rows != 0ull) {
             atomicAdd(&A.msgs[size_t(s) * A.nmsg + 0], rows * g.W * (g.W - 1u));
             atomicAdd(&A.msgs[size_t(s) * A.nmsg + 1], rows * g.W);

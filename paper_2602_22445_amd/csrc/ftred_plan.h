@@ -25,6 +25,7 @@ struct ftred_plan_s {
     uint32_t use_unit;          // ... with eight lanes per subtree (one value per process)
     uint32_t list_tile;         // ... and the subtrees with listed processes on the LDS-tile list kernel (wide groups)
     ftred::UnitLayout ul;
+    uint32_t lift_off, lift_meta_off;   // scratch of the rows the eight-lane kernel folds above its subtrees (ul.lift)
     uint32_t use_fused;         // ... and the levels above it and the root's choice in the same launch
     uint32_t fused_only;        // rows too large for the LDS tiles: no tiers at all, the fused kernel and the register
                                 // walk of the listed subtrees do everything

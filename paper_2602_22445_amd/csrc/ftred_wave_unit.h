@@ -28,6 +28,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "ftred_fused.h"
 #include "ftred_geom.h"
 #include "ftred_kernels.h"
 #include "ftred_wave.h"
@@ -39,7 +40,16 @@ constexpr uint32_t kUnitShift = 3;   // eight lanes per subtree, so eight subtre
 struct UnitLayout {
     uint32_t slot_shift;             // 2^slot_shift sibling subtrees per wavefront pass (<= 3)
     uint32_t group_shift;            // a wavefront walks through 2^group_shift such groups
+    uint32_t lift;                   // levels above the subtrees' top rows that the wavefront folds as well (<= slot_shift)
 };
+
+// levels the kernel can fold above the top rows of its subtrees: the sibling subtrees of a group have one ancestor
+// slot_shift levels up; the tier above must keep at least the root's children
+inline uint32_t unit_lift(uint32_t dlo)
+{
+    const uint32_t sh = dlo < kUnitShift ? dlo : kUnitShift;
+    return dlo == 0 ? 0u : (sh < dlo - 1u ? sh : dlo - 1u);
+}
 
 static_assert(kWaveH == 4, "the lane mapping below is written out for subtrees of height 4");
 
@@ -50,6 +60,7 @@ inline UnitLayout make_unit_layout(uint32_t dlo)
     // two groups per wavefront measured fastest (one: 3 % slower, eight: as slow as one); the plan's flags can
     // ask for another number
     u.group_shift = dlo > u.slot_shift ? 1u : 0u;
+    u.lift = 0;
     return u;
 }
 
@@ -142,6 +153,10 @@ __global__ void __launch_bounds__(kWaveThreads) unit_tier_kernel(RunArgs A, Unit
     // the lane's entry of the failure list, for the subtrees that are not folded here
     const uint32_t F = g.f > 0 ? g.f : 1;
     const uint32_t listed = lane < g.f ? A.fail_rank[size_t(s) * F + lane] : kNoRank;
+    // the whole entry, for the levels above the subtrees: requested here, used after the walk
+    FailRaw fraw;
+    fraw.rank = kNoRank; fraw.round = 0;
+    if (ul.lift != 0u) fraw = failtab_load(g, A.fail_rank, A.fail_round, s);
     UnitRows<T, WP> R;
     request(0, R);
 
@@ -174,8 +189,28 @@ __global__ void __launch_bounds__(kWaveThreads) unit_tier_kernel(RunArgs A, Unit
     // the top rows wait in LDS for one run of stores at the end: a store between the requests would make every
     // wait for rows a wait for that store as well
     extern __shared__ __align__(16) unsigned char unit_lds[];
-    T* tops = reinterpret_cast<T*>(unit_lds);                                  // [groups][slots][W]
+    FailTab& ft = *reinterpret_cast<FailTab*>(unit_lds);                        // used by the levels above only
+    T* tops = reinterpret_cast<T*>(unit_lds + sizeof(FailTab));                // [groups][slots][W]
     uint32_t* folded = reinterpret_cast<uint32_t*>(tops + (size_t(WP) << (ul.group_shift + ul.slot_shift)));
+
+    // The levels above (ul.lift of them): the 2^slot_shift sibling subtrees of a group have a common ancestor
+    // slot_shift levels up; lane 8 gi + r takes row r of group gi's part of the tree in heap order (0 = that
+    // ancestor, children 2r + 1 and 2r + 2, the top rows of the subtrees below the last level).  Its inputs are
+    // requested here, ahead of the walk.
+    const uint32_t nc = 1u << ul.slot_shift;
+    const uint32_t ur = lane & 7u, ugi = lane >> 3;
+    const uint32_t uh = ul.slot_shift - ilog2(ur + 1u);        // height above the top rows (only for ur < nc - 1)
+    const bool lifts = ul.lift != 0u && ugi < ngroups && ur + 1u < nc && uh <= ul.lift;
+    uint32_t uj = 0;
+    T ux[WP];
+#pragma unroll
+    for (int k = 0; k < WP; ++k) ux[k] = T(0);
+    if (lifts) {
+        const uint32_t c0 = group_at(ugi) << ul.slot_shift;   // first subtree of the group
+        const uint32_t pos = (c0 >> uh) + (ur + 1u - (nc >> uh));
+        uj = (1u << (td.dlo - uh)) - 1u + pos;
+        Row::load(x, uj, ux);
+    }
 
     for (uint32_t gi = 0; gi < ngroups; ++gi) {
         UnitRows<T, WP> C = R;
@@ -229,9 +264,84 @@ __global__ void __launch_bounds__(kWaveThreads) unit_tier_kernel(RunArgs A, Unit
         }
     }
     __syncthreads();
-    // the top rows go to the tier above: the subtrees of a group are neighbours, so are their rows there
     const uint32_t ncones = ngroups << ul.slot_shift, smask = (1u << ul.slot_shift) - 1u;
     auto cone_of = [&](uint32_t c) { return (group_at(c >> ul.slot_shift) << ul.slot_shift) + (c & smask); };
+    if (ul.lift != 0u) {
+        // ---- the levels above the subtrees, out of LDS (as in the kernel that folds a whole scenario)
+        uint32_t* lmeta = folded + ncones;                                         // sent / failed bits of the top rows
+        T* up = reinterpret_cast<T*>(lmeta + ncones);                              // [groups][nc - 1 rows][W]; 2 ncones words before it
+        uint32_t* upmeta = reinterpret_cast<uint32_t*>(up + size_t(ngroups) * (nc - 1u) * uint32_t(WP));
+        uint32_t base = 0;
+        if (sv >= A.S || A.attempts) base = root * g.Ratt;     // rounds of the attempt (allreduce)
+        failtab_store(ft, g, failtab_compute(g, fraw, root, base));
+        // the top rows of the subtrees the list kernels folded (an earlier launch) come in from the scratch area
+        for (uint32_t c = lane; c < ncones; c += kWaveThreads) {
+            if (folded[c]) {
+                lmeta[c] = (1u << WP) - 1u;                    // all sent, no failed bit
+            } else {
+                const T* src = reinterpret_cast<const T*>(wsS + td.out_off) + size_t(cone_of(c)) * uint32_t(WP);
+#pragma unroll
+                for (int k = 0; k < WP; ++k) tops[c * uint32_t(WP) + k] = src[k];
+                lmeta[c] = reinterpret_cast<const uint32_t*>(wsS + td.out_meta_off)[cone_of(c)];
+            }
+        }
+        __syncthreads();
+        bool check_fail = false, row_listed = false;
+        if (ft.listed != 0)
+            for (uint32_t qq = 0; qq < ft.n; ++qq) {
+                if (ft.row[qq] == kNoRank) continue;
+                const uint32_t d = ilog2(ft.row[qq] + 1u);
+                if (d + ul.lift >= td.dlo && d < td.dlo) check_fail = true;
+                if (lifts && ft.row[qq] == uj) row_listed = true;
+            }
+        Row::patch(lifts ? uj : kNoRank - 1u, jx, kx, x0, ux);
+        uint32_t uc_cnt = 0, tree_cnt = 0;
+        for (uint32_t h = 1; h <= ul.lift; ++h) {
+            if (lifts && uh == h) {
+                // children: rows 2 ur + 1, 2 ur + 2 of the group's part; below the last level the top rows
+                const uint32_t ci = 2u * ur + 1u;
+                const T* c0p;
+                uint32_t cm0, cm1;
+                if (ci >= nc - 1u) {
+                    const uint32_t at = (ugi << ul.slot_shift) + (ci - (nc - 1u));
+                    c0p = tops + size_t(at) * uint32_t(WP);
+                    cm0 = lmeta[at]; cm1 = lmeta[at + 1u];
+                } else {
+                    c0p = up + (size_t(ugi) * (nc - 1u) + ci) * uint32_t(WP);
+                    cm0 = upmeta[ugi * (nc - 1u) + ci]; cm1 = upmeta[ugi * (nc - 1u) + ci + 1u];
+                }
+                const uint32_t mw = fused_item<T, OP, WP>(ft, check_fail, uj, ux, c0p, c0p + WP, 1u, cm0, cm1, row_listed,
+                                                          uc_cnt, tree_cnt);
+                T* dst = up + (size_t(ugi) * (nc - 1u) + ur) * uint32_t(WP);
+#pragma unroll
+                for (int k = 0; k < WP; ++k) dst[k] = ux[k];
+                upmeta[ugi * (nc - 1u) + ur] = mw;
+                if (h == ul.lift) {
+                    // the rows the tier above takes as its children
+                    const uint32_t pos = uj + 1u - (1u << (td.dlo - h));
+                    T* out = reinterpret_cast<T*>(wsS + A.lift_off) + size_t(pos) * uint32_t(WP);
+#pragma unroll
+                    for (int k = 0; k < WP; ++k) out[k] = ux[k];
+                    reinterpret_cast<uint32_t*>(wsS + A.lift_meta_off)[pos] = mw;
+                }
+            }
+            __syncthreads();
+        }
+        // rows with listed members are counted message by message (the others by their number, beforehand)
+        if (A.msgs && __ballot(uc_cnt | tree_cnt) != 0ull) {
+#pragma unroll
+            for (int d = 32; d >= 1; d >>= 1) {
+                uc_cnt += __shfl_xor(uc_cnt, d);
+                tree_cnt += __shfl_xor(tree_cnt, d);
+            }
+            if (lane == 0) {
+                if (uc_cnt) atomicAdd(&A.msgs[size_t(s) * A.nmsg + 0], (unsigned long long)uc_cnt);
+                if (tree_cnt) atomicAdd(&A.msgs[size_t(s) * A.nmsg + 1], (unsigned long long)tree_cnt);
+            }
+        }
+        return;
+    }
+    // the top rows go to the tier above: the subtrees of a group are neighbours, so are their rows there
     T* dst = reinterpret_cast<T*>(wsS + td.out_off);
     for (uint32_t i = lane; i < ncones * uint32_t(WP); i += kWaveThreads) {
         const uint32_t c = i / uint32_t(WP), k = i - c * uint32_t(WP);
@@ -252,8 +362,14 @@ __global__ void __launch_bounds__(kWaveThreads) unit_tier_kernel(RunArgs A, Unit
 template <class T>
 inline uint32_t unit_lds_bytes(const UnitLayout& ul, uint32_t W)
 {
-    const uint32_t cones = 1u << (ul.group_shift + ul.slot_shift);
-    return cones * W * uint32_t(sizeof(T)) + cones * 4u;
+    const uint32_t cones = 1u << (ul.group_shift + ul.slot_shift), groups = 1u << ul.group_shift;
+    uint32_t n = uint32_t(sizeof(FailTab)) + cones * W * uint32_t(sizeof(T)) + cones * 4u;
+    if (ul.lift) {
+        // words of the top rows, the rows above them and their words
+        const uint32_t rows = groups * ((1u << ul.slot_shift) - 1u);
+        n += cones * 4u + rows * W * uint32_t(sizeof(T)) + rows * 4u;
+    }
+    return n;
 }
 
 #define FTRED_DECLARE_UNIT_LAUNCHER(NAME) \
