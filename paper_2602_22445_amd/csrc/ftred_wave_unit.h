@@ -24,6 +24,15 @@
 // exists, nobody listed as failed, no short last group); the relabelled rank (a
 // root other than process 0) is patched into the row it belongs to.  The others are
 // listed and run by the list kernels.  Output format as there.
+//
+// The wavefront does not stop at the top rows of its subtrees (UnitLayout::lift): the
+// sibling subtrees of a group have one ancestor log2(subtrees per group) levels up,
+// and the rows in between (seven per group of eight) are folded out of LDS by a lane
+// each, with the per-row code of the kernel that folds a whole scenario (fused_item:
+// up-correction in round order, the children's messages with their sent and failed
+// bits).  The top rows of the listed subtrees are then needed here, so on this path the
+// list kernels run in an earlier launch and leave them in the scratch area; one row
+// per group goes on to the tier above, which starts that many levels higher.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
