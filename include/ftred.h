@@ -91,8 +91,10 @@ typedef struct ftred_info {
     uint64_t msgs_tree_ff;       /* failure-free tree messages = P - 1 */
     uint64_t msgs_bcast_tree_ff; /* failure-free broadcast tree messages = P - 1 */
     uint64_t msgs_bcast_corr_ff; /* failure-free broadcast correction messages (= msgs_uc_ff) */
-    uint32_t fused;              /* 1: with deep_kernel 1, one workgroup per scenario folds the deepest tier, the
-                                    levels above it and the root's choice in a single launch */
+    uint32_t fused;              /* 1: with deep_kernel 1, one workgroup folds the deepest tier and the levels above
+                                    it in a single launch: a whole scenario down to the root's choice, or, where the
+                                    top rows of a scenario's subtrees do not fit its LDS tile, the part of the tree
+                                    below one row (the few levels above those rows then take one more launch) */
     uint32_t shape;              /* tree inside a subtree of the root: 2, k, or 1 = binomial (ftred_plan, flags) */
     /* message steps of one failure-free attempt, one port per process: per kind of message (up-correction, tree,
        broadcast down the tree, broadcast correction) the sum over its rounds of the number of messages the

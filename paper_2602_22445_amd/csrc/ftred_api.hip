@@ -287,7 +287,17 @@ extern "C" int ftred_plan(ftred_plan_t** out, uint32_t P, uint32_t f, uint32_t e
         // higher.  The lists of failed processes do not travel through those levels: such runs take the second plan.
         uint32_t lift = 0;
         if (p->use_wave && g.E == 1u && !(flags & 0x10000u)) lift = unit_lift(g.L - uint32_t(kWaveH));
-        if (lift) info_alt = true;
+        // several values per process: one workgroup folds a whole scenario where the top rows of its subtrees fit the
+        // LDS tile, else the part of the tree below one row of depth dp (the smallest dp that fits); the tiers above
+        // then start at depth dp - 1.  `skip` = levels between the deepest tier and the tiers above, either way.
+        uint32_t fused_dp = kNoRank;
+        if (p->use_wave && g.E > 1u && !list_tile && !(flags & 0x10000u) && !((flags >> 13) & 7u)) {
+            const uint32_t dl = g.L - uint32_t(kWaveH);
+            for (uint32_t dp = 0; dp + 1u <= dl && fused_dp == kNoRank; ++dp)
+                if (make_fused_layout(g, dl, dp).ok) fused_dp = dp;
+        }
+        const uint32_t skip = fused_dp != kNoRank && fused_dp != 0u ? (g.L - uint32_t(kWaveH)) - fused_dp : lift;
+        if (skip) info_alt = true;
         {
             uint32_t h0 = hcap0 < g.L ? hcap0 : g.L;
             if (p->use_wave) h0 = uint32_t(kWaveH);
@@ -295,8 +305,8 @@ extern "C" int ftred_plan(ftred_plan_t** out, uint32_t P, uint32_t f, uint32_t e
             t.dlo = g.L - h0; t.dhi = g.L; t.child_in = 0;
             // the levels above, split evenly over as few tiers as the tile allows: small cones are many workgroups
             // of few threads, which is what these latency-bound launches want
-            int d = int(t.dlo) - int(lift) - 1;
-            const uint32_t levels = t.dlo - lift, upper = (levels + hcap1) / (hcap1 + 1u);      // tiers above the deepest one
+            int d = int(t.dlo) - int(skip) - 1;
+            const uint32_t levels = t.dlo - skip, upper = (levels + hcap1) / (hcap1 + 1u);      // tiers above the deepest one
             const uint32_t per = upper ? (levels + upper - 1u) / upper : 0u;             // levels of each but the top one
             while (d >= 0) {
                 if (nt == kMaxTiers) {
@@ -336,9 +346,9 @@ extern "C" int ftred_plan(ftred_plan_t** out, uint32_t P, uint32_t f, uint32_t e
                 td.in_off = p->tiers[t - 1].out_off; td.in_meta_off = p->tiers[t - 1].out_meta_off;
                 td.in_mask_off = p->tiers[t - 1].out_mask_off;
             }
-            if (t == 1 && lift) {
+            if (t == 1 && skip) {
                 // the children of this tier's deepest rows are the rows the kernel of the deepest tier has lifted
-                const uint32_t rows = 1u << (p->tiers[0].dlo - lift);
+                const uint32_t rows = 1u << (p->tiers[0].dlo - skip);
                 p->lift_off = off;
                 off += align_up(rows * g.RB, 16);
                 p->lift_meta_off = off;
@@ -361,8 +371,8 @@ extern "C" int ftred_plan(ftred_plan_t** out, uint32_t P, uint32_t f, uint32_t e
             p->wave_gshift = most - p->wl.group_shift;                // one wavefront per workgroup
             p->wl.stage = (p->wl.group_shift > 0 && wave_can_stage(g, p->wl)) ? 1u : 0u;
             p->use_unit = g.E == 1u ? 1u : 0u;
-            if (!p->use_unit && !p->list_tile && !(flags & 0x10000u) && !((flags >> 13) & 7u)) {
-                p->fl = make_fused_layout(g, p->tiers[0].dlo);
+            if (fused_dp != kNoRank) {
+                p->fl = make_fused_layout(g, p->tiers[0].dlo, fused_dp);
                 p->use_fused = p->fl.ok;
             }
             if (p->use_unit) {
@@ -587,11 +597,12 @@ static int launch_tiers(const ftred_plan_t* plan, RunArgs& A, uint32_t S, uint32
                 // the scenario folds all the others and then everything above them, down to the root's choice
                 const uint32_t lds = (1u << plan->wl.slot_shift) * kWaveRows * uint32_t(sizeof(RowInfo));
                 HIP_TRY(dispatch_wave_list(plan, A, uint32_t(wgs), lds, st));
-                if ((uint64_t(S) + extra) * plan->fl.passes >= (uint64_t(1) << 31))
+                if ((((uint64_t(S) + extra) * plan->fl.passes) << plan->fl.dp) >= (uint64_t(1) << 31))
                     return fail(FTRED_EUNSUPPORTED, "S = %u scenarios need too many workgroups; split the batch", S);
-                HIP_TRY(dispatch_fused(plan, A, (S + extra) * plan->fl.passes,
+                HIP_TRY(dispatch_fused(plan, A, ((S + extra) * plan->fl.passes) << plan->fl.dp,
                                        fused_lds_bytes(plan->g, plan->fl, plan->tiers[0].dlo), st));
-                return FTRED_OK;
+                if (plan->fl.dp == 0u) return FTRED_OK;         // the whole tree and the root's choice
+                continue;                                        // the tiers above the parts' top rows follow
             }
             // where the plain kernel goes on above its subtrees (A.lift) it needs the listed subtrees' top rows:
             // the list kernel runs first

@@ -45,6 +45,8 @@ struct FusedLayout {
     FastDiv div_passes;
     uint32_t one;                    // always 1: trip count of the loop around the walk (see the kernel)
     FastDiv div_ne;
+    uint32_t dp;                     // a workgroup folds the part of the tree below ONE row of depth dp (2^dp parts per
+                                     // scenario; 0: the whole tree and the root's choice)
     uint32_t ok;                     // the plan can use the fused kernel
 };
 
@@ -52,10 +54,12 @@ struct FusedLayout {
 // the narrow groups (three wavefronts per SIMD), two for the wider ones
 inline uint32_t fused_tile_bytes(uint32_t W) { return W <= 5u ? 48u * 1024u : 72u * 1024u; }
 
-inline FusedLayout make_fused_layout(const Geom& g, uint32_t dlo)
+inline FusedLayout make_fused_layout(const Geom& g, uint32_t dlo_tree, uint32_t dp = 0)
 {
     FusedLayout f;
     memset(&f, 0, sizeof(f));
+    f.dp = dp;
+    const uint32_t dlo = dlo_tree - dp;              // levels of a part above its subtrees' top rows
     // the block of value indices: as many as a wavefront has lanes for, fewer where the top rows of a wider block
     // do not fit the tile, but at least a 128-byte line of every process's payload (or all of it)
     for (uint32_t ne = g.E < 64u ? g.E : 64u; ne >= 1u; ne /= 2u) {
@@ -82,7 +86,7 @@ inline FusedLayout make_fused_layout(const Geom& g, uint32_t dlo)
 // "folded here" word per subtree
 inline uint32_t fused_lds_bytes(const Geom& g, const FusedLayout& fl, uint32_t dlo)
 {
-    return uint32_t(sizeof(FailTab)) + ((g.W * fl.ne * g.esz) << dlo) + (8u << dlo);
+    return uint32_t(sizeof(FailTab)) + ((g.W * fl.ne * g.esz) << (dlo - fl.dp)) + (8u << (dlo - fl.dp));
 }
 
 // One (row, value index) item of the levels above the deepest tier.  The row is complete (W members, the root is
@@ -163,23 +167,27 @@ __global__ void __launch_bounds__(kFusedMaxWaves * 64) __attribute__((amdgpu_wav
     extern __shared__ __align__(16) unsigned char smem[];
     const Geom& g = A.g;
     const TierDesc& td = A.tiers[0];
-    const uint32_t dlo = td.dlo;
+    const uint32_t dlo = td.dlo - fl.dp;             // levels of the workgroup's part above its subtrees' top rows
     const uint32_t tid = threadIdx.x, nthr = blockDim.x;
     const uint32_t lane = tid & 63u;
     const uint32_t wid = __builtin_amdgcn_readfirstlane(tid >> 6);     // the same in all lanes: addresses of rows stay scalar
     const uint32_t ncones = 1u << dlo;
     const uint32_t ne = fl.ne, REl = g.W * ne;       // a row of the tile: W members x ne value indices of the block
-    const uint32_t top0 = ncones - 1u;
+    const uint32_t top0 = (1u << td.dlo) - 1u;       // first row of the subtrees' top level in the whole tree
     FailTab& ft = *reinterpret_cast<FailTab*>(smem);
     T* tile = reinterpret_cast<T*>(smem + sizeof(FailTab));
     uint32_t* lmeta = reinterpret_cast<uint32_t*>(smem + sizeof(FailTab) + (size_t(REl) * g.esz << dlo));
     uint32_t* folded = lmeta + ncones;
 
     // ---- which scenario, which block of value indices, which root
-    uint32_t sv = blockIdx.x, pass = 0;              // scenario, or S + retry entry
+    // the workgroup's part of the tree: the rows below row `part` of depth fl.dp (the whole tree if fl.dp == 0)
+    const uint32_t part = blockIdx.x & ((1u << fl.dp) - 1u);
+    const uint32_t cone0 = part << dlo;              // its first subtree
+    uint32_t sv = blockIdx.x >> fl.dp, pass = 0;     // scenario, or S + retry entry
     if (fl.passes > 1u) {
-        sv = fdiv(blockIdx.x, fl.div_passes);
-        pass = blockIdx.x - sv * fl.passes;
+        const uint32_t b = sv;
+        sv = fdiv(b, fl.div_passes);
+        pass = b - sv * fl.passes;
     }
     uint32_t s = sv, root = 0, base = 0;
     bool discard = false;
@@ -214,7 +222,7 @@ __global__ void __launch_bounds__(kFusedMaxWaves * 64) __attribute__((amdgpu_wav
     const uint32_t e = lane - slot * ne;
     const bool active = lane < fl.nact;
     const uint32_t listed = lane < g.f ? A.fail_rank[size_t(s) * F + lane] : kNoRank;
-    const uint32_t special = subtree_of_row(special_row_of_lane(g, dlo, listed, root, lane), dlo);
+    const uint32_t special = subtree_of_row(special_row_of_lane(g, td.dlo, listed, root, lane), td.dlo) - cone0;
     const unsigned char* bk[WP];
 #pragma unroll
     for (int k = 0; k < WP; ++k) bk[k] = pay + size_t(k) * g.EB;
@@ -235,10 +243,10 @@ __global__ void __launch_bounds__(kFusedMaxWaves * 64) __attribute__((amdgpu_wav
         for (uint32_t gi = 0; gi < (1u << fl.group_shift); ++gi) {
             // the groups of a wavefront lie a stride of wavefronts apart: side by side run wavefronts that read
             // rows side by side
-            const uint32_t cone_w = (wid + (gi << fl.wshift)) << fl.slot_shift;
-            if (top0 + cone_w >= g.M) break;
+            const uint32_t cone_w = (wid + (gi << fl.wshift)) << fl.slot_shift;      // within the part
+            if (top0 + cone0 + cone_w >= g.M) break;
             const uint32_t cone = cone_w + (active ? slot : 0u);
-            const uint32_t rs = top0 + cone;                       // top row of the lane's subtree
+            const uint32_t rs = top0 + cone0 + cone;               // top row of the lane's subtree
             const bool exists = active && rs < g.M;
             const uint32_t last_leaf = ((rs + 2u) << kWaveH) - 2u;
             const bool bottom = last_leaf < g.M;                   // complete with the bottom level (a ragged one is listed)
@@ -310,10 +318,10 @@ __global__ void __launch_bounds__(kFusedMaxWaves * 64) __attribute__((amdgpu_wav
             const uint32_t r = fdiv(valid ? q : 0u, fl.div_ne);
             const uint32_t el = (valid ? q : 0u) - r * ne;
             const uint32_t ec = pass * ne + el < g.E ? pass * ne + el : 0u;     // past the last value index: any valid address
-            const uint32_t t = ncones - 1u - r;           // 2^l <= t < 2^(l+1) on level l
+            const uint32_t t = ncones - 1u - r;           // 2^l <= t < 2^(l+1) on level l of the part
             const uint32_t l = ilog2(t);
-            const uint32_t p = (2u << l) - 1u - t;        // position on its level
-            const uint32_t j = (1u << l) - 1u + p;
+            const uint32_t p = (2u << l) - 1u - t;        // position on its level of the part
+            const uint32_t j = (1u << (l + fl.dp)) - 1u + (part << l) + p;
             ij[i] = j; ie[i] = el; ip[i] = p;
             il[i] = (valid && pass * ne + el < g.E) ? l : kNoRank;
             const T* src = reinterpret_cast<const T*>(pay) + (size_t(1u + j * g.W)) * g.E + ec;
@@ -329,13 +337,13 @@ __global__ void __launch_bounds__(kFusedMaxWaves * 64) __attribute__((amdgpu_wav
 
         // ---- the subtrees folded by the list kernel (an earlier launch): their top rows and words from the scratch area
         for (uint32_t c = wid; c < ncones; c += (nthr >> 6)) {
-            if (top0 + c < g.M && !folded[c]) {
-                const T* src = reinterpret_cast<const T*>(wsS + td.out_off + size_t(c) * g.RB);
+            if (top0 + cone0 + c < g.M && !folded[c]) {
+                const T* src = reinterpret_cast<const T*>(wsS + td.out_off + size_t(cone0 + c) * g.RB);
                 for (uint32_t i = lane; i < REl; i += 64u) {
                     const uint32_t k = fdiv(i, fl.div_ne), el = i - k * ne;
                     if (pass * ne + el < g.E) tile[size_t(c) * REl + i] = src[size_t(k) * g.E + pass * ne + el];
                 }
-                if (lane == 0) lmeta[c] = reinterpret_cast<const uint32_t*>(wsS + td.out_meta_off)[c];
+                if (lane == 0) lmeta[c] = reinterpret_cast<const uint32_t*>(wsS + td.out_meta_off)[cone0 + c];
             }
         }
         __syncthreads();
@@ -344,7 +352,7 @@ __global__ void __launch_bounds__(kFusedMaxWaves * 64) __attribute__((amdgpu_wav
         bool check_fail = false;
         if (ft.listed != 0)
             for (uint32_t q = 0; q < ft.n; ++q)
-                if (ft.row[q] != kNoRank && ilog2(ft.row[q] + 1u) < dlo) check_fail = true;
+                if (ft.row[q] != kNoRank && ilog2(ft.row[q] + 1u) < td.dlo) check_fail = true;
         uint32_t im[kFusedItems];
         for (int l = int(dlo) - 1; l >= 0; --l) {
 #pragma unroll
@@ -367,7 +375,15 @@ __global__ void __launch_bounds__(kFusedMaxWaves * 64) __attribute__((amdgpu_wav
             }
             __syncthreads();
         }
-        if (!discard) {
+        if (fl.dp != 0u) {
+            // ---- the part's top row goes on to the tiers above: messages [member][value index], sent and failed bits
+            T* dst = reinterpret_cast<T*>(wsS + A.lift_off) + size_t(part) * g.W * g.E;
+            for (uint32_t i = tid; i < REl; i += nthr) {
+                const uint32_t k = fdiv(i, fl.div_ne), el = i - k * ne;
+                if (pass * ne + el < g.E) dst[size_t(k) * g.E + pass * ne + el] = tile[i];
+            }
+            if (tid == 0 && pass == 0) reinterpret_cast<uint32_t*>(wsS + A.lift_meta_off)[part] = lmeta[0];
+        } else if (!discard) {
         // ---- Algorithm "reduce at the root": lowest-numbered child whose message is present and reports no failure;
         // the root adds its own value iff that subtree holds no member of the root's group (children a .. f+1)
         const uint32_t cm = lmeta[0];
@@ -406,7 +422,7 @@ __global__ void __launch_bounds__(kFusedMaxWaves * 64) __attribute__((amdgpu_wav
             if (tree_cnt) atomicAdd(&A.msgs[size_t(s) * A.nmsg + 1], (unsigned long long)tree_cnt);
         }
     }
-    if (!discard && tid == 0 && pass == 0) A.status[s] = st;
+    if (fl.dp == 0u && !discard && tid == 0 && pass == 0) A.status[s] = st;
 }
 
 #define FTRED_DECLARE_FUSED_LAUNCHER(NAME) \
