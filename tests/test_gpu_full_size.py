@@ -193,6 +193,28 @@ def test_allreduce_p2e20_f8_1024_scenarios_against_the_oracle(p2e20, oracle, w, 
     assert done == per
 
 
+def test_allreduce_p2e20_f4_deep_tree_in_parts(ft, oracle, w):
+    """A tree too deep for one workgroup per scenario (P = 2^20, f = 4, 8 x fp64: 8192 subtrees of the deepest tier):
+    the fused kernel folds it in parts below the rows of one depth, one LDS-tile launch takes it from there; every
+    scenario against the oracle, failures aimed at the seams (tops of parts, the rows just above them, the last
+    rows)."""
+    from _cmp import compare_allreduce
+    P, f, E, S, seed = 1 << 20, 4, 8, 6, 77
+    plan = ft.Plan(P, f, E, ft.F64, ft.SUM)
+    assert plan.info.deep_kernel == 1 and plan.info.fused == 1 and plan.info.tiers == 2
+    Ratt = plan.info.rounds_attempt
+    fr, fo = w.random_failure_sets(seed, S, P, f, inop_permille=500, rounds_per_attempt=Ratt, protected=f + 1)
+    fr[0], fo[0] = w.NO_RANK, 0
+    fr[1], fo[1] = w.NO_RANK, 0
+    fr[1, 0], fo[1, 0] = 0, 0                        # a second attempt
+    W = f + 1
+    # rows 63 .. 126 are the 64 rows of depth 6 (tops of the parts at this size), 31 .. 62 the level above
+    fr[2], fo[2] = [1 + 63 * W, 1 + 64 * W + 1, 1 + 126 * W + 4, 1 + 31 * W + 2], [0, 3, 0, 9]
+    fr[3], fo[3] = [P - 1, P - 2, 1 + 62 * W, 1 + 127 * W + 3], [0, 5, 20, 0]
+    x = w.payload_normal(seed, S, P, E, threads=8)
+    compare_allreduce(ft, oracle, plan, x, fr, fo)
+
+
 def test_allreduce_p2e20_f1_u32_deep_binary_groups(ft, oracle, w):
     """A tree of 19 levels with groups of two (P = 2^20, f = 1, one uint32 per process): the narrowest rows
     (8 bytes) through the eight-lanes-per-subtree kernel and two LDS-tile tiers of seven levels each; every
