@@ -917,11 +917,22 @@ static int run_allreduce_impl(const char* who, const ftred_plan_t* plan, uint32_
                  (uint64_t(g.P) * g.EB) % 16 == 0) ? 1u : 0u;
     if (uint64_t(S) * B.nchunks >= (uint64_t(1) << 31))
         return fail(FTRED_EUNSUPPORTED, "ftred_run_allreduce: S = %u scenarios need too many workgroups; split the batch", S);
+    // the kernel's other instantiation: values that are no multiple of 16 bytes get 16-byte stores where every
+    // scenario's buffers start on one, and chunks of many groups (few bytes per process) take their holders and
+    // counts from the chunk's place in the tree where no listed process touches them
+    B.any16 = (!B.small16 && g.EB % 16 != 0 && g.EB <= 4096u && per_process_out &&
+               reinterpret_cast<uintptr_t>(per_process_out) % 16 == 0 && (uint64_t(g.P) * g.EB) % 16 == 0) ? 1u : 0u;
+    const bool alt = B.any16 || plan->bc_chunk / g.W >= 256u;
     const uint32_t lds = bcast_lds_bytes(B);
     {
         TimedLaunch tl(FTRED_PH_BCAST, st);
-        if (g.shape == kShapeBinary) hipLaunchKernelGGL(bcast_kernel<true>, dim3(S * B.nchunks), dim3(kThreads), lds, st, B);
-        else hipLaunchKernelGGL(bcast_kernel<false>, dim3(S * B.nchunks), dim3(kThreads), lds, st, B);
+        if (g.shape == kShapeBinary) {
+            if (alt) hipLaunchKernelGGL((bcast_kernel<true, true>), dim3(S * B.nchunks), dim3(kThreads), lds, st, B);
+            else hipLaunchKernelGGL((bcast_kernel<true, false>), dim3(S * B.nchunks), dim3(kThreads), lds, st, B);
+        } else {
+            if (alt) hipLaunchKernelGGL((bcast_kernel<false, true>), dim3(S * B.nchunks), dim3(kThreads), lds, st, B);
+            else hipLaunchKernelGGL((bcast_kernel<false, false>), dim3(S * B.nchunks), dim3(kThreads), lds, st, B);
+        }
     }
     HIP_TRY(hipGetLastError());
     return FTRED_OK;

@@ -346,6 +346,7 @@ struct BcastArgs {
     FastDiv div_nchunks;
     uint32_t vec16;
     uint32_t small16;              // one value of 4 or 8 bytes per process: several receive buffers per store
+    uint32_t any16;                // ALT only: values that are no multiple of 16 bytes, 16 bytes per store
 };
 
 struct BcastFail {
@@ -359,11 +360,17 @@ struct BcastFail {
 
 inline uint32_t bcast_lds_bytes(const BcastArgs& B)
 {
-    return uint32_t(sizeof(BcastFail)) + (B.chunk / 32u + 2u) * 4u;
+    // the failure table, the holder bits of the chunk, and (16-byte stores of odd-sized values) a copy of the result
+    return uint32_t(sizeof(BcastFail)) + (B.chunk / 32u + 2u) * 4u + (B.any16 ? B.g.EB : 0u);
 }
 
-// BIN: the default tree shape (binary heap inside a subtree), with its index arithmetic known at compile time
-template <bool BIN>
+// BIN: the default tree shape (binary heap inside a subtree), with its index arithmetic known at compile time.
+// ALT: the instantiation for small or odd-sized values (not the benchmark's: kept apart, since a branch more in
+// this kernel's prologue costs the headline shape several per cent).  It works out the holders and counts of a
+// chunk that no listed process touches from the chunk's place in the tree instead of a thread per group (with
+// few bytes per process a chunk has many groups, and the kernel is bound by them, not by its stores), and writes
+// values that are no multiple of 16 bytes with 16-byte stores (B.any16).
+template <bool BIN, bool ALT>
 __global__ void __launch_bounds__(kThreads) bcast_kernel(BcastArgs B)
 {
     extern __shared__ __align__(16) unsigned char smem[];
@@ -395,6 +402,13 @@ __global__ void __launch_bounds__(kThreads) bcast_kernel(BcastArgs B)
     }
     uint32_t jx = kNoRank;                    // the row of the process numbered `root`, which stands at position 0
     for (uint32_t w = tid; w < nw + 1u; w += kThreads) bits[w] = 0u;
+    if constexpr (ALT) {
+        if (B.any16) {                        // the result's words, at hand for stores that pick them one by one
+            uint32_t* resl = bits + (B.chunk / 32u + 2u);
+            const uint32_t* resg = reinterpret_cast<const uint32_t*>(B.result + size_t(s) * g.EB);
+            for (uint32_t w = tid; w < g.EB / 4u; w += kThreads) resl[w] = resg[w];
+        }
+    }
     if (run) {
         root = B.attempts[s] - 1u;
         t0 = root * g.Ratt + g.Rred;          // broadcast round tau is global round t0 + tau
@@ -455,7 +469,36 @@ __global__ void __launch_bounds__(kThreads) bcast_kernel(BcastArgs B)
     }
     __syncthreads();
 
-    if (run) {
+    if (ALT && BIN && run && bf.touched == 0u && root == 0) {
+        // ---- nobody listed in these rows or above them: every process of the chunk receives, forwards and takes
+        // part in every correction round; holders and message counts follow from the chunk's place in the tree
+        for (uint32_t w = tid; w < nw; w += kThreads) {
+            const uint32_t left = c1 - c0 - 32u * w;
+            bits[w] = left >= 32u ? 0xFFFFFFFFu : (1u << left) - 1u;
+        }
+        if (tid == 0 && B.msgs) {
+            // the rows whose first member lies in the chunk count their messages: ja <= j < jb
+            const uint32_t ja = c0 <= 1u ? 0u : fdiv(c0 - 1u + g.W - 1u, g.divW);
+            uint32_t jb = fdiv(c1 - 1u + g.W - 1u, g.divW);
+            if (jb > g.M) jb = g.M;
+            unsigned long long tree = 0, corr = 0;
+            if (ja < jb) {
+                // tree: a message to every member of the children rows 2 ja + 1 .. 2 jb that exist (the last row
+                // of the tree may be short)
+                const uint32_t lo = 2u * ja + 1u, hi = 2u * jb;
+                if (lo < g.M - 1u) tree += (unsigned long long)g.W * ((hi < g.M - 2u ? hi : g.M - 2u) - lo + 1u);
+                if (lo <= g.M - 1u && g.M - 1u <= hi) tree += g.nlast;
+                // correction: every member of a group sends in each of min(f, group size - 1) rounds
+                const uint32_t with_last = jb == g.M ? 1u : 0u;
+                const uint32_t gl = group_size(g, g.M - 1u);
+                corr = (unsigned long long)(jb - ja - with_last) * g.W * (g.f < g.W - 1u ? g.f : g.W - 1u) +
+                       (unsigned long long)with_last * gl * (g.f < gl - 1u ? g.f : gl - 1u);
+            }
+            if (c0 == 0) tree += g.W;             // the root sends to its f+1 children
+            if (tree) atomicAdd(&B.msgs[size_t(s) * 4u + 2u], tree);
+            if (corr) atomicAdd(&B.msgs[size_t(s) * 4u + 3u], corr);
+        }
+    } else if (run) {
         // ---- who holds the value: one thread per up-correction group
         const bool touched = bf.touched != 0u;         // else every process of these rows receives and forwards
         const uint32_t ntask = nrows + (jx != kNoRank ? 1u : 0u);
@@ -586,6 +629,23 @@ __global__ void __launch_bounds__(kThreads) bcast_kernel(BcastArgs B)
                     val.z = (m & 4u) ? r0w : 0u; val.w = (m & 8u) ? r0w : 0u;
                 }
                 __builtin_nontemporal_store(val, reinterpret_cast<vec16_t*>(dst + size_t(i) * 16u));
+            }
+        } else if (ALT && B.any16) {
+            // 16 bytes = four words, each of some process's receive buffer: the store walks along with (process,
+            // word of its value); P * EB is a multiple of 16, so the chunk ends on a store
+            const uint32_t* resw = bits + (B.chunk / 32u + 2u);       // the kernel's copy of the result in LDS
+            const uint32_t wpv = g.EB / 4u;                          // words per value
+            for (uint32_t o = tid * 16u; o < bytes; o += kThreads * 16u) {
+                uint32_t rr = fdiv(o, g.divEB);
+                uint32_t wi = (o - rr * g.EB) / 4u;
+                uint32_t v[4];
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    v[k] = ((bits[rr >> 5] >> (rr & 31u)) & 1u) ? resw[wi] : 0u;
+                    if (++wi == wpv) { wi = 0; ++rr; }
+                }
+                const vec16_t val = {v[0], v[1], v[2], v[3]};
+                __builtin_nontemporal_store(val, reinterpret_cast<vec16_t*>(dst + o));
             }
         } else if (B.vec16) {
             for (uint32_t o = tid * 16u; o < bytes; o += kThreads * 16u) {
