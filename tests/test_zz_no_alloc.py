@@ -76,6 +76,22 @@ def test_noalloc_equals_run_allreduce_twice_in_a_row(ft, w):
     _same(got3, want1)
 
 
+def test_noalloc_on_the_other_deep_paths(ft, w):
+    """One value per process (eight lanes per subtree, three more levels folded by the same wavefront) and a tree
+    that one workgroup folds in parts: the same array, one call after the other."""
+    plan1, x1, fr1, fo1 = _case(ft, w, 65536, 8, 1, ft.I64, 8, 24)
+    plan2, x2, fr2, fo2 = _case(ft, w, 40000, 4, 8, ft.F64, 3, 25)
+    assert plan1.info.deep_kernel == 2 and plan2.info.fused == 1 and plan2.info.tiers == 2
+    want1 = ft.run_allreduce(plan1, 8, x1, fr1, fo1)
+    want2 = ft.run_allreduce(plan2, 3, x2, fr2, fo2)
+    torch.cuda.synchronize()
+    got1 = ft.run_allreduce_noalloc(plan1, 8, x1, fr1, fo1, _buffers(ft, plan1, 8))
+    got2 = ft.run_allreduce_noalloc(plan2, 3, x2, fr2, fo2, _buffers(ft, plan2, 3))
+    torch.cuda.synchronize()
+    _same(got1, want1)
+    _same(got2, want2)
+
+
 def test_noalloc_rejects_what_does_not_fit(ft, w):
     plan, x, fr, fo = _case(ft, w, 16384, 4, 8, ft.F64, 4, 23)
     S = 4096
