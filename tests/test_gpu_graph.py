@@ -29,7 +29,8 @@ def w():
 KEYS = ("result", "status", "attempts", "msgs", "has_bitmap", "per_process_out")
 
 
-@pytest.mark.parametrize("P,f,E,dtype,S", [(64, 2, 8, 0, 512), (16384, 4, 8, 2, 96), (1 << 16, 8, 1, 0, 8), (3000, 12, 2, 0, 32)])
+@pytest.mark.parametrize("P,f,E,dtype,S", [(64, 2, 8, 0, 512), (16384, 4, 8, 2, 96), (1 << 16, 8, 1, 0, 8), (3000, 12, 2, 0, 32),
+                                           (40000, 4, 8, 2, 12)])
 def test_replays_equal_eager_runs(ft, oracle, w, P, f, E, dtype, S):
     plan = ft.Plan(P, f, E, dtype, ft.SUM)
     Ratt = plan.info.rounds_attempt
