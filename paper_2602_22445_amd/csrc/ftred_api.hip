@@ -376,7 +376,7 @@ extern "C" int ftred_plan(ftred_plan_t** out, uint32_t P, uint32_t f, uint32_t e
                 p->use_fused = p->fl.ok;
             }
             if (p->use_unit) {
-                p->ul = make_unit_layout(p->tiers[0].dlo);
+                p->ul = make_unit_layout(p->tiers[0].dlo, g.W);
                 p->ul.lift = lift;
                 const uint32_t mostu = p->tiers[0].dlo - p->ul.slot_shift;
                 if ((flags >> 13) & 7u) p->ul.group_shift = ((flags >> 13) & 7u) - 1u < mostu ? ((flags >> 13) & 7u) - 1u : mostu;
