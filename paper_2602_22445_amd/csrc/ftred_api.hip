@@ -336,7 +336,10 @@ extern "C" int ftred_plan(ftred_plan_t** out, uint32_t P, uint32_t f, uint32_t e
             // A small cone is a matter of latency and of instructions every wavefront repeats: no more wavefronts
             // than its widest level has work for, but enough threads for the prefetch registers to hold its rows.
             td.threads = uint32_t(kThreads);
-            if (t > 0) {
+            // (The deepest tier's tile kernel: where the register walks run that tier it serves only the list of
+            // subtrees with listed processes, an entry at a time; small entries then want small workgroups, many
+            // of them at once.)
+            if (t > 0 || p->use_wave) {
                 const uint32_t own_bytes = ((2u << h) - 1u) * g.RB, widest = (1u << h) * g.E;
                 uint32_t thr = 64;
                 while (thr < uint32_t(kThreads) && (thr * kStagePerThread < own_bytes || thr < widest)) thr *= 2u;
@@ -569,7 +572,8 @@ static int launch_listed(const ftred_plan_t* plan, const RunArgs& A, uint32_t S,
         HIP_TRY(dispatch_wave_list(plan, A, uint32_t(wgs), lds, st));
     } else {                        // every listed subtree is on the LDS-tile kernel's list
         uint64_t cap = (uint64_t(S) + extra) * (plan->g.f + 3u);
-        HIP_TRY(dispatch_list(plan, A, uint32_t(cap < 4096u ? cap : 4096u), plan->tiers[0].lds_bytes, st));
+        const uint64_t most = 4096u * (uint64_t(kThreads) / plan->tiers[0].threads);     // workgroups that walk the list
+        HIP_TRY(dispatch_list(plan, A, uint32_t(cap < most ? cap : most), plan->tiers[0].lds_bytes, st));
     }
     return FTRED_OK;
 }

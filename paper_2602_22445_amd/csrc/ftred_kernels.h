@@ -808,7 +808,7 @@ __global__ void __launch_bounds__(kThreads) tier_list_kernel(RunArgs A)
     const uint32_t n = *A.fix_count;
     const uint32_t h = td.dhi - td.dlo;
     const uint32_t top0 = (1u << td.dlo) - 1u;
-    const bool reg_patches = g.EB <= uint32_t(kThreads * sizeof(V));
+    const bool reg_patches = g.EB <= uint32_t(blockDim.x * sizeof(V));
     const uint32_t tid = threadIdx.x;
     const uint32_t stride = gridDim.x;
     if (blockIdx.x >= n) return;
@@ -884,8 +884,9 @@ FTRED_DECLARE_LAUNCHERS(f64_sum)
     template <int WP>                                                                              \
     static hipError_t list_wp_##NAME(const RunArgs& A, uint32_t grid, uint32_t lds, hipStream_t st) \
     {                                                                                              \
-        if (A.vec16) hipLaunchKernelGGL((tier_list_kernel<T, OP, WP, true>), dim3(grid), dim3(kThreads), lds, st, A); \
-        else hipLaunchKernelGGL((tier_list_kernel<T, OP, WP, false>), dim3(grid), dim3(kThreads), lds, st, A);        \
+        const uint32_t thr = A.tiers[0].threads;                                                   \
+        if (A.vec16) hipLaunchKernelGGL((tier_list_kernel<T, OP, WP, true>), dim3(grid), dim3(thr), lds, st, A); \
+        else hipLaunchKernelGGL((tier_list_kernel<T, OP, WP, false>), dim3(grid), dim3(thr), lds, st, A);        \
         return hipGetLastError();                                                                  \
     }                                                                                              \
     hipError_t launch_list_##NAME(const RunArgs& A, uint32_t grid, uint32_t lds, hipStream_t st)    \
